@@ -1,0 +1,165 @@
+/*
+ * libgnnagg - message-passing Aggregation by feature slices on one AMD MI355X
+ * (CDNA4 / gfx950).
+ *
+ * The library computes the Aggregation phase of GNN inference as the paper
+ * states it in Algorithm 1 (Section II-B): the feature vector of every vertex
+ * is split into chunks along its last dimension, each chunk is aggregated over
+ * the in-neighbours of every vertex, and the chunk results sit side by side in
+ * the output.  Aggregation is element-wise over features (Section I), so the
+ * chunked result equals the unchunked one.
+ *
+ * Conventions common to all calls
+ *  - Messages flow src -> dst.  The CSR is indexed by DESTINATION: row i lists,
+ *    in colidx[rowptr[i] .. rowptr[i+1]), the SOURCE vertices of the edges that
+ *    end in i (Section II-C: the input is the COO edge set and the vertex
+ *    feature matrix).
+ *  - Unless a parameter says "host", every pointer is a DEVICE pointer owned by
+ *    the caller.  The library allocates no device memory; scratch is passed in
+ *    as `workspace`.  Inputs and outputs must not overlap.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    gnnagg_aggregate and gnnagg_gat_attention only enqueue work on it and
+ *    return; gnnagg_build_csr and gnnagg_plan_rows also wait for it, because
+ *    they hand results back to the host.
+ *  - Every call returns a gnnagg_status.  Invalid arguments are detected on the
+ *    host before anything is launched and leave all outputs untouched.  Index
+ *    values outside [0, N) inside colidx are a contract violation that the
+ *    aggregation calls do not check; gnnagg_build_csr does check src/dst.
+ *  - Workspace protocol: call once with workspace == NULL to receive the
+ *    required size in *workspace_bytes (nothing is launched); then call with a
+ *    buffer of at least that size, 256-byte aligned, and *workspace_bytes set
+ *    to its size.
+ */
+#ifndef GNNAGG_H
+#define GNNAGG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GNNAGG_API __attribute__((visibility("default")))
+
+typedef enum {
+  GNNAGG_OK = 0,
+  GNNAGG_EINVAL = -1,       /* an argument is out of range or inconsistent */
+  GNNAGG_ENULL = -2,        /* a required pointer is NULL */
+  GNNAGG_EUNSUPPORTED = -3, /* valid request this build does not implement */
+  GNNAGG_EWORKSPACE = -4,   /* workspace missing, too small or misaligned */
+  GNNAGG_EDEVICE = -5       /* a HIP call failed */
+} gnnagg_status;
+
+typedef enum {
+  GNNAGG_SUM = 0,  /* out[i,f] = sum_j X[j,f] */
+  GNNAGG_WSUM = 1, /* out[i,f] = sum_j edge_w[e] * X[j,f]   (GCN with the weights of NORM_SYM) */
+  GNNAGG_MEAN = 2, /* out[i,f] = (sum_j X[j,f]) / deg(i), 0 for an empty row (GraphSAGE mean) */
+  GNNAGG_MAX = 3   /* out[i,f] = max_j X[j,f], +0.0 for an empty row; -0 orders below +0 */
+} gnnagg_op;
+
+typedef enum { GNNAGG_F32 = 0, GNNAGG_BF16 = 1 } gnnagg_dtype;
+
+enum {
+  GNNAGG_SELF_LOOPS = 1, /* append the edges i -> i, i = 0..N-1, after the E input edges */
+  GNNAGG_NORM_SYM = 2    /* edge_w = 1/sqrt(d_i d_j), d = row length after self-loops */
+};
+
+/* Number of degree classes in a row plan (class 0: empty rows; class c >= 1:
+ * rows with 2^(c-1) <= degree < 2^c). */
+#define GNNAGG_PLAN_CLASSES 33
+
+GNNAGG_API int gnnagg_version(void);
+GNNAGG_API const char* gnnagg_strerror(int status);
+
+/*
+ * COO -> destination-indexed CSR (Section II-C: forward takes the COO edge
+ * set; Section III discusses the cost of converting it to CSR).
+ *
+ *   src, dst   [E] int32, edge k is src[k] -> dst[k]; values must lie in [0,N)
+ *   flags      GNNAGG_SELF_LOOPS | GNNAGG_NORM_SYM
+ *   rowptr     [N+1] int64 out
+ *   colidx     [nnz] int32 out, nnz = E (+ N with SELF_LOOPS).  Inside a row the
+ *              entries are ordered by (source ascending, input position
+ *              ascending); duplicate edges are kept.
+ *   edge_w     [nnz] fp32 out, may be NULL.  With NORM_SYM: the fp64 value
+ *              1/sqrt(d_i*d_j) rounded once to fp32; otherwise 1.0f.
+ *   perm       [nnz] int64 out, may be NULL: input position of the edge held in
+ *              each CSR slot (self-loop i has position E+i).
+ *
+ * The result is unique, so it can be compared bit for bit.  Returns
+ * GNNAGG_EINVAL (outputs undefined) if a src/dst value is out of range,
+ * GNNAGG_EUNSUPPORTED if nnz >= 2^32 or N >= 2^31.  Waits for `stream`.
+ */
+GNNAGG_API int gnnagg_build_csr(int64_t N, int64_t E, const int32_t* src, const int32_t* dst, uint32_t flags,
+                     int64_t* rowptr, int32_t* colidx, float* edge_w, int64_t* perm, void* workspace,
+                     size_t* workspace_bytes, void* stream);
+
+/*
+ * Degree-sorted row schedule for the aggregation kernels (per graph, reusable
+ * by every later aggregation call on the same CSR).  Power-law degree
+ * distributions (Section III, Table II: average degree 4.5 to 597) need rows of
+ * similar length to share a wavefront and hub rows to get a whole workgroup.
+ *
+ *   row_order  [N] int32 out: row ids by degree descending, ties by row id
+ *   class_off  HOST pointer, [GNNAGG_PLAN_CLASSES+1] int64 out: rows of degree
+ *              class c occupy row_order[class_off[32-c] .. class_off[33-c])
+ *
+ * Waits for `stream`.
+ */
+GNNAGG_API int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_order, int64_t* class_off,
+                     void* workspace, size_t* workspace_bytes, void* stream);
+
+/*
+ * Aggregation on each decomposition layer (Algorithm 1, the Message /
+ * Aggregate / Concat steps).
+ *
+ *   X        [N,F] row-major, x_dtype GNNAGG_F32 or GNNAGG_BF16 (bf16 is widened
+ *            exactly; all accumulation is fp32)
+ *   out      [N,F] row-major, out_dtype must be GNNAGG_F32
+ *   edge_w   [nnz] fp32, required for GNNAGG_WSUM, ignored otherwise
+ *   f_chunk  chunk WIDTH (the paper's "dimension of each decomposition layer",
+ *            Section III): chunk c covers columns [c*f_chunk, min(F,(c+1)*f_chunk)).
+ *            Chunks run one after another over all rows (the chunk-outer,
+ *            vertex-inner order of Algorithm 1), each written in place into its
+ *            columns of `out` (no separate concat).  0 or >= F: one chunk.
+ *   row_order, class_off   a plan from gnnagg_plan_rows for this rowptr, or both
+ *            NULL (rows then run in natural order, one wavefront per row slice:
+ *            correct for any graph, slow on hub rows).  class_off is a HOST
+ *            pointer and is read before the call returns.
+ *
+ * Sums are compensated, so every element is within a few fp32 ulp of the
+ * exactly rounded result whatever the degree; max is exact.  No atomics are
+ * used: results are bit-reproducible from run to run.
+ */
+GNNAGG_API int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* edge_w,
+                     const void* X, int x_dtype, void* out, int out_dtype, int32_t F, int32_t f_chunk,
+                     const int32_t* row_order, const int64_t* class_off, void* stream);
+
+/*
+ * Graph-attention aggregation (the GAT operator the paper evaluates in
+ * Section III, with chunk width 8 = one head at 8 channels per head).
+ *
+ *   H          [N, heads, C] fp32
+ *   a_src,a_dst [heads, C] fp32
+ *   score      s_src[j,h] = sum_c a_src[h,c] H[j,h,c], s_dst likewise, computed
+ *              once from whole head vectors (so every chunk sees the same
+ *              weights); e_ij,h = LeakyReLU(s_src[j,h] + s_dst[i,h])
+ *   alpha      [nnz, heads] fp32 out, may be NULL: softmax of e over the in-edges
+ *              of each destination, per head
+ *   out        [N, heads, C] fp32 out, may be NULL: sum_j alpha_ij,h H[j,h,:];
+ *              empty rows give 0
+ *   f_chunk    0, or a multiple of C (chunks are whole heads); anything else is
+ *              GNNAGG_EINVAL
+ *   workspace  holds the two score arrays, 2*N*heads fp32
+ */
+GNNAGG_API int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* H,
+                         const float* a_src, const float* a_dst, int32_t heads, int32_t C,
+                         float negative_slope, float* alpha, float* out, int32_t f_chunk,
+                         const int32_t* row_order, const int64_t* class_off, void* workspace,
+                         size_t* workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GNNAGG_H */

@@ -1,0 +1,13 @@
+"""libgnnagg for AMD MI355X: message-passing Aggregation by feature slices
+(arXiv 2104.03058, Algorithm 1) as hand-written HIP kernels behind a C ABI.
+
+This package is only the thin ctypes binding over ``libgnnagg.so``; every step
+of the path runs in the library's kernels.  PyTorch supplies device memory and
+streams, nothing else.  There is no CPU fallback: without the built library or
+without a GPU the calls raise.
+"""
+from .binding import (  # noqa: F401
+    BF16, F32, MAX, MEAN, NORM_SYM, PLAN_CLASSES, SELF_LOOPS, SUM, WSUM, GnnaggError, RowPlan,
+    gnnagg_aggregate, gnnagg_build_csr, gnnagg_gat_attention, gnnagg_plan_rows, gnnagg_strerror,
+    gnnagg_version, library_path, load_library,
+)

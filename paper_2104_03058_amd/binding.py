@@ -1,0 +1,215 @@
+"""ctypes binding of libgnnagg.so: argument marshalling only.
+
+Each function mirrors the C entry point of the same name in ``include/gnnagg.h``
+and takes torch tensors that already live on the GPU.  Output tensors and
+workspaces are allocated here with torch (device memory is all torch is used
+for); no arithmetic of the method happens in Python.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+SUM, WSUM, MEAN, MAX = 0, 1, 2, 3
+F32, BF16 = 0, 1
+SELF_LOOPS, NORM_SYM = 1, 2
+PLAN_CLASSES = 33
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgnnagg.so")
+_lib = None
+
+
+class GnnaggError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__("%s failed: %d (%s)" % (fn, status, gnnagg_strerror(status)))
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libgnnagg.so built in-tree; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                "%s is missing: build it with `python -m paper_2104_03058_amd.build`" % _LIB_PATH)
+        lib = ctypes.CDLL(_LIB_PATH)
+        i64, i32, u32, ci, vp, f32 = (ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_int,
+                                      ctypes.c_void_p, ctypes.c_float)
+        szp = ctypes.POINTER(ctypes.c_size_t)
+        lib.gnnagg_version.restype = ci
+        lib.gnnagg_version.argtypes = []
+        lib.gnnagg_strerror.restype = ctypes.c_char_p
+        lib.gnnagg_strerror.argtypes = [ci]
+        lib.gnnagg_build_csr.restype = ci
+        lib.gnnagg_build_csr.argtypes = [i64, i64, vp, vp, u32, vp, vp, vp, vp, vp, szp, vp]
+        lib.gnnagg_plan_rows.restype = ci
+        lib.gnnagg_plan_rows.argtypes = [i64, vp, vp, vp, vp, szp, vp]
+        lib.gnnagg_aggregate.restype = ci
+        lib.gnnagg_aggregate.argtypes = [ci, i64, vp, vp, vp, vp, ci, vp, ci, i32, i32, vp, vp, vp]
+        lib.gnnagg_gat_attention.restype = ci
+        lib.gnnagg_gat_attention.argtypes = [i64, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp, i32, vp, vp, vp, szp,
+                                             vp]
+        _lib = lib
+    return _lib
+
+
+def gnnagg_version() -> int:
+    return load_library().gnnagg_version()
+
+
+def gnnagg_strerror(status: int) -> str:
+    return load_library().gnnagg_strerror(status).decode()
+
+
+def _dev(t: Optional[torch.Tensor], dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must be a GPU tensor" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    # torch's caching allocator hands out 512-byte aligned blocks
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def _check(fn: str, rc: int):
+    if rc != 0:
+        raise GnnaggError(fn, rc)
+
+
+def gnnagg_build_csr(N: int, src: torch.Tensor, dst: torch.Tensor, flags: int = 0, want_w: bool = False,
+                     want_perm: bool = False, stream=None):
+    """COO -> destination-indexed CSR on the GPU.
+    Returns (rowptr int64 [N+1], colidx int32 [nnz], edge_w float32 [nnz] | None, perm int64 [nnz] | None)."""
+    lib = load_library()
+    E = int(src.shape[0])
+    if dst.shape[0] != E:
+        raise ValueError("src and dst differ in length")
+    dev = src.device
+    nnz = E + (N if flags & SELF_LOOPS else 0)
+    need = ctypes.c_size_t(0)
+    _check("gnnagg_build_csr", lib.gnnagg_build_csr(N, E, None, None, flags, None, None, None, None, None,
+                                                     ctypes.byref(need), None))
+    ws = _workspace(need.value, dev)
+    rowptr = torch.empty(N + 1, dtype=torch.int64, device=dev)
+    colidx = torch.empty(nnz, dtype=torch.int32, device=dev)
+    w = torch.empty(nnz, dtype=torch.float32, device=dev) if want_w else None
+    perm = torch.empty(nnz, dtype=torch.int64, device=dev) if want_perm else None
+    have = ctypes.c_size_t(ws.numel())
+    rc = lib.gnnagg_build_csr(N, E, _dev(src, torch.int32, "src"), _dev(dst, torch.int32, "dst"), flags,
+                              _dev(rowptr), _dev(colidx), _dev(w), _dev(perm), _dev(ws), ctypes.byref(have),
+                              _stream(stream))
+    _check("gnnagg_build_csr", rc)
+    return rowptr, colidx, w, perm
+
+
+@dataclass
+class RowPlan:
+    """Degree-sorted row schedule: device row order plus host class offsets."""
+    row_order: torch.Tensor
+    class_off: "ctypes.Array"
+
+    def class_offsets(self):
+        return list(self.class_off)
+
+
+def gnnagg_plan_rows(rowptr: torch.Tensor, stream=None) -> RowPlan:
+    lib = load_library()
+    N = int(rowptr.shape[0]) - 1
+    dev = rowptr.device
+    need = ctypes.c_size_t(0)
+    _check("gnnagg_plan_rows", lib.gnnagg_plan_rows(N, None, None, None, None, ctypes.byref(need), None))
+    ws = _workspace(need.value, dev)
+    order = torch.empty(max(N, 1), dtype=torch.int32, device=dev)
+    class_off = (ctypes.c_int64 * (PLAN_CLASSES + 1))()
+    have = ctypes.c_size_t(ws.numel())
+    rc = lib.gnnagg_plan_rows(N, _dev(rowptr, torch.int64, "rowptr"), _dev(order),
+                              ctypes.cast(class_off, ctypes.c_void_p), _dev(ws), ctypes.byref(have),
+                              _stream(stream))
+    _check("gnnagg_plan_rows", rc)
+    return RowPlan(order[:N] if N > 0 else order[:0], class_off)
+
+
+def _x_dtype(X: torch.Tensor) -> int:
+    if X.dtype == torch.float32:
+        return F32
+    if X.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("X must be float32 or bfloat16")
+
+
+def gnnagg_aggregate(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w: Optional[torch.Tensor],
+                     X: torch.Tensor, out: Optional[torch.Tensor] = None, f_chunk: int = 0,
+                     plan: Optional[RowPlan] = None, stream=None) -> torch.Tensor:
+    """out[N,F] fp32 = aggregation of X[N,F] over the CSR; enqueued on the current stream."""
+    lib = load_library()
+    if X.dim() != 2:
+        raise ValueError("X must be [N, F]")
+    N, F = int(X.shape[0]), int(X.shape[1])
+    if rowptr.shape[0] != N + 1:
+        raise ValueError("rowptr must have N+1 entries")
+    if out is None:
+        out = torch.empty((N, F), dtype=torch.float32, device=X.device)
+    elif tuple(out.shape) != (N, F):
+        raise ValueError("out must be [N, F]")
+    rc = lib.gnnagg_aggregate(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
+                              _dev(edge_w, torch.float32, "edge_w"), _dev(X, None, "X"), _x_dtype(X),
+                              _dev(out, torch.float32, "out"), F32, F, f_chunk,
+                              _dev(plan.row_order, torch.int32, "row_order") if plan is not None else None,
+                              ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None,
+                              _stream(stream))
+    _check("gnnagg_aggregate", rc)
+    return out
+
+
+def gnnagg_gat_attention(rowptr: torch.Tensor, colidx: torch.Tensor, H: torch.Tensor, a_src: torch.Tensor,
+                         a_dst: torch.Tensor, negative_slope: float = 0.2, want_alpha: bool = False,
+                         want_out: bool = True, f_chunk: int = 0, plan: Optional[RowPlan] = None, stream=None):
+    """H [N,heads,C] fp32 -> (alpha [nnz,heads] | None, out [N,heads,C] | None)."""
+    lib = load_library()
+    if H.dim() != 3:
+        raise ValueError("H must be [N, heads, C]")
+    N, heads, C = (int(v) for v in H.shape)
+    if tuple(a_src.shape) != (heads, C) or tuple(a_dst.shape) != (heads, C):
+        raise ValueError("a_src and a_dst must be [heads, C]")
+    dev = H.device
+    nnz = int(colidx.shape[0])
+    need = ctypes.c_size_t(0)
+    _check("gnnagg_gat_attention",
+           lib.gnnagg_gat_attention(N, None, None, None, None, None, heads, C, negative_slope, None, None, f_chunk,
+                                    None, None, None, ctypes.byref(need), None))
+    ws = _workspace(need.value, dev)
+    alpha = torch.empty((nnz, heads), dtype=torch.float32, device=dev) if want_alpha else None
+    out = torch.empty((N, heads, C), dtype=torch.float32, device=dev) if want_out else None
+    have = ctypes.c_size_t(ws.numel())
+    rc = lib.gnnagg_gat_attention(N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
+                                  _dev(H, torch.float32, "H"), _dev(a_src, torch.float32, "a_src"),
+                                  _dev(a_dst, torch.float32, "a_dst"), heads, C, negative_slope, _dev(alpha),
+                                  _dev(out), f_chunk,
+                                  _dev(plan.row_order, torch.int32, "row_order") if plan is not None else None,
+                                  ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None,
+                                  _dev(ws), ctypes.byref(have), _stream(stream))
+    _check("gnnagg_gat_attention", rc)
+    # the score arrays in ws are read by the kernels just enqueued: keep ws alive until they ran
+    ws.record_stream(torch.cuda.current_stream() if stream is None else stream)
+    return alpha, out

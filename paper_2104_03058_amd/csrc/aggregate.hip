@@ -1,0 +1,278 @@
+// gnnagg_aggregate: sum / weighted sum / mean / max over CSR neighbour lists,
+// one feature slice at a time (paper Algorithm 1: Message, Aggregate, Concat).
+//
+// Work decomposition for wave64 hardware
+//   - A feature slice is at most 64 lanes x VEC columns (VEC columns = 16 bytes
+//     of input per lane), so the lanes that share a neighbour read one
+//     contiguous piece of its row: the gathers coalesce.
+//   - 2^g lanes span the slice; a row gets 2^L lanes (L >= g), i.e. 2^(L-g)
+//     neighbour slots that walk the row's edge list interleaved and are merged
+//     with cross-lane shuffles at the end.  L comes from the row's degree class:
+//     short rows share a wave (several rows per wave), long rows get a wave,
+//     hub rows get the whole workgroup and meet in LDS.
+//   - Slices are enumerated chunk-major over the grid, so chunks run in the
+//     chunk-outer / vertex-inner order of Algorithm 1 and each slice is written
+//     straight into its columns of `out` (the Concat step costs nothing).
+//   - Sums carry a compensation term per column (hi + lo), also through the
+//     merges, so the result does not depend on the degree or on how the row was
+//     split; max works on order-preserving integer keys and is exact.
+#include "common.hpp"
+#include "schedule.hpp"
+#include "device_utils.hpp"
+
+namespace gnnagg {
+namespace {
+
+enum { OPK_SUM = 0, OPK_WSUM = 1, OPK_MAX = 2 };
+constexpr int kUnroll = 8;  // independent gathers in flight per lane
+
+struct AggArgs {
+  const int64_t* rowptr;
+  const int32_t* colidx;
+  const float* edge_w;
+  const void* X;
+  float* out;
+  const int32_t* order;
+  int64_t F;
+  SliceLaunch sl;
+  int32_t mean;
+  SegTable segs;
+};
+
+// float bits <-> integer key whose signed order is the float order with
+// -0 below +0 (the map is its own inverse)
+__device__ inline int32_t order_key(float f) {
+  const int32_t b = __float_as_int(f);
+  return b ^ ((b >> 31) & 0x7fffffff);
+}
+__device__ inline float key_value(int32_t k) { return __int_as_float(k ^ ((k >> 31) & 0x7fffffff)); }
+
+// Per-lane reduction state for VEC columns.
+template <int OPK, int VEC>
+struct State {
+  float hi[VEC];  // running sum            | max: key bits
+  float lo[VEC];  // running compensation   | max: unused
+  __device__ inline void init() {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      hi[k] = (OPK == OPK_MAX) ? __int_as_float((int32_t)0x80000000) : 0.0f;
+      lo[k] = 0.0f;
+    }
+  }
+  __device__ inline void add(const float (&v)[VEC], float w) {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      if (OPK == OPK_MAX) {
+        const int32_t a = __float_as_int(hi[k]), b = order_key(v[k]);
+        hi[k] = __int_as_float(a > b ? a : b);
+      } else {
+        // compensated accumulation: hi + lo tracks the exact running sum
+        const float y = (OPK == OPK_WSUM) ? __builtin_fmaf(w, v[k], lo[k]) : v[k] + lo[k];
+        const float t = hi[k] + y;
+        lo[k] = y - (t - hi[k]);
+        hi[k] = t;
+      }
+    }
+  }
+  __device__ inline void merge(const State& o) {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      if (OPK == OPK_MAX) {
+        const int32_t a = __float_as_int(hi[k]), b = __float_as_int(o.hi[k]);
+        hi[k] = __int_as_float(a > b ? a : b);
+      } else {
+        // error-free addition of the two running sums; the rounding error joins the compensation
+        const float t = hi[k] + o.hi[k];
+        const float bb = t - hi[k];
+        const float err = (hi[k] - (t - bb)) + (o.hi[k] - bb);
+        lo[k] = (lo[k] + o.lo[k]) + err;
+        hi[k] = t;
+      }
+    }
+  }
+  __device__ inline State shuffled_xor(int stride) const {
+    State o;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      o.hi[k] = __shfl_xor(hi[k], stride, kWave);
+      if (OPK != OPK_MAX) o.lo[k] = __shfl_xor(lo[k], stride, kWave);
+    }
+    return o;
+  }
+};
+
+template <typename T, int OPK, int VEC>
+__global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
+  __shared__ float lds[(kWavesPerBlock - 1) * kWave * 2 * VEC];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+
+  const LaneRole role = lane_role(a.sl, a.segs, blockIdx.x, tid);
+  const int g = role.g, ng = role.ng, P = role.P, col = role.col;
+  const bool hub = role.hub, row_ok = role.row_ok, col_ok = role.col_ok;
+  int64_t r = 0, e0 = 0, e1 = 0;
+  if (row_ok) {
+    r = a.order ? (int64_t)a.order[role.ridx] : role.ridx;
+    e0 = a.rowptr[r];
+    e1 = a.rowptr[r + 1];
+  }
+  const int64_t deg = e1 - e0;
+  const T* __restrict__ xcol = static_cast<const T*>(a.X) + col;
+  const int64_t e_stop = (row_ok && col_ok) ? e1 : e0;
+
+  State<OPK, VEC> st;
+  st.init();
+  for (int64_t e = e0 + ng; e < e_stop; e += (int64_t)kUnroll * P) {
+    int32_t j[kUnroll];
+    float w[kUnroll];
+    typename Raw<T, VEC>::type raw[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int64_t ee = e + (int64_t)u * P;
+      const bool ok = ee < e_stop;
+      j[u] = ok ? a.colidx[ee] : -1;
+      if (OPK == OPK_WSUM) w[u] = ok ? a.edge_w[ee] : 0.0f;
+      else w[u] = 1.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+      if (j[u] >= 0) raw[u] = load_raw<T, VEC>(xcol + (int64_t)j[u] * a.F);
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      if (j[u] >= 0) {
+        float v[VEC];
+        unpack(raw[u], v);
+        st.add(v, w[u]);
+      }
+    }
+  }
+
+  // ---- merge the neighbour slots of a row -------------------------------------
+  const int lanes_in_wave = hub ? kWave : (1 << role.L);
+  for (int stride = 1 << g; stride < lanes_in_wave; stride <<= 1) st.merge(st.shuffled_xor(stride));
+  if (hub) {
+    // lanes [0, 2^g) of each wave now hold that wave's partial for their columns (if 2^g < 64);
+    // waves 1..3 park theirs in LDS, wave 0 folds them in wave order
+    if (wv > 0) {
+      float* slotp = lds + ((wv - 1) * kWave + lane) * 2 * VEC;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        slotp[k] = st.hi[k];
+        slotp[VEC + k] = st.lo[k];
+      }
+    }
+    __syncthreads();
+    if (wv == 0) {
+      for (int ww = 1; ww < kWavesPerBlock; ++ww) {
+        const float* slotp = lds + ((ww - 1) * kWave + lane) * 2 * VEC;
+        State<OPK, VEC> o;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+          o.hi[k] = slotp[k];
+          o.lo[k] = slotp[VEC + k];
+        }
+        st.merge(o);
+      }
+    }
+  }
+
+  // ---- write the slice of the output row ----------------------------------------
+  if (role.writer) {
+    float res[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      if (OPK == OPK_MAX) {
+        res[k] = deg > 0 ? key_value(__float_as_int(st.hi[k])) : 0.0f;
+      } else {
+        const float s = st.hi[k] + st.lo[k];
+        res[k] = (a.mean && deg > 0) ? s / (float)deg : s;
+      }
+    }
+    store_row<VEC>(a.out + r * a.F + col, res);
+  }
+}
+
+template <typename T, int OPK, int VEC>
+int launch_one(const AggArgs& a, uint64_t grid, hipStream_t stream) {
+  hipLaunchKernelGGL((aggregate_kernel<T, OPK, VEC>), dim3((unsigned)grid), dim3(kBlock), 0, stream, a);
+  return hipGetLastError() == hipSuccess ? GNNAGG_OK : GNNAGG_EDEVICE;
+}
+
+template <typename T, int OPK>
+int launch_vec(const AggArgs& a, uint64_t grid, hipStream_t stream) {
+  switch (a.sl.vec) {
+    case 1: return launch_one<T, OPK, 1>(a, grid, stream);
+    case 2: return launch_one<T, OPK, 2>(a, grid, stream);
+    case 4: return launch_one<T, OPK, 4>(a, grid, stream);
+    case 8:
+      if constexpr (sizeof(T) == 2) return launch_one<T, OPK, 8>(a, grid, stream);
+      return GNNAGG_EINVAL;
+    default: return GNNAGG_EINVAL;
+  }
+}
+
+template <typename T>
+int launch_op(int opk, const AggArgs& a, uint64_t grid, hipStream_t stream) {
+  switch (opk) {
+    case OPK_SUM: return launch_vec<T, OPK_SUM>(a, grid, stream);
+    case OPK_WSUM: return launch_vec<T, OPK_WSUM>(a, grid, stream);
+    default: return launch_vec<T, OPK_MAX>(a, grid, stream);
+  }
+}
+
+}  // namespace
+}  // namespace gnnagg
+
+using namespace gnnagg;
+
+extern "C" int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                                const float* edge_w, const void* X, int x_dtype, void* out, int out_dtype,
+                                int32_t F, int32_t f_chunk, const int32_t* row_order, const int64_t* class_off,
+                                void* stream_) {
+  if (op < GNNAGG_SUM || op > GNNAGG_MAX) return GNNAGG_EINVAL;
+  if (N < 0 || F <= 0 || f_chunk < 0) return GNNAGG_EINVAL;
+  if (x_dtype != GNNAGG_F32 && x_dtype != GNNAGG_BF16) return GNNAGG_EINVAL;
+  if (out_dtype != GNNAGG_F32) return out_dtype == GNNAGG_BF16 ? GNNAGG_EUNSUPPORTED : GNNAGG_EINVAL;
+  if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
+  if ((row_order == nullptr) != (class_off == nullptr)) return GNNAGG_EINVAL;
+  if (N == 0) return GNNAGG_OK;
+  if (!rowptr || !X || !out) return GNNAGG_ENULL;
+  if (op == GNNAGG_WSUM && !edge_w) return GNNAGG_ENULL;
+  // colidx may only be NULL for a graph without edges, which the host cannot see; require it
+  if (!colidx) return GNNAGG_ENULL;
+  const size_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
+  if (((uintptr_t)X % xs) || ((uintptr_t)out % 4) || ((uintptr_t)rowptr % 8) || ((uintptr_t)colidx % 4) ||
+      (edge_w && ((uintptr_t)edge_w % 4)))
+    return GNNAGG_EINVAL;
+  if (X == out) return GNNAGG_EINVAL;
+
+  std::vector<SliceLaunch> launches;
+  plan_columns(F, f_chunk, (int)(16 / xs), 0, &launches);
+  hipStream_t stream = (hipStream_t)stream_;
+  const int opk = (op == GNNAGG_WSUM) ? OPK_WSUM : (op == GNNAGG_MAX ? OPK_MAX : OPK_SUM);
+
+  // build and validate every launch before the first one is enqueued
+  std::vector<AggArgs> args(launches.size());
+  std::vector<uint64_t> grids(launches.size());
+  for (size_t k = 0; k < launches.size(); ++k) {
+    AggArgs& a = args[k];
+    a.rowptr = rowptr;
+    a.colidx = colidx;
+    a.edge_w = edge_w;
+    a.X = X;
+    a.out = static_cast<float*>(out);
+    a.order = row_order;
+    a.F = F;
+    a.sl = launches[k];
+    a.mean = (op == GNNAGG_MEAN);
+    int rc = build_segments(class_off, N, a.sl.g_log2, &a.segs);
+    if (rc != GNNAGG_OK) return rc;
+    grids[k] = (uint64_t)a.segs.blocks_per_slice * (uint64_t)a.sl.n_chunks * (uint64_t)a.sl.n_sub;
+    if (grids[k] == 0 || grids[k] > 0x7fffffffull) return GNNAGG_EUNSUPPORTED;
+  }
+  for (size_t k = 0; k < launches.size(); ++k) {
+    int rc = (x_dtype == GNNAGG_F32) ? launch_op<float>(opk, args[k], grids[k], stream)
+                                     : launch_op<bf16_t>(opk, args[k], grids[k], stream);
+    if (rc != GNNAGG_OK) return rc;
+  }
+  return GNNAGG_OK;
+}

@@ -1,0 +1,233 @@
+// gnnagg_build_csr and gnnagg_plan_rows: the per-graph steps that precede
+// aggregation (paper Section II-C: the edge set arrives in COO form; Section
+// III: format conversion is a cost of its own).
+//
+// CSR build = one stable radix sort of the edges on the key
+// (destination, source) carrying the input position, so that ties fall in
+// input order; row pointers come from the boundaries of the sorted keys.
+// Integer work only, no atomics on the outputs: the result is unique.
+#include "common.hpp"
+#include "radix_sort.hpp"
+
+namespace gnnagg {
+namespace {
+
+__global__ __launch_bounds__(kBlock) void make_edge_keys_kernel(const int32_t* __restrict__ src,
+                                                                const int32_t* __restrict__ dst, int64_t E,
+                                                                int64_t nnz, int64_t N, int src_bits,
+                                                                uint64_t* __restrict__ keys,
+                                                                uint32_t* __restrict__ vals,
+                                                                uint32_t* __restrict__ bad) {
+  const int64_t k = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (k >= nnz) return;
+  int64_t s, d;
+  if (k < E) {
+    s = src[k];
+    d = dst[k];
+    if (s < 0 || s >= N || d < 0 || d >= N) {  // keep every later access in range, report to the host
+      *bad = 1u;
+      s = 0;
+      d = 0;
+    }
+  } else {
+    s = d = k - E;  // appended self-loop
+  }
+  keys[k] = ((uint64_t)d << src_bits) | (uint64_t)s;
+  vals[k] = (uint32_t)k;
+}
+
+__global__ void fill_u32_kernel(uint32_t* __restrict__ p, uint32_t v) { *p = v; }
+
+__global__ __launch_bounds__(kBlock) void fill_i64_kernel(int64_t* __restrict__ p, int64_t n, int64_t v) {
+  const int64_t k = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (k < n) p[k] = v;
+}
+
+// rowptr[r] = first slot whose destination is >= r.  Slot e writes the rows in
+// (dst[e-1], dst[e]]; the last slot also closes the rows above its destination.
+__global__ __launch_bounds__(kBlock) void csr_from_sorted_kernel(const uint64_t* __restrict__ keys,
+                                                                 const uint32_t* __restrict__ vals,
+                                                                 int64_t nnz, int64_t N, int src_bits,
+                                                                 int64_t* __restrict__ rowptr,
+                                                                 int32_t* __restrict__ colidx,
+                                                                 int64_t* __restrict__ perm) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (e >= nnz) return;
+  const uint64_t key = keys[e];
+  const int64_t d = (int64_t)(key >> src_bits);
+  const int64_t dprev = (e == 0) ? -1 : (int64_t)(keys[e - 1] >> src_bits);
+  for (int64_t r = dprev + 1; r <= d; ++r) rowptr[r] = e;
+  if (e == nnz - 1)
+    for (int64_t r = d + 1; r <= N; ++r) rowptr[r] = nnz;
+  colidx[e] = (int32_t)(key & ((1ull << src_bits) - 1ull));
+  if (perm) perm[e] = (int64_t)vals[e];
+}
+
+// GCN symmetric normalisation: fp64 1/sqrt(d_i d_j), one rounding to fp32.
+__global__ __launch_bounds__(kBlock) void edge_weight_kernel(const uint64_t* __restrict__ keys, int64_t nnz,
+                                                             int src_bits, const int64_t* __restrict__ rowptr,
+                                                             int norm_sym, float* __restrict__ edge_w) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (e >= nnz) return;
+  if (!norm_sym) {
+    edge_w[e] = 1.0f;
+    return;
+  }
+  const uint64_t key = keys[e];
+  const int64_t i = (int64_t)(key >> src_bits);
+  const int64_t j = (int64_t)(key & ((1ull << src_bits) - 1ull));
+  const double di = (double)(rowptr[i + 1] - rowptr[i]);
+  const double dj = (double)(rowptr[j + 1] - rowptr[j]);
+  edge_w[e] = (float)(1.0 / sqrt(di * dj));
+}
+
+// ---- row plan -------------------------------------------------------------
+__device__ inline int degree_class(int64_t deg) {  // 0 for empty, else 1 + floor(log2 deg), capped at 32
+  if (deg <= 0) return 0;
+  const int c = 64 - __clzll((unsigned long long)deg);
+  return c > 32 ? 32 : c;
+}
+
+__global__ __launch_bounds__(kBlock) void make_degree_keys_kernel(const int64_t* __restrict__ rowptr, int64_t N,
+                                                                  uint64_t* __restrict__ keys,
+                                                                  uint32_t* __restrict__ vals) {
+  const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (r >= N) return;
+  int64_t deg = rowptr[r + 1] - rowptr[r];
+  if (deg < 0) deg = 0;
+  if (deg > 0xffffffffll) deg = 0xffffffffll;
+  keys[r] = 0xffffffffull - (uint64_t)deg;  // ascending key = descending degree
+  vals[r] = (uint32_t)r;
+}
+
+// Writes row_order and, at every change of degree class along the sorted
+// order, the class offsets: class c starts at class_off[32 - c].
+__global__ __launch_bounds__(kBlock) void plan_finish_kernel(const uint64_t* __restrict__ keys,
+                                                             const uint32_t* __restrict__ vals, int64_t N,
+                                                             int32_t* __restrict__ row_order,
+                                                             int64_t* __restrict__ class_off) {
+  const int64_t k = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (k > N) return;
+  // class of the row at sorted position k; position N acts as class -1, position -1 as class 33
+  const int c = (k < N) ? degree_class((int64_t)(0xffffffffull - keys[k])) : -1;
+  const int cprev = (k == 0) ? GNNAGG_PLAN_CLASSES : degree_class((int64_t)(0xffffffffull - keys[k - 1]));
+  for (int cc = cprev - 1; cc > c; --cc) class_off[32 - cc] = k;  // classes with no rows
+  if (c >= 0 && c != cprev) class_off[32 - c] = k;
+  if (k < N) row_order[k] = (int32_t)vals[k];
+  else class_off[GNNAGG_PLAN_CLASSES] = N;
+}
+
+struct CsrWorkspace {
+  uint64_t *keys_a, *keys_b;
+  uint32_t *vals_a, *vals_b, *hist, *scan, *bad;
+  size_t bytes;
+};
+
+CsrWorkspace carve_sort_workspace(void* base, int64_t n) {
+  Carver c(base);
+  CsrWorkspace w;
+  const size_t cnt = (size_t)(n > 0 ? n : 1);
+  w.keys_a = c.take<uint64_t>(cnt);
+  w.keys_b = c.take<uint64_t>(cnt);
+  w.vals_a = c.take<uint32_t>(cnt);
+  w.vals_b = c.take<uint32_t>(cnt);
+  const size_t hw = sort_hist_words(n > 0 ? n : 1);
+  w.hist = c.take<uint32_t>(hw);
+  w.scan = c.take<uint32_t>(scan_scratch_words((int64_t)hw));
+  w.bad = c.take<uint32_t>(64);
+  w.bytes = c.used;
+  return w;
+}
+
+unsigned grid_for(int64_t n) { return (unsigned)ceil_div(n > 0 ? n : 1, kBlock); }
+
+}  // namespace
+}  // namespace gnnagg
+
+using namespace gnnagg;
+
+extern "C" int gnnagg_build_csr(int64_t N, int64_t E, const int32_t* src, const int32_t* dst, uint32_t flags,
+                                int64_t* rowptr, int32_t* colidx, float* edge_w, int64_t* perm, void* workspace,
+                                size_t* workspace_bytes, void* stream_) {
+  if (N < 0 || E < 0) return GNNAGG_EINVAL;
+  if (flags & ~(uint32_t)(GNNAGG_SELF_LOOPS | GNNAGG_NORM_SYM)) return GNNAGG_EINVAL;
+  if (!workspace_bytes) return GNNAGG_ENULL;
+  if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
+  if (N == 0 && E > 0) return GNNAGG_EINVAL;  // no vertex an edge could touch
+  const int64_t nnz = E + ((flags & GNNAGG_SELF_LOOPS) ? N : 0);
+  if (nnz >= (1ll << 32)) return GNNAGG_EUNSUPPORTED;
+  CsrWorkspace w = carve_sort_workspace(workspace, nnz);
+  if (!workspace) {
+    *workspace_bytes = w.bytes;
+    return GNNAGG_OK;
+  }
+  if (!rowptr || (E > 0 && (!src || !dst)) || (nnz > 0 && !colidx)) return GNNAGG_ENULL;
+  if (*workspace_bytes < w.bytes || ((uintptr_t)workspace & 255u)) return GNNAGG_EWORKSPACE;
+  hipStream_t stream = (hipStream_t)stream_;
+
+  if (nnz == 0) {
+    hipLaunchKernelGGL(fill_i64_kernel, dim3(grid_for(N + 1)), dim3(kBlock), 0, stream, rowptr, N + 1, (int64_t)0);
+    GNNAGG_HIP_TRY(hipGetLastError());
+    GNNAGG_HIP_TRY(hipStreamSynchronize(stream));
+    return GNNAGG_OK;
+  }
+  const int src_bits = bits_for((uint64_t)(N - 1));
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(1), 0, stream, w.bad, 0u);
+  hipLaunchKernelGGL(make_edge_keys_kernel, dim3(grid_for(nnz)), dim3(kBlock), 0, stream, src, dst, E, nnz, N,
+                     src_bits, w.keys_a, w.vals_a, w.bad);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  bool in_a = true;
+  int rc = radix_sort_pairs(w.keys_a, w.vals_a, w.keys_b, w.vals_b, nnz, 0, 2 * src_bits, w.hist, w.scan, stream,
+                            &in_a);
+  if (rc != GNNAGG_OK) return rc;
+  const uint64_t* keys = in_a ? w.keys_a : w.keys_b;
+  const uint32_t* vals = in_a ? w.vals_a : w.vals_b;
+  hipLaunchKernelGGL(csr_from_sorted_kernel, dim3(grid_for(nnz)), dim3(kBlock), 0, stream, keys, vals, nnz, N,
+                     src_bits, rowptr, colidx, perm);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  if (edge_w) {
+    hipLaunchKernelGGL(edge_weight_kernel, dim3(grid_for(nnz)), dim3(kBlock), 0, stream, keys, nnz, src_bits,
+                       (const int64_t*)rowptr, (int)((flags & GNNAGG_NORM_SYM) != 0), edge_w);
+    GNNAGG_HIP_TRY(hipGetLastError());
+  }
+  uint32_t bad = 0;
+  GNNAGG_HIP_TRY(hipMemcpyAsync(&bad, w.bad, sizeof(bad), hipMemcpyDeviceToHost, stream));
+  GNNAGG_HIP_TRY(hipStreamSynchronize(stream));
+  return bad ? GNNAGG_EINVAL : GNNAGG_OK;
+}
+
+extern "C" int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_order, int64_t* class_off,
+                                void* workspace, size_t* workspace_bytes, void* stream_) {
+  if (N < 0) return GNNAGG_EINVAL;
+  if (!workspace_bytes) return GNNAGG_ENULL;
+  if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
+  CsrWorkspace w = carve_sort_workspace(workspace, N);
+  Carver extra(workspace ? (char*)workspace + w.bytes : nullptr);
+  int64_t* d_off = extra.take<int64_t>(GNNAGG_PLAN_CLASSES + 1);
+  const size_t need = w.bytes + extra.used;
+  if (!workspace) {
+    *workspace_bytes = need;
+    return GNNAGG_OK;
+  }
+  if (!rowptr || !class_off || (N > 0 && !row_order)) return GNNAGG_ENULL;
+  if (*workspace_bytes < need || ((uintptr_t)workspace & 255u)) return GNNAGG_EWORKSPACE;
+  hipStream_t stream = (hipStream_t)stream_;
+  if (N == 0) {
+    for (int k = 0; k <= GNNAGG_PLAN_CLASSES; ++k) class_off[k] = 0;
+    return GNNAGG_OK;
+  }
+  hipLaunchKernelGGL(make_degree_keys_kernel, dim3(grid_for(N)), dim3(kBlock), 0, stream, rowptr, N, w.keys_a,
+                     w.vals_a);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  bool in_a = true;
+  int rc = radix_sort_pairs(w.keys_a, w.vals_a, w.keys_b, w.vals_b, N, 0, 32, w.hist, w.scan, stream, &in_a);
+  if (rc != GNNAGG_OK) return rc;
+  hipLaunchKernelGGL(plan_finish_kernel, dim3(grid_for(N + 1)), dim3(kBlock), 0, stream,
+                     (const uint64_t*)(in_a ? w.keys_a : w.keys_b), (const uint32_t*)(in_a ? w.vals_a : w.vals_b), N,
+                     row_order, d_off);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  GNNAGG_HIP_TRY(hipMemcpyAsync(class_off, d_off, sizeof(int64_t) * (GNNAGG_PLAN_CLASSES + 1),
+                                hipMemcpyDeviceToHost, stream));
+  GNNAGG_HIP_TRY(hipStreamSynchronize(stream));
+  return GNNAGG_OK;
+}

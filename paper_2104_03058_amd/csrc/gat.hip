@@ -1,0 +1,277 @@
+// gnnagg_gat_attention: edge scores, softmax over each destination's in-edges
+// and the per-head weighted sum, in one pass over the neighbour rows.
+//
+// The attention logits need whole head vectors, so the two per-vertex score
+// arrays are computed once up front; chunks are whole heads (the paper's GAT
+// chunk width 8, Section III, is one head at 8 channels) and every chunk sees
+// the same weights.  The softmax is kept online: a lane carries (running max,
+// running denominator, running weighted sum) for the head its columns belong
+// to, one exp per edge, and the states of a row's neighbour slots are merged
+// with cross-lane shuffles (hub rows: across waves through LDS).
+#include <math.h>
+
+#include "common.hpp"
+#include "device_utils.hpp"
+#include "schedule.hpp"
+
+namespace gnnagg {
+namespace {
+
+constexpr int kGatUnroll = 4;
+
+struct GatArgs {
+  const int64_t* rowptr;
+  const int32_t* colidx;
+  const float* H;
+  const float* s_src;
+  const float* s_dst;
+  float* alpha;
+  float* out;
+  const int32_t* order;
+  int32_t heads, C;
+  float slope;
+  SliceLaunch sl;
+  SegTable segs;
+};
+
+// s_src[j,h] = a_src[h,:] . H[j,h,:],  s_dst[j,h] = a_dst[h,:] . H[j,h,:]
+__global__ __launch_bounds__(kBlock) void gat_scores_kernel(const float* __restrict__ H,
+                                                            const float* __restrict__ a_src,
+                                                            const float* __restrict__ a_dst, int64_t n_vh,
+                                                            int32_t heads, int32_t C, float* __restrict__ s_src,
+                                                            float* __restrict__ s_dst) {
+  const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (t >= n_vh) return;
+  const int h = (int)(t % heads);
+  const float* __restrict__ x = H + t * C;
+  const float* __restrict__ as = a_src + (int64_t)h * C;
+  const float* __restrict__ ad = a_dst + (int64_t)h * C;
+  float s = 0.0f, d = 0.0f;
+  for (int c = 0; c < C; ++c) {
+    const float v = x[c];
+    s = __builtin_fmaf(as[c], v, s);
+    d = __builtin_fmaf(ad[c], v, d);
+  }
+  s_src[t] = s;
+  s_dst[t] = d;
+}
+
+template <int VEC>
+struct SoftState {
+  float m;         // running maximum of the logits seen
+  float l;         // sum of exp(logit - m)
+  float acc[VEC];  // sum of exp(logit - m) * H
+  __device__ inline void init() {
+    m = -INFINITY;
+    l = 0.0f;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) acc[k] = 0.0f;
+  }
+  __device__ inline void add(float logit, const float (&v)[VEC]) {
+    const float d = logit - m;
+    const float ex = expf(-fabsf(d));  // exp of the smaller minus the larger; exp(-inf) = 0 on the first edge
+    if (d > 0.0f) {
+      l = __builtin_fmaf(l, ex, 1.0f);
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) acc[k] = __builtin_fmaf(acc[k], ex, v[k]);
+      m = logit;
+    } else {
+      l += ex;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) acc[k] = __builtin_fmaf(ex, v[k], acc[k]);
+    }
+  }
+  __device__ inline void merge(const SoftState& o) {
+    const float mm = fmaxf(m, o.m);
+    const float sa = (m == mm) ? 1.0f : expf(m - mm);
+    const float sb = (o.m == mm) ? 1.0f : expf(o.m - mm);
+    l = l * sa + o.l * sb;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) acc[k] = acc[k] * sa + o.acc[k] * sb;
+    m = mm;
+  }
+  __device__ inline SoftState shuffled_xor(int stride) const {
+    SoftState o;
+    o.m = __shfl_xor(m, stride, kWave);
+    o.l = __shfl_xor(l, stride, kWave);
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) o.acc[k] = __shfl_xor(acc[k], stride, kWave);
+    return o;
+  }
+};
+
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) {
+  __shared__ float lds[(kWavesPerBlock - 1) * kWave * (2 + VEC)];
+  __shared__ float fin[2 * kWave];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+
+  const LaneRole role = lane_role(a.sl, a.segs, blockIdx.x, tid);
+  const int g = role.g, ng = role.ng, P = role.P, col = role.col;  // slice widths are multiples of VEC here
+  const bool hub = role.hub, row_ok = role.row_ok, col_ok = role.col_ok;
+  int64_t r = 0, e0 = 0, e1 = 0;
+  if (row_ok) {
+    r = a.order ? (int64_t)a.order[role.ridx] : role.ridx;
+    e0 = a.rowptr[r];
+    e1 = a.rowptr[r + 1];
+  }
+  const int head = col / a.C;  // VEC divides C, so the lane's columns lie in one head
+  const int64_t HC = (int64_t)a.heads * a.C;
+  const float* __restrict__ hcol = a.H + col;
+  const int64_t e_stop = (row_ok && col_ok) ? e1 : e0;
+  const float sd = (row_ok && col_ok) ? a.s_dst[r * a.heads + head] : 0.0f;
+
+  SoftState<VEC> st;
+  st.init();
+  for (int64_t e = e0 + ng; e < e_stop; e += (int64_t)kGatUnroll * P) {
+    int32_t j[kGatUnroll];
+    float ss[kGatUnroll];
+    typename Raw<float, VEC>::type raw[kGatUnroll];
+#pragma unroll
+    for (int u = 0; u < kGatUnroll; ++u) {
+      const int64_t ee = e + (int64_t)u * P;
+      j[u] = (ee < e_stop) ? a.colidx[ee] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < kGatUnroll; ++u) {
+      if (j[u] >= 0) {
+        ss[u] = a.s_src[(int64_t)j[u] * a.heads + head];
+        raw[u] = load_raw<float, VEC>(hcol + (int64_t)j[u] * HC);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kGatUnroll; ++u) {
+      if (j[u] >= 0) {
+        float v[VEC];
+        unpack(raw[u], v);
+        const float s = ss[u] + sd;
+        st.add(s >= 0.0f ? s : a.slope * s, v);
+      }
+    }
+  }
+
+  const int lanes_in_wave = hub ? kWave : (1 << role.L);
+  for (int stride = 1 << g; stride < lanes_in_wave; stride <<= 1) st.merge(st.shuffled_xor(stride));
+  if (hub) {
+    if (wv > 0) {
+      float* p = lds + ((wv - 1) * kWave + lane) * (2 + VEC);
+      p[0] = st.m;
+      p[1] = st.l;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) p[2 + k] = st.acc[k];
+    }
+    __syncthreads();
+    if (wv == 0) {
+      for (int ww = 1; ww < kWavesPerBlock; ++ww) {
+        const float* p = lds + ((ww - 1) * kWave + lane) * (2 + VEC);
+        SoftState<VEC> o;
+        o.m = p[0];
+        o.l = p[1];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) o.acc[k] = p[2 + k];
+        st.merge(o);
+      }
+      fin[lane] = st.m;
+      fin[kWave + lane] = st.l;
+    }
+    __syncthreads();
+    st.m = fin[lane];  // every wave now knows the row's final maximum and denominator
+    st.l = fin[kWave + lane];
+  }
+
+  if (a.out && role.writer) {
+    float res[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) res[k] = (e1 > e0) ? st.acc[k] / st.l : 0.0f;
+    store_row<VEC>(a.out + r * HC + col, res);
+  }
+  // softmax weights, written by the first lane of every head
+  if (a.alpha && row_ok && col_ok && (col % a.C) == 0) {
+    for (int64_t e = e0 + ng; e < e1; e += P) {
+      const float s = a.s_src[(int64_t)a.colidx[e] * a.heads + head] + sd;
+      const float logit = s >= 0.0f ? s : a.slope * s;
+      a.alpha[e * a.heads + head] = expf(logit - st.m) / st.l;
+    }
+  }
+}
+
+template <int VEC>
+int launch_gat(const GatArgs& a, uint64_t grid, hipStream_t stream) {
+  hipLaunchKernelGGL((gat_aggregate_kernel<VEC>), dim3((unsigned)grid), dim3(kBlock), 0, stream, a);
+  return hipGetLastError() == hipSuccess ? GNNAGG_OK : GNNAGG_EDEVICE;
+}
+
+}  // namespace
+}  // namespace gnnagg
+
+using namespace gnnagg;
+
+extern "C" int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* H,
+                                    const float* a_src, const float* a_dst, int32_t heads, int32_t C,
+                                    float negative_slope, float* alpha, float* out, int32_t f_chunk,
+                                    const int32_t* row_order, const int64_t* class_off, void* workspace,
+                                    size_t* workspace_bytes, void* stream_) {
+  if (N < 0 || heads <= 0 || C <= 0 || f_chunk < 0) return GNNAGG_EINVAL;
+  if ((int64_t)heads * C > 0x7fffffffll) return GNNAGG_EINVAL;
+  if (!(negative_slope == negative_slope)) return GNNAGG_EINVAL;
+  const int32_t F = heads * C;
+  if (f_chunk > 0 && f_chunk < F && (f_chunk % C) != 0) return GNNAGG_EINVAL;  // a chunk may not split a head
+  if (!workspace_bytes) return GNNAGG_ENULL;
+  if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
+  if ((row_order == nullptr) != (class_off == nullptr)) return GNNAGG_EINVAL;
+  Carver carve(workspace);
+  float* s_src = carve.take<float>((size_t)(N > 0 ? N : 1) * heads);
+  float* s_dst = carve.take<float>((size_t)(N > 0 ? N : 1) * heads);
+  if (!workspace) {
+    *workspace_bytes = carve.used;
+    return GNNAGG_OK;
+  }
+  if (*workspace_bytes < carve.used || ((uintptr_t)workspace & 255u)) return GNNAGG_EWORKSPACE;
+  if (N == 0) return GNNAGG_OK;
+  if (!rowptr || !colidx || !H || !a_src || !a_dst) return GNNAGG_ENULL;
+  if (!alpha && !out) return GNNAGG_OK;
+  if (((uintptr_t)H % 4) || ((uintptr_t)rowptr % 8) || ((uintptr_t)colidx % 4) || ((uintptr_t)a_src % 4) ||
+      ((uintptr_t)a_dst % 4) || (out && ((uintptr_t)out % 4)) || (alpha && ((uintptr_t)alpha % 4)))
+    return GNNAGG_EINVAL;
+  if (out == H) return GNNAGG_EINVAL;
+
+  std::vector<SliceLaunch> launches;
+  plan_columns(F, f_chunk, 4, C, &launches);
+  std::vector<GatArgs> args(launches.size());
+  std::vector<uint64_t> grids(launches.size());
+  for (size_t k = 0; k < launches.size(); ++k) {
+    GatArgs& a = args[k];
+    a.rowptr = rowptr;
+    a.colidx = colidx;
+    a.H = H;
+    a.s_src = s_src;
+    a.s_dst = s_dst;
+    a.alpha = alpha;
+    a.out = out;
+    a.order = row_order;
+    a.heads = heads;
+    a.C = C;
+    a.slope = negative_slope;
+    a.sl = launches[k];
+    if (a.sl.sub_w % a.sl.vec || a.sl.chunk_w % a.sl.vec) return GNNAGG_EINVAL;  // cannot happen: vec divides C
+    int rc = build_segments(class_off, N, a.sl.g_log2, &a.segs);
+    if (rc != GNNAGG_OK) return rc;
+    grids[k] = (uint64_t)a.segs.blocks_per_slice * (uint64_t)a.sl.n_chunks * (uint64_t)a.sl.n_sub;
+    if (grids[k] == 0 || grids[k] > 0x7fffffffull) return GNNAGG_EUNSUPPORTED;
+  }
+  hipStream_t stream = (hipStream_t)stream_;
+  const int64_t n_vh = N * heads;
+  hipLaunchKernelGGL(gat_scores_kernel, dim3((unsigned)ceil_div(n_vh, kBlock)), dim3(kBlock), 0, stream, H, a_src,
+                     a_dst, n_vh, heads, C, s_src, s_dst);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  for (size_t k = 0; k < launches.size(); ++k) {
+    int rc;
+    switch (args[k].sl.vec) {
+      case 1: rc = launch_gat<1>(args[k], grids[k], stream); break;
+      case 2: rc = launch_gat<2>(args[k], grids[k], stream); break;
+      default: rc = launch_gat<4>(args[k], grids[k], stream); break;
+    }
+    if (rc != GNNAGG_OK) return rc;
+  }
+  return GNNAGG_OK;
+}

@@ -1,0 +1,206 @@
+// Host-side scheduling shared by the aggregation and attention launches:
+// how a column range is cut into feature slices, and how the degree classes of
+// a row plan map onto lane groups.
+//
+// Feature decomposition (paper Algorithm 1) becomes a tiling of the launch
+// grid: a work item is (row group, feature slice), and the slices of one chunk
+// are enumerated chunk-major, so the hardware dispatcher walks the chunks in
+// the paper's chunk-outer / vertex-inner order and the rows of X touched at
+// any time are restricted to the current chunk's columns.
+#pragma once
+#include <vector>
+
+#include "common.hpp"
+
+namespace gnnagg {
+
+constexpr int kMaxSeg = 8;
+
+// A run of rows (positions in the row plan) handled with 2^lr_log2 lanes per
+// row: lr_log2 in [g_log2, 6] = that many lanes of one wave; 8 = a whole
+// 256-thread workgroup per row (hub rows; partials meet in LDS).
+struct Seg {
+  int32_t row_begin, row_end;
+  int32_t blk_begin;  // first workgroup of this run inside one slice's block range
+  int32_t lr_log2;
+};
+
+struct SegTable {
+  int32_t nseg;
+  uint32_t blocks_per_slice;
+  Seg seg[kMaxSeg];
+};
+
+// One launch: n_chunks chunks of equal width chunk_w starting every
+// chunk_stride columns from c_begin; each chunk is cut into n_sub slices of
+// sub_w columns (the last one may be narrower, never narrower than vec).
+// A lane owns vec consecutive columns; 2^g_log2 lanes span one slice.
+struct SliceLaunch {
+  int32_t c_begin, chunk_stride, chunk_w, n_chunks, sub_w, n_sub, vec, g_log2;
+};
+
+// What one thread of a launch does: which row (position in the plan), which
+// columns, which neighbour slot.  The same function runs in the kernels and in
+// the host-side coverage test.
+struct LaneRole {
+  int64_t ridx;   // position in the row plan (valid if row_ok)
+  int32_t col;    // first of the lane's vec columns
+  int32_t W;      // width of the slice this workgroup works on
+  int32_t ng;     // neighbour slot: the lane visits edges e0+ng, e0+ng+P, ...
+  int32_t P;      // neighbour slots per row
+  int32_t L;      // log2 lanes per row (8 = whole workgroup)
+  int32_t g;      // log2 lanes per slice
+  bool row_ok;    // the lane has a row
+  bool col_ok;    // the lane has columns
+  bool hub;       // the row owns the whole workgroup
+  bool writer;    // the lane stores the merged result for its columns
+};
+
+__host__ __device__ inline LaneRole lane_role(const SliceLaunch& sl, const SegTable& segs, uint32_t block,
+                                              int tid) {
+  LaneRole r;
+  const int lane = tid & (kWave - 1), wv = tid / kWave;
+  const uint32_t slice = block / segs.blocks_per_slice;
+  uint32_t lb = block - slice * segs.blocks_per_slice;
+  const int chunk = (int)(slice / (uint32_t)sl.n_sub);
+  const int sub = (int)(slice - (uint32_t)chunk * (uint32_t)sl.n_sub);
+  const int w_off = sub * sl.sub_w;
+  const int rest = sl.chunk_w - w_off;
+  r.W = sl.sub_w < rest ? sl.sub_w : rest;
+  const int c0 = sl.c_begin + chunk * sl.chunk_stride + w_off;
+
+  int32_t row_begin = segs.seg[0].row_begin, row_end = segs.seg[0].row_end;
+  int32_t blk_begin = segs.seg[0].blk_begin, L = segs.seg[0].lr_log2;
+#pragma unroll
+  for (int k = 1; k < kMaxSeg; ++k) {
+    if (k < segs.nseg && lb >= (uint32_t)segs.seg[k].blk_begin) {
+      row_begin = segs.seg[k].row_begin;
+      row_end = segs.seg[k].row_end;
+      blk_begin = segs.seg[k].blk_begin;
+      L = segs.seg[k].lr_log2;
+    }
+  }
+  lb -= (uint32_t)blk_begin;
+  r.L = L;
+  r.g = sl.g_log2;
+  r.hub = (L == 8);
+  int64_t slot;
+  int sub_lane;
+  if (r.hub) {
+    slot = lb;
+    sub_lane = tid;
+  } else {
+    slot = ((((int64_t)lb * kWavesPerBlock) + wv) << (6 - L)) + (lane >> L);
+    sub_lane = lane & ((1 << L) - 1);
+  }
+  const int gl = sub_lane & ((1 << r.g) - 1);  // position inside the slice
+  r.ng = sub_lane >> r.g;
+  r.P = (r.hub ? kBlock : (1 << L)) >> r.g;
+  r.ridx = (int64_t)row_begin + slot;
+  r.row_ok = r.ridx < (int64_t)row_end;
+  r.col_ok = sl.vec * gl < r.W;
+  // the last lane of a ragged slice re-reads the slice's final vec columns
+  const int shift = sl.vec * gl < r.W - sl.vec ? sl.vec * gl : r.W - sl.vec;
+  r.col = c0 + shift;
+  r.writer = r.row_ok && r.col_ok && r.ng == 0;
+  return r;
+}
+
+inline int pow2_ceil_log2(int64_t x) {
+  int l = 0;
+  while ((1ll << l) < x) ++l;
+  return l;
+}
+
+// Cuts [0,F) into chunks of width f_chunk (0 or >= F: one chunk) and every
+// chunk into slices of at most 64 lanes x vec columns.  max_vec is the widest
+// per-lane vector (16 bytes of input); vec_multiple forces vec to divide it
+// (attention: a lane must stay inside one head) or is 0.
+inline void plan_columns(int32_t F, int32_t f_chunk, int max_vec, int vec_multiple,
+                         std::vector<SliceLaunch>* out) {
+  out->clear();
+  const int32_t width = (f_chunk <= 0 || f_chunk >= F) ? F : f_chunk;
+  struct Group { int32_t c_begin, n_chunks, chunk_w; };
+  std::vector<Group> groups;
+  if (F / width > 0) groups.push_back({0, F / width, width});
+  if (F % width) groups.push_back({(F / width) * width, 1, F % width});
+  while (!groups.empty()) {
+    Group gr = groups.back();
+    groups.pop_back();
+    int vec = max_vec;
+    while (vec > 1 && (vec > gr.chunk_w || (vec_multiple && vec_multiple % vec))) vec >>= 1;
+    const int32_t cap = kWave * vec;
+    int32_t n_sub = (int32_t)ceil_div(gr.chunk_w, cap);
+    int32_t sub_w = (int32_t)(ceil_div(ceil_div(gr.chunk_w, n_sub), vec) * vec);
+    int32_t last = gr.chunk_w - (n_sub - 1) * sub_w;
+    if (last < vec) {  // balanced cut left a sliver: use full-width slices instead
+      sub_w = cap;
+      n_sub = (int32_t)ceil_div(gr.chunk_w, cap);
+      last = gr.chunk_w - (n_sub - 1) * sub_w;
+      if (last < vec) {  // give the sliver a launch of its own with a narrower vector
+        groups.push_back({gr.c_begin + (n_sub - 1) * sub_w, gr.n_chunks, last});
+        // the sliver repeats once per chunk, chunk_stride apart: keep the stride of the parent
+        groups.back().c_begin = gr.c_begin + (n_sub - 1) * sub_w;
+        gr.chunk_w = (n_sub - 1) * sub_w;
+        n_sub -= 1;
+      }
+    }
+    SliceLaunch sl;
+    sl.c_begin = gr.c_begin;
+    sl.chunk_stride = width;
+    sl.chunk_w = gr.chunk_w;
+    sl.n_chunks = gr.n_chunks;
+    sl.sub_w = sub_w;
+    sl.n_sub = n_sub;
+    sl.vec = vec;
+    sl.g_log2 = pow2_ceil_log2(ceil_div(sub_w, vec));
+    out->push_back(sl);
+  }
+}
+
+// Maps degree classes to lane groups for slices spanned by 2^g_log2 lanes.
+// A row of degree d gets about d/8 neighbour slots (a power of two) so that each
+// slot walks at least eight neighbours; beyond what a wave offers the row moves
+// to a whole workgroup.  Without a plan every row gets one wave.
+inline int build_segments(const int64_t* class_off, int64_t N, int g_log2, SegTable* t) {
+  t->nseg = 0;
+  int64_t blocks = 0;
+  auto rows_per_block = [](int L) -> int64_t { return L == 8 ? 1 : (int64_t)kWavesPerBlock << (6 - L); };
+  auto push = [&](int64_t rb, int64_t re, int L) {
+    if (re <= rb) return;
+    if (t->nseg > 0 && t->seg[t->nseg - 1].lr_log2 == L) {
+      // extend the previous run: recompute its block count
+      Seg& s = t->seg[t->nseg - 1];
+      blocks = s.blk_begin;
+      s.row_end = (int32_t)re;
+      blocks += ceil_div((int64_t)s.row_end - s.row_begin, rows_per_block(L));
+      return;
+    }
+    Seg& s = t->seg[t->nseg++];
+    s.row_begin = (int32_t)rb;
+    s.row_end = (int32_t)re;
+    s.blk_begin = (int32_t)blocks;
+    s.lr_log2 = L;
+    blocks += ceil_div(re - rb, rows_per_block(L));
+  };
+  if (!class_off) {
+    push(0, N, 6);
+  } else {
+    if (class_off[0] != 0 || class_off[GNNAGG_PLAN_CLASSES] != N) return GNNAGG_EINVAL;
+    for (int k = 0; k < GNNAGG_PLAN_CLASSES; ++k)
+      if (class_off[k] > class_off[k + 1]) return GNNAGG_EINVAL;
+    for (int k = 0; k < GNNAGG_PLAN_CLASSES; ++k) {
+      const int c = 32 - k;                      // rows with 2^(c-1) <= degree < 2^c
+      const int p_log2 = c >= 4 ? c - 4 : 0;     // neighbour slots wanted: degree / 8
+      int L = g_log2 + p_log2;
+      L = (L >= 8) ? 8 : (L > 6 ? 6 : L);
+      push(class_off[k], class_off[k + 1], L);
+      if (blocks > 0x7fffffffll) return GNNAGG_EUNSUPPORTED;
+    }
+  }
+  if (blocks > 0x7fffffffll) return GNNAGG_EUNSUPPORTED;
+  t->blocks_per_slice = (uint32_t)blocks;
+  return GNNAGG_OK;
+}
+
+}  // namespace gnnagg

@@ -1,0 +1,147 @@
+"""CPU-only checks of the GPU library's host side: the shared object loads and
+exports every symbol the header declares, argument validation answers before
+anything is launched, and the launch geometry (feature slices x degree-class
+lane groups) covers every output element and every edge exactly as intended."""
+import ctypes
+import os
+import re
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "gnnagg.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2104_03058_amd as g
+    from paper_2104_03058_amd import build
+    if not os.path.exists(g.library_path()):
+        build.build()
+    return g.load_library()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    return sorted(set(re.findall(r"GNNAGG_API\s+[\w\s\*]+?\b(gnnagg_\w+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary():
+    names = declared_symbols()
+    for must in ["gnnagg_build_csr", "gnnagg_aggregate", "gnnagg_gat_attention", "gnnagg_plan_rows",
+                 "gnnagg_strerror", "gnnagg_version"]:
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+
+
+def test_version_and_strerror(lib):
+    import paper_2104_03058_amd as g
+    assert g.gnnagg_version() >= 100
+    assert g.gnnagg_strerror(0) == "ok"
+    assert "invalid" in g.gnnagg_strerror(-1)
+    assert g.gnnagg_strerror(-99) == "unknown status"
+
+
+def test_argument_validation_returns_before_any_launch(lib):
+    """All of these are rejected on the host; no HIP call is reached, so they run without a GPU."""
+    EINVAL, ENULL, EUNSUP, EWS = -1, -2, -3, -4
+    one = ctypes.c_void_p(4096)  # a non-null, aligned stand-in pointer that is never dereferenced
+    agg = lib.gnnagg_aggregate
+    assert agg(7, 4, one, one, one, one, 0, one, 0, 8, 0, None, None, None) == EINVAL      # op
+    assert agg(0, -1, one, one, one, one, 0, one, 0, 8, 0, None, None, None) == EINVAL     # N
+    assert agg(0, 4, one, one, one, one, 0, one, 0, 0, 0, None, None, None) == EINVAL      # F
+    assert agg(0, 4, one, one, one, one, 0, one, 0, 8, -2, None, None, None) == EINVAL     # f_chunk
+    assert agg(0, 4, one, one, one, one, 5, one, 0, 8, 0, None, None, None) == EINVAL      # x_dtype
+    assert agg(0, 4, one, one, one, one, 0, one, 1, 8, 0, None, None, None) == EUNSUP      # bf16 output
+    assert agg(0, 4, None, one, one, one, 0, one, 0, 8, 0, None, None, None) == ENULL      # rowptr
+    assert agg(1, 4, one, one, None, one, 0, one, 0, 8, 0, None, None, None) == ENULL      # wsum needs edge_w
+    assert agg(0, 4, one, one, one, one, 0, one, 0, 8, 0, one, None, None) == EINVAL       # half a plan
+    assert agg(0, 4, one, one, one, one, 0, one, 0, 8, 0, None, None, None) == EINVAL      # X aliases out
+    assert agg(0, 4, one, one, one, ctypes.c_void_p(4098), 0, one, 0, 8, 0, None, None, None) == EINVAL  # alignment
+    assert agg(0, 0, None, None, None, None, 0, None, 0, 8, 0, None, None, None) == 0      # empty graph: nothing to do
+
+    need = ctypes.c_size_t(0)
+    csr = lib.gnnagg_build_csr
+    assert csr(-1, 0, None, None, 0, None, None, None, None, None, ctypes.byref(need), None) == EINVAL
+    assert csr(4, 2, None, None, 8, None, None, None, None, None, ctypes.byref(need), None) == EINVAL  # flags
+    assert csr(4, 2, None, None, 0, None, None, None, None, None, None, None) == ENULL
+    assert csr(4, 1 << 32, None, None, 0, None, None, None, None, None, ctypes.byref(need), None) == EUNSUP
+    assert csr(4, 2, None, None, 0, None, None, None, None, None, ctypes.byref(need), None) == 0
+    assert need.value > 0 and need.value % 256 == 0
+    small = ctypes.c_size_t(16)
+    assert csr(4, 2, one, one, 0, one, one, None, None, one, ctypes.byref(small), None) == EWS
+    big = ctypes.c_size_t(need.value)
+    assert csr(4, 2, one, one, 0, one, one, None, None, ctypes.c_void_p(4097), ctypes.byref(big), None) == EWS
+    assert csr(4, 2, None, one, 0, one, one, None, None, one, ctypes.byref(big), None) == ENULL
+
+    plan = lib.gnnagg_plan_rows
+    assert plan(-3, None, None, None, None, ctypes.byref(need), None) == EINVAL
+    assert plan(10, None, None, None, None, ctypes.byref(need), None) == 0 and need.value > 0
+
+    gat = lib.gnnagg_gat_attention
+    f = ctypes.c_float(0.2)
+    assert gat(4, one, one, one, one, one, 0, 8, f, None, one, 0, None, None, None, ctypes.byref(need), None) == EINVAL
+    assert gat(4, one, one, one, one, one, 8, 8, f, None, one, 12, None, None, None, ctypes.byref(need), None) == EINVAL
+    assert gat(4, one, one, one, one, one, 8, 8, f, None, one, 16, None, None, None, ctypes.byref(need), None) == 0
+    assert need.value >= 2 * 4 * 8 * 4
+    assert gat(4, one, one, one, one, one, 8, 8, f, None, one, 0, None, None, one, ctypes.byref(small), None) == EWS
+
+
+# ------------------------------------------------------------------ launch geometry
+@pytest.fixture(scope="module")
+def checker(tmp_path_factory):
+    exe = str(tmp_path_factory.mktemp("host") / "schedule_check")
+    subprocess.check_call(["g++", "-O1", "-std=c++17", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
+                           "-I" + os.path.join(ROOT, "include"),
+                           "-I" + os.path.join(ROOT, "paper_2104_03058_amd", "csrc"),
+                           os.path.join(ROOT, "tests", "host", "schedule_check.cpp"), "-o", exe])
+    return exe
+
+
+def run_checker(exe, F, f_chunk, max_vec, vec_multiple, N, class_counts=None):
+    args = [exe, str(F), str(f_chunk), str(max_vec), str(vec_multiple), str(N), "1" if class_counts else "0"]
+    if class_counts:
+        args += [str(c) for c in class_counts]
+    p = subprocess.run(args, capture_output=True, text=True)
+    assert p.returncode == 0 and p.stdout.startswith("OK"), (args, p.stdout, p.stderr)
+
+
+def counts(N, spread):
+    """rows per class 32..0: `spread` maps class -> rows, the rest go to class 1."""
+    c = [0] * 33
+    used = 0
+    for cls, n in spread.items():
+        c[32 - cls] = n
+        used += n
+    c[32 - 1] += N - used
+    assert c[32 - 1] >= 0
+    return c
+
+
+@pytest.mark.parametrize("F,f_chunk,max_vec", [
+    (1433, 0, 4), (1433, 16, 4), (1433, 64, 4),          # config 1 sweep (ragged last chunk of width 9)
+    (500, 0, 4), (602, 0, 4), (602, 8, 4), (602, 16, 4), (602, 32, 4), (602, 64, 4),
+    (100, 0, 8), (16, 0, 8), (32, 0, 8), (100, 7, 8),    # bf16 widths; a chunk narrower than the vector
+    (1, 0, 4), (3, 0, 4), (5, 2, 4), (257, 0, 4), (2051, 0, 8), (513, 512, 8),
+])
+def test_geometry_without_plan(checker, F, f_chunk, max_vec):
+    run_checker(checker, F, f_chunk, max_vec, 0, 37)
+
+
+@pytest.mark.parametrize("F,f_chunk,max_vec", [(602, 0, 4), (602, 64, 4), (100, 0, 8), (16, 0, 8), (9, 4, 4), (64, 8, 4)])
+def test_geometry_with_degree_classes(checker, F, f_chunk, max_vec):
+    N = 300
+    cc = counts(N, {0: 7, 2: 40, 3: 33, 4: 29, 5: 21, 6: 17, 7: 13, 8: 9, 9: 6, 11: 5, 15: 3, 32: 1})
+    run_checker(checker, F, f_chunk, max_vec, 0, N, cc)
+
+
+@pytest.mark.parametrize("heads,C,f_chunk", [(8, 8, 0), (8, 8, 8), (8, 8, 16), (3, 5, 0), (4, 6, 12), (40, 8, 0)])
+def test_geometry_attention_lanes_stay_inside_heads(checker, heads, C, f_chunk):
+    N = 120
+    cc = counts(N, {0: 3, 2: 30, 4: 20, 6: 10, 9: 4, 13: 2})
+    run_checker(checker, heads * C, f_chunk, 4, C, N, cc)

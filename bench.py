@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the aggregation hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4-gcn] [--f-chunk C]
+
+A step is one gnnagg_aggregate call (chunk addressing, gather, reduce, in-place
+concat) over the whole synthetic graph, with the CSR, the row plan and the
+features already resident in HBM.  The CSR build and the row plan are per-graph
+steps; they are timed separately and reported under "setup".  Prints one JSON
+line: edge-features/s, the HBM roofline of the aggregation kernel (algorithmic
+bytes / HIP-event time, peak 8 TB/s) and the CPU checker timed on the host
+cores on a bounded sample of destination rows of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+
+WORKLOADS = {
+    # name: (graph key, op, F, feature dtype, self loops + GCN norm)
+    "c4-gcn": ("c4", "wsum", 602, "f32", True),
+    "c4-mean": ("c4", "mean", 602, "f32", False),
+    "c5-sum": ("c5", "sum", 100, "bf16", False),
+    "c5-max": ("c5", "max", 100, "bf16", False),
+    "c5-sum-f32": ("c5", "sum", 32, "bf16", False),
+    "c5-sum-f16": ("c5", "sum", 16, "bf16", False),
+    "c2-mean": ("c2", "mean", 500, "f32", False),
+    "c1-gcn": ("c1", "wsum", 1433, "f32", True),
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(nnz, N, F, x_bytes, weighted, f_chunk):
+    """Bytes the method itself has to move per call: every neighbour-row slice once per edge, the
+    index (and weight) of every edge once per chunk pass, every output element once, the row
+    pointers once per chunk pass."""
+    P = 1 if (f_chunk <= 0 or f_chunk >= F) else -(-F // f_chunk)
+    return nnz * F * x_bytes + P * nnz * (4 + (4 if weighted else 0)) + N * F * 4 + P * (N + 1) * 8
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c4-gcn", choices=sorted(WORKLOADS))
+    ap.add_argument("--f-chunk", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    import paper_2104_03058_amd as g
+    import workloads as W
+    g.load_library()
+
+    gkey, opname, F, xdt, gcn = WORKLOADS[args.workload]
+    t0 = time.time()
+    N, src, dst = W.graph(gkey)
+    log("graph %s: N=%d directed edges=%d (%.1fs)" % (gkey, N, len(src), time.time() - t0))
+    t0 = time.time()
+    X = W.normal_bf16((N, F), seed=13) if xdt == "bf16" else (
+        W.bernoulli_f32((N, F), 0.013, seed=13) if gkey == "c1" else W.normal_f32((N, F), seed=13))
+    log("features [%d,%d] %s (%.1fs)" % (N, F, xdt, time.time() - t0))
+
+    def dev(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    d_src, d_dst, d_X = dev(src), dev(dst), dev(X)
+    flags = (g.SELF_LOOPS | g.NORM_SYM) if gcn else 0
+    # ---- per-graph setup: CSR build and row plan (timed, not part of a step)
+    g.gnnagg_build_csr(N, d_src, d_dst, flags, want_w=gcn)  # warm-up (allocator, code objects)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    d_rp, d_ci, d_w, _ = g.gnnagg_build_csr(N, d_src, d_dst, flags, want_w=gcn)
+    torch.cuda.synchronize()
+    t_csr = time.time() - t0
+    t0 = time.time()
+    plan = g.gnnagg_plan_rows(d_rp)
+    torch.cuda.synchronize()
+    t_plan = time.time() - t0
+    del d_src, d_dst
+    nnz = int(d_ci.shape[0])
+    log("device CSR build %.1f ms, row plan %.1f ms, nnz=%d" % (t_csr * 1e3, t_plan * 1e3, nnz))
+
+    op = {"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname]
+    out = torch.empty((N, F), dtype=torch.float32, device="cuda")
+
+    def step():
+        g.gnnagg_aggregate(op, d_rp, d_ci, d_w, d_X, out, args.f_chunk, plan)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # whole timed region: wall clock around K steps; per-step kernel time: HIP events on the launch stream
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = np.array([a.elapsed_time(b) for a, b in ev])
+    ms_per_step = wall * 1e3 / args.steps
+    edge_features = float(nnz) * F
+    x_bytes = 2 if xdt == "bf16" else 4
+    b_alg = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", args.f_chunk)
+    kern_ms = float(ms.mean())
+    achieved = b_alg / (kern_ms * 1e-3) / 1e9
+    log("step %.3f ms wall, kernel mean %.3f ms (min %.3f), %.3e edge-features/s, %.0f GB/s algorithmic" %
+        (ms_per_step, kern_ms, ms.min(), edge_features / (ms_per_step * 1e-3), achieved))
+
+    # ---- CPU checker on the host cores: bounded sample of destination rows, also the parity check
+    cpu = None
+    parity = None
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
+        t0 = time.time()
+        rp, ci, w, _ = oracle.build_csr(N, src, dst, flags, want_w=gcn, threads=threads)
+        log("checker CSR build %.1fs on %d threads" % (time.time() - t0, threads))
+        rop = {"sum": oracle.SUM, "wsum": oracle.WSUM, "mean": oracle.MEAN, "max": oracle.MAX}[opname]
+        rng = np.random.default_rng(0)
+        deg = np.diff(rp)
+        probe = np.sort(rng.choice(N, size=min(N, 256), replace=False)).astype(np.int64)
+        t0 = time.time()
+        oracle.aggregate_rows(rop, probe, rp, ci, w, X, threads=threads)
+        rate = max(float(deg[probe].sum()) * F / max(time.time() - t0, 1e-4), 1.0)
+        want = args.cpu_seconds * rate / F  # edges to cover in about cpu_seconds
+        nrows = int(min(N, max(256, want / max(deg.mean(), 1.0))))
+        rows = np.sort(rng.choice(N, size=nrows, replace=False)).astype(np.int64)
+        t0 = time.time()
+        ref = oracle.aggregate_rows(rop, rows, rp, ci, w, X, threads=threads)
+        dt = time.time() - t0
+        ef = float(deg[rows].sum()) * F
+        cpu = {"value": ef / dt, "unit": "edge-features/s", "cores": threads, "kind": "oracle",
+               "sample": "%d random destination rows of %s (%.3g edge-features, %.1f s)" % (nrows, args.workload, ef, dt)}
+        got = out[torch.from_numpy(rows).cuda()].cpu().numpy()
+        tol = 1e-2 if xdt == "bf16" else 1e-5
+        if opname == "max":
+            parity = bool(np.array_equal(got.view(np.uint32), ref.view(np.uint32)))
+        else:
+            parity = bool(np.all(np.abs(got.astype(np.float64) - ref) <= 1e-6 + tol * np.abs(ref)))
+        log("checker: %.3e edge-features/s on %d threads; parity on the sample: %s" % (cpu["value"], threads, parity))
+
+    rec = {
+        "metric": "aggregated edge-features/sec", "value": edge_features / (ms_per_step * 1e-3),
+        "unit": "edge-features/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if xdt == "f32" else "bf16-in/f32-acc", "data": "synthetic",
+        "config": {"workload": args.workload, "graph": W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "op": opname,
+                   "f_chunk": args.f_chunk, "x_dtype": xdt},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "aggregate_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": b_alg},
+        "cpu_baseline": cpu,
+        "parity_on_sample": parity,
+        "setup": {"csr_build_ms": t_csr * 1e3, "row_plan_ms": t_plan * 1e3},
+    }
+    print(json.dumps(rec), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -128,8 +128,9 @@ GNNAGG_API int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
  *            correct for any graph, slow on hub rows).  class_off is a HOST
  *            pointer and is read before the call returns.
  *
- * Sums are compensated, so every element is within a few fp32 ulp of the
- * exactly rounded result whatever the degree; max is exact.  No atomics are
+ * Sums accumulate in fp64 and are rounded to fp32 once, so every element is
+ * the correctly rounded sum up to fp64 reordering effects, whatever the degree;
+ * max is exact.  No atomics are
  * used: results are bit-reproducible from run to run.
  */
 GNNAGG_API int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* edge_w,

@@ -13,8 +13,8 @@
 //   - Slices are enumerated chunk-major over the grid, so chunks run in the
 //     chunk-outer / vertex-inner order of Algorithm 1 and each slice is written
 //     straight into its columns of `out` (the Concat step costs nothing).
-//   - Sums carry a compensation term per column (hi + lo), also through the
-//     merges, so the result does not depend on the degree or on how the row was
+//   - Sums accumulate in fp64 (full rate on this chip) and are rounded to fp32
+//     once, so the result does not depend on the degree or on how the row was
 //     split; max works on order-preserving integer keys and is exact.
 #include "common.hpp"
 #include "schedule.hpp"
@@ -47,63 +47,89 @@ __device__ inline int32_t order_key(float f) {
 }
 __device__ inline float key_value(int32_t k) { return __int_as_float(k ^ ((k >> 31) & 0x7fffffff)); }
 
-// Per-lane reduction state for VEC columns.
+// Per-lane reduction state for VEC columns.  Sums accumulate in fp64: on this
+// hardware the fp64 vector pipe runs at the same rate as unpacked fp32, the
+// product of two fp32 values is exact in fp64, and a sum of 2^32 fp32 terms
+// keeps ~20 guard bits, so the value rounded to fp32 at the end does not
+// depend on the degree of the row or on how the row was split over lanes.
 template <int OPK, int VEC>
 struct State {
-  float hi[VEC];  // running sum            | max: key bits
-  float lo[VEC];  // running compensation   | max: unused
+  double acc[VEC];
   __device__ inline void init() {
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) {
-      hi[k] = (OPK == OPK_MAX) ? __int_as_float((int32_t)0x80000000) : 0.0f;
-      lo[k] = 0.0f;
-    }
+    for (int k = 0; k < VEC; ++k) acc[k] = 0.0;
   }
   __device__ inline void add(const float (&v)[VEC], float w) {
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
-      if (OPK == OPK_MAX) {
-        const int32_t a = __float_as_int(hi[k]), b = order_key(v[k]);
-        hi[k] = __int_as_float(a > b ? a : b);
-      } else {
-        // compensated accumulation: hi + lo tracks the exact running sum
-        const float y = (OPK == OPK_WSUM) ? __builtin_fmaf(w, v[k], lo[k]) : v[k] + lo[k];
-        const float t = hi[k] + y;
-        lo[k] = y - (t - hi[k]);
-        hi[k] = t;
-      }
+      if (OPK == OPK_WSUM) acc[k] = __builtin_fma((double)w, (double)v[k], acc[k]);
+      else acc[k] += (double)v[k];
     }
   }
   __device__ inline void merge(const State& o) {
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) {
-      if (OPK == OPK_MAX) {
-        const int32_t a = __float_as_int(hi[k]), b = __float_as_int(o.hi[k]);
-        hi[k] = __int_as_float(a > b ? a : b);
-      } else {
-        // error-free addition of the two running sums; the rounding error joins the compensation
-        const float t = hi[k] + o.hi[k];
-        const float bb = t - hi[k];
-        const float err = (hi[k] - (t - bb)) + (o.hi[k] - bb);
-        lo[k] = (lo[k] + o.lo[k]) + err;
-        hi[k] = t;
-      }
-    }
+    for (int k = 0; k < VEC; ++k) acc[k] += o.acc[k];
   }
   __device__ inline State shuffled_xor(int stride) const {
     State o;
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) {
-      o.hi[k] = __shfl_xor(hi[k], stride, kWave);
-      if (OPK != OPK_MAX) o.lo[k] = __shfl_xor(lo[k], stride, kWave);
-    }
+    for (int k = 0; k < VEC; ++k) o.acc[k] = __shfl_xor(acc[k], stride, kWave);
     return o;
   }
+  __device__ inline void park(double* slot) const {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) slot[k] = acc[k];
+  }
+  __device__ inline void unpark(const double* slot) {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) acc[k] = slot[k];
+  }
+  __device__ inline float result(int k, int64_t deg, bool mean) const {
+    return (float)((mean && deg > 0) ? acc[k] / (double)deg : acc[k]);
+  }
+};
+
+// max: integer keys, exact and independent of the order of the operands
+template <int VEC>
+struct State<OPK_MAX, VEC> {
+  int32_t key[VEC];
+  __device__ inline void init() {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) key[k] = (int32_t)0x80000000;
+  }
+  __device__ inline void add(const float (&v)[VEC], float) {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      const int32_t b = order_key(v[k]);
+      key[k] = key[k] > b ? key[k] : b;
+    }
+  }
+  __device__ inline void merge(const State& o) {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) key[k] = key[k] > o.key[k] ? key[k] : o.key[k];
+  }
+  __device__ inline State shuffled_xor(int stride) const {
+    State o;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) o.key[k] = __shfl_xor(key[k], stride, kWave);
+    return o;
+  }
+  __device__ inline void park(double* slot) const {
+    int32_t* p = reinterpret_cast<int32_t*>(slot);
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) p[k] = key[k];
+  }
+  __device__ inline void unpark(const double* slot) {
+    const int32_t* p = reinterpret_cast<const int32_t*>(slot);
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) key[k] = p[k];
+  }
+  __device__ inline float result(int k, int64_t deg, bool) const { return deg > 0 ? key_value(key[k]) : 0.0f; }
 };
 
 template <typename T, int OPK, int VEC>
 __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
-  __shared__ float lds[(kWavesPerBlock - 1) * kWave * 2 * VEC];
+  __shared__ double lds[(kWavesPerBlock - 1) * kWave * VEC];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
 
   const LaneRole role = lane_role(a.sl, a.segs, blockIdx.x, tid);
@@ -152,24 +178,12 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
   if (hub) {
     // lanes [0, 2^g) of each wave now hold that wave's partial for their columns (if 2^g < 64);
     // waves 1..3 park theirs in LDS, wave 0 folds them in wave order
-    if (wv > 0) {
-      float* slotp = lds + ((wv - 1) * kWave + lane) * 2 * VEC;
-#pragma unroll
-      for (int k = 0; k < VEC; ++k) {
-        slotp[k] = st.hi[k];
-        slotp[VEC + k] = st.lo[k];
-      }
-    }
+    if (wv > 0) st.park(lds + ((wv - 1) * kWave + lane) * VEC);
     __syncthreads();
     if (wv == 0) {
       for (int ww = 1; ww < kWavesPerBlock; ++ww) {
-        const float* slotp = lds + ((ww - 1) * kWave + lane) * 2 * VEC;
         State<OPK, VEC> o;
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) {
-          o.hi[k] = slotp[k];
-          o.lo[k] = slotp[VEC + k];
-        }
+        o.unpark(lds + ((ww - 1) * kWave + lane) * VEC);
         st.merge(o);
       }
     }
@@ -179,14 +193,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
   if (role.writer) {
     float res[VEC];
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) {
-      if (OPK == OPK_MAX) {
-        res[k] = deg > 0 ? key_value(__float_as_int(st.hi[k])) : 0.0f;
-      } else {
-        const float s = st.hi[k] + st.lo[k];
-        res[k] = (a.mean && deg > 0) ? s / (float)deg : s;
-      }
-    }
+    for (int k = 0; k < VEC; ++k) res[k] = st.result(k, deg, a.mean != 0);
     store_row<VEC>(a.out + r * a.F + col, res);
   }
 }

@@ -46,45 +46,45 @@ __global__ __launch_bounds__(kBlock) void gat_scores_kernel(const float* __restr
   const float* __restrict__ x = H + t * C;
   const float* __restrict__ as = a_src + (int64_t)h * C;
   const float* __restrict__ ad = a_dst + (int64_t)h * C;
-  float s = 0.0f, d = 0.0f;
+  double s = 0.0, d = 0.0;  // fp64 dot product, rounded once
   for (int c = 0; c < C; ++c) {
-    const float v = x[c];
-    s = __builtin_fmaf(as[c], v, s);
-    d = __builtin_fmaf(ad[c], v, d);
+    const double v = (double)x[c];
+    s = __builtin_fma((double)as[c], v, s);
+    d = __builtin_fma((double)ad[c], v, d);
   }
-  s_src[t] = s;
-  s_dst[t] = d;
+  s_src[t] = (float)s;
+  s_dst[t] = (float)d;
 }
 
 template <int VEC>
 struct SoftState {
-  float m;         // running maximum of the logits seen
-  float l;         // sum of exp(logit - m)
-  float acc[VEC];  // sum of exp(logit - m) * H
+  float m;          // running maximum of the logits seen
+  double l;         // sum of exp(logit - m)
+  double acc[VEC];  // sum of exp(logit - m) * H   (fp64: hub rows add thousands of terms)
   __device__ inline void init() {
     m = -INFINITY;
-    l = 0.0f;
+    l = 0.0;
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) acc[k] = 0.0f;
+    for (int k = 0; k < VEC; ++k) acc[k] = 0.0;
   }
   __device__ inline void add(float logit, const float (&v)[VEC]) {
     const float d = logit - m;
-    const float ex = expf(-fabsf(d));  // exp of the smaller minus the larger; exp(-inf) = 0 on the first edge
+    const double ex = (double)expf(-fabsf(d));  // exp(smaller - larger); exp(-inf) = 0 on the first edge
     if (d > 0.0f) {
-      l = __builtin_fmaf(l, ex, 1.0f);
+      l = __builtin_fma(l, ex, 1.0);
 #pragma unroll
-      for (int k = 0; k < VEC; ++k) acc[k] = __builtin_fmaf(acc[k], ex, v[k]);
+      for (int k = 0; k < VEC; ++k) acc[k] = __builtin_fma(acc[k], ex, (double)v[k]);
       m = logit;
     } else {
       l += ex;
 #pragma unroll
-      for (int k = 0; k < VEC; ++k) acc[k] = __builtin_fmaf(ex, v[k], acc[k]);
+      for (int k = 0; k < VEC; ++k) acc[k] = __builtin_fma(ex, (double)v[k], acc[k]);
     }
   }
   __device__ inline void merge(const SoftState& o) {
     const float mm = fmaxf(m, o.m);
-    const float sa = (m == mm) ? 1.0f : expf(m - mm);
-    const float sb = (o.m == mm) ? 1.0f : expf(o.m - mm);
+    const double sa = (m == mm) ? 1.0 : (double)expf(m - mm);
+    const double sb = (o.m == mm) ? 1.0 : (double)expf(o.m - mm);
     l = l * sa + o.l * sb;
 #pragma unroll
     for (int k = 0; k < VEC; ++k) acc[k] = acc[k] * sa + o.acc[k] * sb;
@@ -102,8 +102,8 @@ struct SoftState {
 
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) {
-  __shared__ float lds[(kWavesPerBlock - 1) * kWave * (2 + VEC)];
-  __shared__ float fin[2 * kWave];
+  __shared__ double lds[(kWavesPerBlock - 1) * kWave * (2 + VEC)];
+  __shared__ double fin[2 * kWave];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
 
   const LaneRole role = lane_role(a.sl, a.segs, blockIdx.x, tid);
@@ -154,8 +154,8 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
   for (int stride = 1 << g; stride < lanes_in_wave; stride <<= 1) st.merge(st.shuffled_xor(stride));
   if (hub) {
     if (wv > 0) {
-      float* p = lds + ((wv - 1) * kWave + lane) * (2 + VEC);
-      p[0] = st.m;
+      double* p = lds + ((wv - 1) * kWave + lane) * (2 + VEC);
+      p[0] = (double)st.m;
       p[1] = st.l;
 #pragma unroll
       for (int k = 0; k < VEC; ++k) p[2 + k] = st.acc[k];
@@ -163,26 +163,26 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
     __syncthreads();
     if (wv == 0) {
       for (int ww = 1; ww < kWavesPerBlock; ++ww) {
-        const float* p = lds + ((ww - 1) * kWave + lane) * (2 + VEC);
+        const double* p = lds + ((ww - 1) * kWave + lane) * (2 + VEC);
         SoftState<VEC> o;
-        o.m = p[0];
+        o.m = (float)p[0];
         o.l = p[1];
 #pragma unroll
         for (int k = 0; k < VEC; ++k) o.acc[k] = p[2 + k];
         st.merge(o);
       }
-      fin[lane] = st.m;
+      fin[lane] = (double)st.m;
       fin[kWave + lane] = st.l;
     }
     __syncthreads();
-    st.m = fin[lane];  // every wave now knows the row's final maximum and denominator
+    st.m = (float)fin[lane];  // every wave now knows the row's final maximum and denominator
     st.l = fin[kWave + lane];
   }
 
   if (a.out && role.writer) {
     float res[VEC];
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) res[k] = (e1 > e0) ? st.acc[k] / st.l : 0.0f;
+    for (int k = 0; k < VEC; ++k) res[k] = (e1 > e0) ? (float)(st.acc[k] / st.l) : 0.0f;
     store_row<VEC>(a.out + r * HC + col, res);
   }
   // softmax weights, written by the first lane of every head
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
     for (int64_t e = e0 + ng; e < e1; e += P) {
       const float s = a.s_src[(int64_t)a.colidx[e] * a.heads + head] + sd;
       const float logit = s >= 0.0f ? s : a.slope * s;
-      a.alpha[e * a.heads + head] = expf(logit - st.m) / st.l;
+      a.alpha[e * a.heads + head] = (float)((double)expf(logit - st.m) / st.l);
     }
   }
 }

@@ -1,0 +1,82 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration the
+benchmark times (device-built CSR, row plan, one chunk): the CSR is compared
+bit for bit with the CPU checker's, the aggregation on sampled destination rows
+that the checker computes one by one (hubs, median rows and empty rows)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as W
+from test_gpu_parity import assert_bits, assert_close, dev, host, say
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(rp, n=96, seed=0):
+    deg = np.diff(rp)
+    order = np.argsort(-deg, kind="stable")
+    rng = np.random.default_rng(seed)
+    pick = list(order[:8]) + list(order[-4:]) + list(order[len(order) // 2 - 4:len(order) // 2 + 4])
+    pick += list(rng.choice(len(deg), size=n - len(pick), replace=False))
+    return np.unique(np.array(pick, np.int64))
+
+
+def test_config4_full_size_gcn_and_mean():
+    import paper_2104_03058_amd as g
+    N, src, dst = W.graph("c4")
+    say("c4 full: N", N, "E", len(src))
+    flags = oracle.SELF_LOOPS | oracle.NORM_SYM
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, flags, want_w=True, threads=16)
+    say("c4 full: checker CSR done, nnz", len(ci), "max deg", int(np.diff(rp).max()))
+    d_rp, d_ci, d_w, _ = g.gnnagg_build_csr(N, dev(src), dev(dst), flags, want_w=True)
+    assert np.array_equal(host(d_rp), rp) and np.array_equal(host(d_ci), ci)
+    assert_bits(host(d_w), w, "edge_w")
+    say("c4 full: device CSR matches bit for bit")
+    X = W.normal_f32((N, 602), seed=13)
+    d_X = dev(X)
+    plan = g.gnnagg_plan_rows(d_rp)
+    rows = sample_rows(rp)
+    for fc in (0, 64):
+        say("c4 full: wsum f_chunk", fc)
+        out = g.gnnagg_aggregate(g.WSUM, d_rp, d_ci, d_w, d_X, None, fc, plan)
+        got = host(out[torch.from_numpy(rows).cuda()])
+        ref = oracle.aggregate_rows(oracle.WSUM, rows, rp, ci, w, X, threads=16)
+        assert_close(got, ref, what="c4 wsum fc=%d" % fc)
+        del out
+    say("c4 full: mean")
+    out = g.gnnagg_aggregate(g.MEAN, d_rp, d_ci, None, d_X, None, 0, plan)
+    got = host(out[torch.from_numpy(rows).cuda()])
+    ref = oracle.aggregate_rows(oracle.MEAN, rows, rp, ci, None, X, threads=16)
+    assert_close(got, ref, what="c4 mean")
+    # property that holds at any size: the all-ones matrix aggregates to the row degree, exactly
+    ones = torch.ones((N, 8), dtype=torch.float32, device="cuda")
+    deg = host(g.gnnagg_aggregate(g.SUM, d_rp, d_ci, None, ones, None, 0, plan))
+    assert np.array_equal(deg[:, 0], np.diff(rp).astype(np.float32)) and np.array_equal(deg[:, 7], deg[:, 0])
+
+
+@pytest.mark.parametrize("F", [100, 32, 16])
+def test_config5_full_size_bf16_sum_and_max(F):
+    import paper_2104_03058_amd as g
+    N, src, dst = W.graph("c5")
+    say("c5 full: N", N, "E", len(src), "F", F)
+    rp, ci, _, _ = oracle.build_csr(N, src, dst, 0, threads=16)
+    d_rp, d_ci, _, _ = g.gnnagg_build_csr(N, dev(src), dev(dst), 0)
+    assert np.array_equal(host(d_rp), rp) and np.array_equal(host(d_ci), ci)
+    X = W.normal_bf16((N, F), seed=14 + F)
+    d_X = dev(X)
+    plan = g.gnnagg_plan_rows(d_rp)
+    rows = sample_rows(rp, n=256)
+    idx = torch.from_numpy(rows).cuda()
+    for name, gop, rop in (("sum", g.SUM, oracle.SUM), ("max", g.MAX, oracle.MAX)):
+        say("c5 full:", name)
+        out = g.gnnagg_aggregate(gop, d_rp, d_ci, None, d_X, None, 0, plan)
+        got = host(out[idx])
+        ref = oracle.aggregate_rows(rop, rows, rp, ci, None, X, threads=16)
+        if name == "max":
+            assert_bits(got, ref, "c5 max F=%d" % F)
+        else:
+            assert_close(got, ref, bf16=True, what="c5 sum F=%d" % F)
+        del out

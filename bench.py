@@ -53,7 +53,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c4-gcn", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="c4-gcn", choices=sorted(WORKLOADS) + ["copy"],
+                    help="'copy' runs only the library's plain copy kernel on 1 GiB (profiler calibration)")
     ap.add_argument("--f-chunk", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -67,6 +68,29 @@ def main():
     import paper_2104_03058_amd as g
     import workloads as W
     g.load_library()
+
+    # plain streaming copy of 1 GiB: the measured HBM copy rate of this device, reported beside the roofline
+    probe_bytes = 1 << 30
+    p_src = torch.empty(probe_bytes, dtype=torch.uint8, device="cuda").fill_(1)
+    p_dst = torch.empty_like(p_src)
+    g.gnnagg_copy_probe(p_dst, p_src)
+    torch.cuda.synchronize()
+    n_probe = max(args.steps, 3) if args.workload == "copy" else 5
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n_probe):
+        g.gnnagg_copy_probe(p_dst, p_src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_ms = e0.elapsed_time(e1) / n_probe
+    copy_gbs = 2.0 * probe_bytes / (copy_ms * 1e-3) / 1e9
+    log("copy probe: 1 GiB in %.3f ms -> %.0f GB/s read+write" % (copy_ms, copy_gbs))
+    del p_src, p_dst
+    if args.workload == "copy":
+        print(json.dumps({"metric": "hbm copy rate", "value": copy_gbs, "unit": "GB/s", "n_gpus": 1,
+                          "steps": n_probe, "ms_per_step": copy_ms, "bytes_read": probe_bytes,
+                          "bytes_written": probe_bytes, "config": {"workload": "copy"}}), flush=True)
+        return
 
     gkey, opname, F, xdt, gcn = WORKLOADS[args.workload]
     t0 = time.time()
@@ -169,7 +193,8 @@ def main():
                    "f_chunk": args.f_chunk, "x_dtype": xdt},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "aggregate_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": b_alg},
+                     "kernel": "aggregate_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": b_alg,
+                     "measured_copy_gbs": copy_gbs},
         "cpu_baseline": cpu,
         "parity_on_sample": parity,
         "setup": {"csr_build_ms": t_csr * 1e3, "row_plan_ms": t_plan * 1e3},

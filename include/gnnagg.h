@@ -160,6 +160,15 @@ GNNAGG_API int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
                          const int32_t* row_order, const int64_t* class_off, void* workspace,
                          size_t* workspace_bytes, void* stream);
 
+/*
+ * Measurement aid, not part of the method: copies `bytes` bytes (a multiple of
+ * 16, both pointers 16-byte aligned, buffers disjoint) from src to dst with a
+ * plain streaming kernel on `stream`.  Its HBM traffic is known exactly (bytes
+ * read + bytes written), which gives the achievable copy rate of the device and
+ * the scale of the profiler's byte counters next to the aggregation kernels.
+ */
+GNNAGG_API int gnnagg_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -58,6 +58,8 @@ def load_library():
         lib.gnnagg_gat_attention.restype = ci
         lib.gnnagg_gat_attention.argtypes = [i64, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp, i32, vp, vp, vp, szp,
                                              vp]
+        lib.gnnagg_copy_probe.restype = ci
+        lib.gnnagg_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         _lib = lib
     return _lib
 
@@ -213,3 +215,11 @@ def gnnagg_gat_attention(rowptr: torch.Tensor, colidx: torch.Tensor, H: torch.Te
     # the score arrays in ws are read by the kernels just enqueued: keep ws alive until they ran
     ws.record_stream(torch.cuda.current_stream() if stream is None else stream)
     return alpha, out
+
+
+def gnnagg_copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """Plain streaming copy of src into dst (same byte size): the measurement aid of the library."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("dst and src differ in size")
+    _check("gnnagg_copy_probe", load_library().gnnagg_copy_probe(_dev(dst), _dev(src), nbytes, _stream(stream)))

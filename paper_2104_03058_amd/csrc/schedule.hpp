@@ -203,4 +203,38 @@ inline int build_segments(const int64_t* class_off, int64_t N, int g_log2, SegTa
   return GNNAGG_OK;
 }
 
+// How many workgroups of the aggregation kernel should share a compute unit.  Every resident wave
+// keeps eight row gathers in flight, and every line in flight occupies L2; at full occupancy the lines
+// in flight alone (256 CUs x 16-20 waves x 8 x ~7 lines x 128 B = ~30 MB) are as large as the whole L2
+// (8 x 4 MB), so nothing that was fetched stays long enough to serve a second destination.  On dense
+// graphs, where a row of X is gathered hundreds of times, fewer resident waves mean more L2 hits and
+// a shorter run (measured on MI355X, 64-lane slices: 2 workgroups per CU are 30 % faster than 4-5 at
+// mean degree ~490, 3 are 5-17 % faster at mean degree 128-256); on sparse graphs and narrow slices
+// the parallelism is worth more.  The mean degree is estimated from the plan's degree classes.
+// Returns 0 for "no cap".
+inline int resident_workgroup_cap(const int64_t* class_off, int64_t N, int g_log2) {
+  if (!class_off || N <= 0 || g_log2 < 4) return 0;
+  double edges = 0.0;
+  for (int k = 0; k < GNNAGG_PLAN_CLASSES; ++k) {
+    const int c = 32 - k;  // rows with 2^(c-1) <= degree < 2^c
+    if (c == 0) continue;
+    const double mid = 1.5 * (double)(1ull << (c - 1)) - 0.5;
+    edges += mid * (double)(class_off[k + 1] - class_off[k]);
+  }
+  const double mean_degree = edges / (double)N;
+  if (g_log2 < 6) return mean_degree >= 384.0 ? 3 : 0;  // 16/32-lane slices: smaller effect (~10 % at ~490)
+  if (mean_degree >= 384.0) return 2;
+  if (mean_degree >= 96.0) return 3;
+  return 0;
+}
+
+// LDS a workgroup has to occupy so that exactly `cap` workgroups fit in the 160 KB of a gfx950
+// compute unit (cap + 1 must not fit; 1 KB of slack covers the allocation granularity).
+inline uint32_t lds_claim(int cap) {
+  constexpr uint32_t kLdsPerCu = 160 * 1024;
+  if (cap <= 0) return 0;
+  const uint32_t claim = kLdsPerCu / (uint32_t)(cap + 1) + 1024;
+  return claim > 64 * 1024 ? 64 * 1024 : claim;  // what a launch may request without opting in to more
+}
+
 }  // namespace gnnagg

@@ -5,7 +5,9 @@
 
 A step is one gnnagg_aggregate call (chunk addressing, gather, reduce, in-place
 concat) over the whole synthetic graph, with the CSR, the row plan and the
-features already resident in HBM.  The CSR build and the row plan are per-graph
+features already resident in HBM.  The default workload is the dense
+232,965-vertex / 114.6 M-edge graph with 602 fp32 features and GCN weights; the
+sparse 2.4 M-vertex bf16 workload is measured after it and reported under "also".  The CSR build and the row plan are per-graph
 steps; they are timed separately and reported under "setup".  Prints one JSON
 line: edge-features/s, the HBM roofline of the aggregation kernel (algorithmic
 bytes / HIP-event time, peak 8 TB/s) and the CPU checker timed on the host
@@ -22,6 +24,14 @@ import time
 import numpy as np
 
 HBM_PEAK_GBS = 8000.0
+
+# HBM-side bytes per aggregation launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, scaled on the copy
+# probe: see profiles/aggregate_kernel_*.txt), valid for the kernels as committed with those profiles and
+# for f_chunk = 0 only.  Set an entry to None when the kernel changes until the counters are taken again.
+MEASURED_TRAFFIC = {
+    "c4-gcn": 176.595e9,  # profiles/aggregate_kernel_c4_gcn.txt
+    "c5-sum": 16.559e9,   # profiles/aggregate_kernel_c5_sum_bf16.txt
+}
 
 WORKLOADS = {
     # name: (graph key, op, F, feature dtype, self loops + GCN norm)
@@ -48,51 +58,9 @@ def algorithmic_bytes(nnz, N, F, x_bytes, weighted, f_chunk):
     return nnz * F * x_bytes + P * nnz * (4 + (4 if weighted else 0)) + N * F * 4 + P * (N + 1) * 8
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c4-gcn", choices=sorted(WORKLOADS) + ["copy"],
-                    help="'copy' runs only the library's plain copy kernel on 1 GiB (profiler calibration)")
-    ap.add_argument("--f-chunk", type=int, default=0)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
-
-    import torch
-    if not torch.cuda.is_available():
-        sys.exit("bench.py needs a GPU")
-    import paper_2104_03058_amd as g
-    import workloads as W
-    g.load_library()
-
-    # plain streaming copy of 1 GiB: the measured HBM copy rate of this device, reported beside the roofline
-    probe_bytes = 1 << 30
-    p_src = torch.empty(probe_bytes, dtype=torch.uint8, device="cuda").fill_(1)
-    p_dst = torch.empty_like(p_src)
-    g.gnnagg_copy_probe(p_dst, p_src)
-    torch.cuda.synchronize()
-    n_probe = max(args.steps, 3) if args.workload == "copy" else 5
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(n_probe):
-        g.gnnagg_copy_probe(p_dst, p_src)
-    e1.record()
-    torch.cuda.synchronize()
-    copy_ms = e0.elapsed_time(e1) / n_probe
-    copy_gbs = 2.0 * probe_bytes / (copy_ms * 1e-3) / 1e9
-    log("copy probe: 1 GiB in %.3f ms -> %.0f GB/s read+write" % (copy_ms, copy_gbs))
-    del p_src, p_dst
-    if args.workload == "copy":
-        print(json.dumps({"metric": "hbm copy rate", "value": copy_gbs, "unit": "GB/s", "n_gpus": 1,
-                          "steps": n_probe, "ms_per_step": copy_ms, "bytes_read": probe_bytes,
-                          "bytes_written": probe_bytes, "config": {"workload": "copy"}}), flush=True)
-        return
-
-    gkey, opname, F, xdt, gcn = WORKLOADS[args.workload]
+def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_seconds, copy_gbs):
+    """One workload: setup (CSR build, row plan), timed aggregation steps, optional CPU-checker leg."""
+    gkey, opname, F, xdt, gcn = WORKLOADS[workload]
     t0 = time.time()
     N, src, dst = W.graph(gkey)
     log("graph %s: N=%d directed edges=%d (%.1fs)" % (gkey, N, len(src), time.time() - t0))
@@ -127,13 +95,13 @@ def main():
     out = torch.empty((N, F), dtype=torch.float32, device="cuda")
 
     def step():
-        g.gnnagg_aggregate(op, d_rp, d_ci, d_w, d_X, out, args.f_chunk, plan)
+        g.gnnagg_aggregate(op, d_rp, d_ci, d_w, d_X, out, f_chunk, plan)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     # whole timed region: wall clock around K steps; per-step kernel time: HIP events on the launch stream
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     t0 = time.perf_counter()
     for a, b in ev:
         a.record()
@@ -142,10 +110,10 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms = np.array([a.elapsed_time(b) for a, b in ev])
-    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step = wall * 1e3 / steps
     edge_features = float(nnz) * F
     x_bytes = 2 if xdt == "bf16" else 4
-    b_alg = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", args.f_chunk)
+    b_alg = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", f_chunk)
     kern_ms = float(ms.mean())
     achieved = b_alg / (kern_ms * 1e-3) / 1e9
     log("step %.3f ms wall, kernel mean %.3f ms (min %.3f), %.3e edge-features/s, %.0f GB/s algorithmic" %
@@ -154,7 +122,7 @@ def main():
     # ---- CPU checker on the host cores: bounded sample of destination rows, also the parity check
     cpu = None
     parity = None
-    if not args.no_cpu_baseline:
+    if not (not cpu_baseline):
         import oracle
         threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
         t0 = time.time()
@@ -167,7 +135,7 @@ def main():
         t0 = time.time()
         oracle.aggregate_rows(rop, probe, rp, ci, w, X, threads=threads)
         rate = max(float(deg[probe].sum()) * F / max(time.time() - t0, 1e-4), 1.0)
-        want = args.cpu_seconds * rate / F  # edges to cover in about cpu_seconds
+        want = cpu_seconds * rate / F  # edges to cover in about cpu_seconds
         nrows = int(min(N, max(256, want / max(deg.mean(), 1.0))))
         rows = np.sort(rng.choice(N, size=nrows, replace=False)).astype(np.int64)
         t0 = time.time()
@@ -175,7 +143,7 @@ def main():
         dt = time.time() - t0
         ef = float(deg[rows].sum()) * F
         cpu = {"value": ef / dt, "unit": "edge-features/s", "cores": threads, "kind": "oracle",
-               "sample": "%d random destination rows of %s (%.3g edge-features, %.1f s)" % (nrows, args.workload, ef, dt)}
+               "sample": "%d random destination rows of %s (%.3g edge-features, %.1f s)" % (nrows, workload, ef, dt)}
         got = out[torch.from_numpy(rows).cuda()].cpu().numpy()
         tol = 1e-2 if xdt == "bf16" else 1e-5
         if opname == "max":
@@ -186,19 +154,78 @@ def main():
 
     rec = {
         "metric": "aggregated edge-features/sec", "value": edge_features / (ms_per_step * 1e-3),
-        "unit": "edge-features/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "unit": "edge-features/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if xdt == "f32" else "bf16-in/f32-acc", "data": "synthetic",
-        "config": {"workload": args.workload, "graph": W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "op": opname,
-                   "f_chunk": args.f_chunk, "x_dtype": xdt},
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": workload, "graph": W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "op": opname,
+                   "f_chunk": f_chunk, "x_dtype": xdt},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC.get(workload) if f_chunk == 0 else None,
                      "kernel": "aggregate_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": b_alg,
                      "measured_copy_gbs": copy_gbs},
         "cpu_baseline": cpu,
         "parity_on_sample": parity,
         "setup": {"csr_build_ms": t_csr * 1e3, "row_plan_ms": t_plan * 1e3},
     }
+    return rec
+
+
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c4-gcn", choices=sorted(WORKLOADS) + ["copy"],
+                    help="'copy' runs only the library's plain copy kernel on 1 GiB (profiler calibration)")
+    ap.add_argument("--f-chunk", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--also", default="c5-sum",
+                    help="comma list of further workloads measured after the main one and reported under 'also'")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    import paper_2104_03058_amd as g
+    import workloads as W
+    g.load_library()
+
+    # plain streaming copy of 1 GiB: the measured HBM copy rate of this device, reported beside the roofline
+    probe_bytes = 1 << 30
+    p_src = torch.empty(probe_bytes, dtype=torch.uint8, device="cuda").fill_(1)
+    p_dst = torch.empty_like(p_src)
+    g.gnnagg_copy_probe(p_dst, p_src)
+    torch.cuda.synchronize()
+    n_probe = max(args.steps, 3) if args.workload == "copy" else 5
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n_probe):
+        g.gnnagg_copy_probe(p_dst, p_src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_ms = e0.elapsed_time(e1) / n_probe
+    copy_gbs = 2.0 * probe_bytes / (copy_ms * 1e-3) / 1e9
+    log("copy probe: 1 GiB in %.3f ms -> %.0f GB/s read+write" % (copy_ms, copy_gbs))
+    del p_src, p_dst
+    if args.workload == "copy":
+        print(json.dumps({"metric": "hbm copy rate", "value": copy_gbs, "unit": "GB/s", "n_gpus": 1,
+                          "steps": n_probe, "ms_per_step": copy_ms, "bytes_read": probe_bytes,
+                          "bytes_written": probe_bytes, "config": {"workload": "copy"}}), flush=True)
+        return
+
+    rec = measure(g, W, torch, args.workload, args.f_chunk, args.steps, args.warmup, not args.no_cpu_baseline,
+                  args.cpu_seconds, copy_gbs)
+    also = []
+    for wl in [w for w in args.also.split(",") if w and w != args.workload]:
+        r = measure(g, W, torch, wl, 0, args.steps, args.warmup, False, 0.0, copy_gbs)
+        also.append({k: r[k] for k in ("value", "unit", "ms_per_step", "config", "roofline", "setup")})
+    rec["also"] = also
     print(json.dumps(rec), flush=True)
 
 

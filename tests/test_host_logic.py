@@ -145,3 +145,36 @@ def test_geometry_attention_lanes_stay_inside_heads(checker, heads, C, f_chunk):
     N = 120
     cc = counts(N, {0: 3, 2: 30, 4: 20, 6: 10, 9: 4, 13: 2})
     run_checker(checker, heads * C, f_chunk, 4, C, N, cc)
+
+
+# ------------------------------------------------------------------ resident-workgroup cap
+@pytest.fixture(scope="module")
+def cap_checker(tmp_path_factory):
+    exe = str(tmp_path_factory.mktemp("host") / "cap_check")
+    subprocess.check_call(["g++", "-O1", "-std=c++17", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
+                           "-I" + os.path.join(ROOT, "include"),
+                           "-I" + os.path.join(ROOT, "paper_2104_03058_amd", "csrc"),
+                           os.path.join(ROOT, "tests", "host", "cap_check.cpp"), "-o", exe])
+    return exe
+
+
+def run_cap(exe, g, N, spread):
+    out = subprocess.run([exe, str(g), str(N)] + [str(c) for c in counts(N, spread)], capture_output=True, text=True)
+    assert out.returncode == 0, out.stderr
+    return [int(t) for t in out.stdout.split()]
+
+
+def test_workgroup_cap_follows_mean_degree(cap_checker):
+    N = 1000
+    dense = {10: 600, 9: 300, 8: 100}        # degrees 128..1023: mean ~ 580
+    medium = {8: 700, 7: 300}                # degrees 64..255: mean ~ 160
+    sparse = {3: 500, 2: 300, 5: 100}        # single digits
+    cap, claim, noplan = run_cap(cap_checker, 6, N, dense)
+    assert cap == 2 and noplan == 0
+    # exactly `cap` workgroups fit into 160 KB of LDS
+    assert cap * claim <= 160 * 1024 < (cap + 1) * claim
+    cap, claim, _ = run_cap(cap_checker, 6, N, medium)
+    assert cap == 3 and cap * claim <= 160 * 1024 < (cap + 1) * claim
+    assert run_cap(cap_checker, 6, N, sparse)[:2] == [0, 0]
+    assert run_cap(cap_checker, 5, N, dense)[0] == 3 and run_cap(cap_checker, 5, N, medium)[0] == 0
+    assert run_cap(cap_checker, 2, N, dense)[0] == 0   # narrow slices are never capped

@@ -19,12 +19,12 @@
 #include "common.hpp"
 #include "schedule.hpp"
 #include "device_utils.hpp"
+#include "gather.hpp"
 
 namespace gnnagg {
 namespace {
 
 enum { OPK_SUM = 0, OPK_WSUM = 1, OPK_MAX = 2 };
-constexpr int kUnroll = 8;  // independent gathers in flight per lane
 
 struct AggArgs {
   const int64_t* rowptr;
@@ -133,182 +133,27 @@ struct State<OPK_MAX, VEC> {
   __device__ inline float result(int k, int64_t deg, bool) const { return deg > 0 ? key_value(key[k]) : 0.0f; }
 };
 
-typedef int32_t i32x4_u __attribute__((ext_vector_type(4), aligned(4)));
-
-__device__ inline int64_t uniform64(int64_t v) {  // v is the same in every lane: move it to scalar registers
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
-  return (int64_t)(((uint64_t)hi << 32) | lo);
-}
-
-// One gather + accumulate batch: kUnroll independent 16-byte row loads issued back to back, then the
-// accumulates.  Straight-line code: an entry that does not exist (OKEXPR false, only in MASKED
-// batches) re-reads the row JSAFE, which does exist, and enters the reduction with weight 0 (sums)
-// or the lowest key (max), so no load sits behind a branch.
-#define GNNAGG_BATCH(UN, MASKED, OKEXPR, JEXPR, WEXPR, JSAFE)                                     \
-  {                                                                                           \
-    typename Raw<T, VEC>::type raw[(UN)];                                                  \
-    float wv[(UN)];                                                                        \
-    bool okv[(UN)];                                                                        \
-    _Pragma("unroll") for (int u = 0; u < (UN); ++u) {                                     \
-      okv[u] = (MASKED) ? (bool)(OKEXPR) : true;                                              \
-      const int64_t jj = okv[u] ? (int64_t)(JEXPR) : (int64_t)(JSAFE);                        \
-      const float wsel = (OPK == OPK_WSUM) ? (float)(WEXPR) : 1.0f;                           \
-      wv[u] = okv[u] ? wsel : 0.0f;                                                           \
-      raw[u] = load_raw<T, VEC>(reinterpret_cast<const T*>(xb + jj * rowbytes + lane_off));   \
-    }                                                                                         \
-    _Pragma("unroll") for (int u = 0; u < (UN); ++u) {                                     \
-      float v[VEC];                                                                           \
-      unpack(raw[u], v);                                                                      \
-      st.template add<(MASKED)>(v, wv[u], okv[u]);                                            \
-    }                                                                                         \
-  }
-
-// How a row's edge list is dealt out to its P = 2^p_log2 neighbour slots: in rounds of 8*P consecutive
-// edges, slot ng taking edges [8*ng, 8*ng + 8) of every round - one gather batch.  All slots of a row
-// therefore work on the same 8*P-edge stretch of the (source-sorted) list at any time, and rows that
-// run side by side advance through the source ids together: this keeps the set of X rows in flight
-// small enough for L2 to serve a row to several destinations.
-//
-// Slot = a whole wavefront (64 lanes span the slice).  The wave reads the edge indices (and weights) of
-// its next eight batches with one load each, then walks them: the source row of an entry is broadcast
-// with v_readlane, so row addresses live in scalar registers.  [e0, e1), ng are the same in every lane.
-template <typename T, int OPK, int VEC, int U>
-__device__ inline void gather_wave(const AggArgs& a, State<OPK, VEC>& st, int64_t e0, int64_t e1, int ng,
-                                   int p_log2, int col, int lane) {
-  const int64_t e0_u = uniform64(e0), e1_u = uniform64(e1);
-  const int ng_u = __builtin_amdgcn_readfirstlane(ng);
-  static_assert(U == 4 || U == 8 || U == 16, "a batch is 4, 8 or 16 gathers");
-  constexpr int u_log2 = (U == 4) ? 2 : (U == 8 ? 3 : 4);
-  const int shift = u_log2 + p_log2;                  // log2 of the round length (U edges per slot)
-  const int64_t outer = (int64_t)kWave << p_log2;     // edges the row advances per index load
-  const int64_t lane_pos = ((int64_t)(lane >> u_log2) << shift) + (ng_u << u_log2) + (lane & (U - 1));
-  const char* __restrict__ xb = static_cast<const char*>(a.X);
-  const int64_t rowbytes = a.F * (int64_t)sizeof(T);
-  const uint32_t lane_off = (uint32_t)col * (uint32_t)sizeof(T);
-  int32_t idx_c = 0;
-  float w_c = 1.0f;
-  if (e0_u + lane_pos < e1_u) {
-    idx_c = a.colidx[e0_u + lane_pos];
-    if (OPK == OPK_WSUM) w_c = a.edge_w[e0_u + lane_pos];
-  }
-  for (int64_t e = e0_u; e < e1_u; e += outer) {
-    int32_t idx_n = 0;  // the next eight batches' indices are requested before this block's rows
-    float w_n = 1.0f;
-    if (e + outer + lane_pos < e1_u) {
-      idx_n = a.colidx[e + outer + lane_pos];
-      if (OPK == OPK_WSUM) w_n = a.edge_w[e + outer + lane_pos];
-    }
-    for (int k = 0; k < kWave / U; ++k) {
-      const int64_t left = e1_u - (e + ((int64_t)k << shift) + (ng_u << u_log2));
-      if (left <= 0) break;
-      const int l0 = k * U;
-      if (left >= U) {
-        GNNAGG_BATCH(U, false, true, __builtin_amdgcn_readlane(idx_c, l0 + u),
-                     __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_c), l0 + u)), 0)
-      } else {
-        GNNAGG_BATCH(U, true, u < left, __builtin_amdgcn_readlane(idx_c, l0 + u),
-                     __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_c), l0 + u)),
-                     __builtin_amdgcn_readlane(idx_c, l0))
-      }
-    }
-    idx_c = idx_n;
-    w_c = w_n;
-  }
-}
-
-// Slot = 2^g lanes, 8 <= 2^g <= 32.  The lanes of a slot read the indices of the slot's next 2^g / 8
-// batches with one load and hand them round with cross-lane shuffles.  All lanes of a slot run the loop
-// together; lanes without columns of their own hold indices for the others and re-read the slice's
-// last columns (role.col is always a valid column) rather than branching around the gathers.
+// Accumulator policy of the walk in gather.hpp: one 16-byte piece of the source row per edge.
 template <typename T, int OPK, int VEC>
-__device__ inline void gather_wide(const AggArgs& a, State<OPK, VEC>& st, int64_t e0, int64_t e1, int ng,
-                                   int p_log2, int col, int lane, int g) {
-  const int G = 1 << g;
-  const int gl = lane & (G - 1), slot_base = lane & ~(G - 1);
-  const int shift = 3 + p_log2;
-  const int64_t outer = (int64_t)G << p_log2;
-  const int64_t lane_pos = ((int64_t)(gl >> 3) << shift) + (ng << 3) + (gl & 7);
-  const char* __restrict__ xb = static_cast<const char*>(a.X);
-  const int64_t rowbytes = a.F * (int64_t)sizeof(T);
-  const uint32_t lane_off = (uint32_t)col * (uint32_t)sizeof(T);
-  int32_t idx_c = -1;
-  float w_c = 0.0f;
-  if (e0 + lane_pos < e1) {
-    idx_c = a.colidx[e0 + lane_pos];
-    if (OPK == OPK_WSUM) w_c = a.edge_w[e0 + lane_pos];
+struct AggAcc {
+  static constexpr bool kWeighted = (OPK == OPK_WSUM);
+  State<OPK, VEC> st;
+  const char* __restrict__ xb;  // X plus this lane's column offset, in bytes
+  int64_t rowbytes;
+  typename Raw<T, VEC>::type raw[kUnroll];
+  __device__ inline void fetch(int u, int64_t j) {
+    raw[u] = load_raw<T, VEC>(reinterpret_cast<const T*>(xb + j * rowbytes));
   }
-  for (int64_t e = e0; e < e1; e += outer) {
-    int32_t idx_n = -1;
-    float w_n = 0.0f;
-    if (e + outer + lane_pos < e1) {
-      idx_n = a.colidx[e + outer + lane_pos];
-      if (OPK == OPK_WSUM) w_n = a.edge_w[e + outer + lane_pos];
-    }
-    for (int k = 0; k < (G >> 3); ++k) {
-      if (e + ((int64_t)k << shift) + (ng << 3) >= e1) break;  // same for every lane of the slot
-      int32_t j[kUnroll];
-      float wj[kUnroll];
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
-        j[u] = __shfl(idx_c, slot_base + k * kUnroll + u, kWave);
-        wj[u] = (OPK == OPK_WSUM) ? __shfl(w_c, slot_base + k * kUnroll + u, kWave) : 1.0f;
-      }
-      GNNAGG_BATCH(kUnroll, true, j[u] >= 0, j[u], wj[u], j[0])
-    }
-    idx_c = idx_n;
-    w_c = w_n;
+  template <bool MASKED>
+  __device__ inline void use(int u, float w, bool ok) {
+    float v[VEC];
+    unpack(raw[u], v);
+    st.template add<MASKED>(v, w, ok);
   }
-}
-
-// Slot = 1, 2 or 4 lanes (slices of at most 16 fp32 / 32 bf16 columns).  Every lane reads the next
-// eight edge indices of its slot's range itself, as two 16-byte loads (the lanes of a slot read the
-// same addresses, which the memory pipeline merges).  The loads may run past the end of the slot's
-// range into the following entries of colidx, never past nnz.
-template <typename T, int OPK, int VEC>
-__device__ inline void gather_narrow(const AggArgs& a, State<OPK, VEC>& st, int64_t es, int64_t ee,
-                                     int64_t stride, int col, int64_t nnz) {
-  const char* __restrict__ xb = static_cast<const char*>(a.X);
-  const int64_t rowbytes = a.F * (int64_t)sizeof(T);
-  const uint32_t lane_off = (uint32_t)col * (uint32_t)sizeof(T);
-  for (int64_t e = es; e < ee; e += stride) {
-    int32_t j[kUnroll];
-    float wj[kUnroll];
-    if (e + kUnroll <= nnz) {
-      const i32x4_u i0 = *reinterpret_cast<const i32x4_u*>(a.colidx + e);
-      const i32x4_u i1 = *reinterpret_cast<const i32x4_u*>(a.colidx + e + 4);
-      j[0] = i0.x; j[1] = i0.y; j[2] = i0.z; j[3] = i0.w;
-      j[4] = i1.x; j[5] = i1.y; j[6] = i1.z; j[7] = i1.w;
-      if (OPK == OPK_WSUM) {
-        const f32x4_u w0 = *reinterpret_cast<const f32x4_u*>(a.edge_w + e);
-        const f32x4_u w1 = *reinterpret_cast<const f32x4_u*>(a.edge_w + e + 4);
-        wj[0] = w0.x; wj[1] = w0.y; wj[2] = w0.z; wj[3] = w0.w;
-        wj[4] = w1.x; wj[5] = w1.y; wj[6] = w1.z; wj[7] = w1.w;
-      }
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u)
-        if (e + u >= ee) j[u] = -1;
-    } else {
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
-        const bool ok = e + u < ee;
-        j[u] = ok ? a.colidx[e + u] : -1;
-        if (OPK == OPK_WSUM) wj[u] = ok ? a.edge_w[e + u] : 0.0f;
-      }
-    }
-    if (OPK != OPK_WSUM) {
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u) wj[u] = 1.0f;
-    }
-    GNNAGG_BATCH(kUnroll, true, j[u] >= 0, j[u], wj[u], j[0])
-  }
-}
-
-enum { MODE_WAVE = 0, MODE_WIDE = 1, MODE_NARROW = 2 };  // 64 / 8..32 / 1..4 lanes per slice (fixed per launch)
+};
 
 template <typename T, int OPK, int VEC, int MODE>
 __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
-  static_assert(kUnroll == 8, "gather_narrow reads eight indices as two 16-byte loads");
   __shared__ double lds[(kWavesPerBlock - 1) * kWave * VEC];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
 
@@ -322,19 +167,13 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
     e1 = a.rowptr[r + 1];
   }
   const int64_t deg = e1 - e0;
-  const int p_log2 = (hub ? 8 : role.L) - g;  // log2 of the row's neighbour slots
-
-  State<OPK, VEC> st;
-  st.init();
-  if constexpr (MODE == MODE_WAVE) {
-    gather_wave<T, OPK, VEC, kUnroll>(a, st, e0, e1, role.ng, p_log2, col, lane);
-  } else if constexpr (MODE == MODE_WIDE) {
-    gather_wide<T, OPK, VEC>(a, st, e0, e1, role.ng, p_log2, col, lane, g);
-  } else {
-    const int64_t nnz = a.rowptr[a.N];
-    if (col_ok)
-      gather_narrow<T, OPK, VEC>(a, st, e0 + (int64_t)role.ng * kUnroll, e1, (int64_t)kUnroll << p_log2, col, nnz);
-  }
+  AggAcc<T, OPK, VEC> acc;
+  acc.st.init();
+  acc.xb = static_cast<const char*>(a.X) + (int64_t)col * (int64_t)sizeof(T);
+  acc.rowbytes = a.F * (int64_t)sizeof(T);
+  const int64_t nnz = (MODE == MODE_NARROW) ? a.rowptr[a.N] : 0;
+  gather_row<MODE>(acc, a.colidx, a.edge_w, e0, e1, role.ng, g, role.L, col_ok, lane, nnz);
+  State<OPK, VEC>& st = acc.st;
 
   // ---- merge the neighbour slots of a row -------------------------------------
   const int lanes_in_wave = hub ? kWave : (1 << role.L);

@@ -12,12 +12,11 @@
 
 #include "common.hpp"
 #include "device_utils.hpp"
+#include "gather.hpp"
 #include "schedule.hpp"
 
 namespace gnnagg {
 namespace {
-
-constexpr int kGatUnroll = 4;
 
 struct GatArgs {
   const int64_t* rowptr;
@@ -30,6 +29,7 @@ struct GatArgs {
   const int32_t* order;
   int32_t heads, C;
   float slope;
+  int64_t N;
   SliceLaunch sl;
   SegTable segs;
 };
@@ -100,7 +100,34 @@ struct SoftState {
   }
 };
 
+// Accumulator policy of the walk in gather.hpp: per edge, the source's score for this lane's head and
+// one 16-byte piece of its feature row.
 template <int VEC>
+struct GatAcc {
+  static constexpr bool kWeighted = false;
+  SoftState<VEC> st;
+  const char* __restrict__ hb;  // H plus this lane's column offset, in bytes
+  int64_t rowbytes;
+  const float* __restrict__ s_src_h;  // s_src plus this lane's head
+  int32_t heads;
+  float sd, slope;
+  typename Raw<float, VEC>::type raw[kUnroll];
+  float ss[kUnroll];
+  __device__ inline void fetch(int u, int64_t j) {
+    ss[u] = s_src_h[j * heads];
+    raw[u] = load_raw<float, VEC>(reinterpret_cast<const float*>(hb + j * rowbytes));
+  }
+  template <bool MASKED>
+  __device__ inline void use(int u, float, bool ok) {
+    if (MASKED && !ok) return;
+    float v[VEC];
+    unpack(raw[u], v);
+    const float s = ss[u] + sd;
+    st.add(s >= 0.0f ? s : slope * s, v);
+  }
+};
+
+template <int VEC, int MODE>
 __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) {
   __shared__ double lds[(kWavesPerBlock - 1) * kWave * (2 + VEC)];
   __shared__ double fin[2 * kWave];
@@ -117,38 +144,19 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
   }
   const int head = col / a.C;  // VEC divides C, so the lane's columns lie in one head
   const int64_t HC = (int64_t)a.heads * a.C;
-  const float* __restrict__ hcol = a.H + col;
-  const int64_t e_stop = (row_ok && col_ok) ? e1 : e0;
-  const float sd = (row_ok && col_ok) ? a.s_dst[r * a.heads + head] : 0.0f;
 
-  SoftState<VEC> st;
-  st.init();
-  for (int64_t e = e0 + ng; e < e_stop; e += (int64_t)kGatUnroll * P) {
-    int32_t j[kGatUnroll];
-    float ss[kGatUnroll];
-    typename Raw<float, VEC>::type raw[kGatUnroll];
-#pragma unroll
-    for (int u = 0; u < kGatUnroll; ++u) {
-      const int64_t ee = e + (int64_t)u * P;
-      j[u] = (ee < e_stop) ? a.colidx[ee] : -1;
-    }
-#pragma unroll
-    for (int u = 0; u < kGatUnroll; ++u) {
-      if (j[u] >= 0) {
-        ss[u] = a.s_src[(int64_t)j[u] * a.heads + head];
-        raw[u] = load_raw<float, VEC>(hcol + (int64_t)j[u] * HC);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < kGatUnroll; ++u) {
-      if (j[u] >= 0) {
-        float v[VEC];
-        unpack(raw[u], v);
-        const float s = ss[u] + sd;
-        st.add(s >= 0.0f ? s : a.slope * s, v);
-      }
-    }
-  }
+  GatAcc<VEC> acc;
+  acc.st.init();
+  acc.hb = reinterpret_cast<const char*>(a.H + col);
+  acc.rowbytes = HC * (int64_t)sizeof(float);
+  acc.s_src_h = a.s_src + head;
+  acc.heads = a.heads;
+  acc.slope = a.slope;
+  acc.sd = row_ok ? a.s_dst[r * a.heads + head] : 0.0f;
+  const float sd = acc.sd;
+  const int64_t nnz = (MODE == MODE_NARROW) ? a.rowptr[a.N] : 0;
+  gather_row<MODE>(acc, a.colidx, nullptr, e0, e1, ng, g, role.L, col_ok, lane, nnz);
+  SoftState<VEC>& st = acc.st;
 
   const int lanes_in_wave = hub ? kWave : (1 << role.L);
   for (int stride = 1 << g; stride < lanes_in_wave; stride <<= 1) st.merge(st.shuffled_xor(stride));
@@ -185,7 +193,8 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
     for (int k = 0; k < VEC; ++k) res[k] = (e1 > e0) ? (float)(st.acc[k] / st.l) : 0.0f;
     store_row<VEC>(a.out + r * HC + col, res);
   }
-  // softmax weights, written by the first lane of every head
+  // softmax weights, written by the first lane of every head; the row's edges are dealt to the slots
+  // one at a time here
   if (a.alpha && row_ok && col_ok && (col % a.C) == 0) {
     for (int64_t e = e0 + ng; e < e1; e += P) {
       const float s = a.s_src[(int64_t)a.colidx[e] * a.heads + head] + sd;
@@ -197,7 +206,14 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
 
 template <int VEC>
 int launch_gat(const GatArgs& a, uint64_t grid, hipStream_t stream) {
-  hipLaunchKernelGGL((gat_aggregate_kernel<VEC>), dim3((unsigned)grid), dim3(kBlock), 0, stream, a);
+  const int g = a.sl.g_log2;
+  if (g == 6) {
+    hipLaunchKernelGGL((gat_aggregate_kernel<VEC, MODE_WAVE>), dim3((unsigned)grid), dim3(kBlock), 0, stream, a);
+  } else if (g >= 3) {
+    hipLaunchKernelGGL((gat_aggregate_kernel<VEC, MODE_WIDE>), dim3((unsigned)grid), dim3(kBlock), 0, stream, a);
+  } else {
+    hipLaunchKernelGGL((gat_aggregate_kernel<VEC, MODE_NARROW>), dim3((unsigned)grid), dim3(kBlock), 0, stream, a);
+  }
   return hipGetLastError() == hipSuccess ? GNNAGG_OK : GNNAGG_EDEVICE;
 }
 
@@ -252,6 +268,7 @@ extern "C" int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
     a.heads = heads;
     a.C = C;
     a.slope = negative_slope;
+    a.N = N;
     a.sl = launches[k];
     if (a.sl.sub_w % a.sl.vec || a.sl.chunk_w % a.sl.vec) return GNNAGG_EINVAL;  // cannot happen: vec divides C
     int rc = build_segments(class_off, N, a.sl.g_log2, &a.segs);

@@ -43,6 +43,17 @@ WORKLOADS = {
     "c5-sum-f16": ("c5", "sum", 16, "bf16", False),
     "c2-mean": ("c2", "mean", 500, "f32", False),
     "c1-gcn": ("c1", "wsum", 1433, "f32", True),
+    # attention: F = (heads, channels per head); self-loops, no GCN weights
+    "c3-gat": ("c2", "gat", (8, 8), "f32", False),
+    "c4-gat": ("c4", "gat", (8, 8), "f32", False),
+    # the paper's regime: Combination first, so Aggregation runs at the hidden width 8/16/32 (Section III)
+    "c4-hid32-gcn": ("c4", "wsum", 32, "f32", True),
+    "c4-hid8-gcn": ("c4", "wsum", 8, "f32", True),
+    "c6-hid32-gcn": ("c6", "wsum", 32, "f32", True),
+    "c6-hid16-gcn": ("c6", "wsum", 16, "f32", True),
+    "c6-hid8-gcn": ("c6", "wsum", 8, "f32", True),
+    "c6-hid32-mean": ("c6", "mean", 32, "f32", False),
+    "c6-gat": ("c6", "gat", (8, 4), "f32", False),
 }
 
 
@@ -61,6 +72,9 @@ def algorithmic_bytes(nnz, N, F, x_bytes, weighted, f_chunk):
 def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_seconds, copy_gbs):
     """One workload: setup (CSR build, row plan), timed aggregation steps, optional CPU-checker leg."""
     gkey, opname, F, xdt, gcn = WORKLOADS[workload]
+    gat = opname == "gat"
+    heads, C = F if gat else (1, F)
+    F = heads * C
     t0 = time.time()
     N, src, dst = W.graph(gkey)
     log("graph %s: N=%d directed edges=%d (%.1fs)" % (gkey, N, len(src), time.time() - t0))
@@ -75,7 +89,7 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
         return torch.from_numpy(a).cuda()
 
     d_src, d_dst, d_X = dev(src), dev(dst), dev(X)
-    flags = (g.SELF_LOOPS | g.NORM_SYM) if gcn else 0
+    flags = (g.SELF_LOOPS | g.NORM_SYM) if gcn else (g.SELF_LOOPS if gat else 0)
     # ---- per-graph setup: CSR build and row plan (timed, not part of a step)
     g.gnnagg_build_csr(N, d_src, d_dst, flags, want_w=gcn)  # warm-up (allocator, code objects)
     torch.cuda.synchronize()
@@ -91,11 +105,21 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
     nnz = int(d_ci.shape[0])
     log("device CSR build %.1f ms, row plan %.1f ms, nnz=%d" % (t_csr * 1e3, t_plan * 1e3, nnz))
 
-    op = {"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname]
     out = torch.empty((N, F), dtype=torch.float32, device="cuda")
+    if gat:
+        a_s, a_d = W.normal_f32((heads, C), seed=14, std=0.1), W.normal_f32((heads, C), seed=15, std=0.1)
+        d_as, d_ad = dev(a_s), dev(a_d)
+        d_H, out3 = d_X.view(N, heads, C), out.view(N, heads, C)
+        ws = torch.empty(g.gnnagg_gat_workspace_bytes(N, heads, C), dtype=torch.uint8, device="cuda")
 
-    def step():
-        g.gnnagg_aggregate(op, d_rp, d_ci, d_w, d_X, out, f_chunk, plan)
+        def step():
+            g.gnnagg_gat_attention(d_rp, d_ci, d_H, d_as, d_ad, 0.2, False, True, f_chunk, plan, out=out3,
+                                   workspace=ws)
+    else:
+        op = {"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname]
+
+        def step():
+            g.gnnagg_aggregate(op, d_rp, d_ci, d_w, d_X, out, f_chunk, plan)
 
     for _ in range(warmup):
         step()
@@ -113,7 +137,10 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
     ms_per_step = wall * 1e3 / steps
     edge_features = float(nnz) * F
     x_bytes = 2 if xdt == "bf16" else 4
-    b_alg = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", f_chunk)
+    if gat:  # per edge: the row piece, one score per head, the index; per vertex: H once for the scores, out, scores
+        b_alg = nnz * (F * 4 + heads * 4 + 4) + 2 * N * F * 4 + 2 * N * heads * 4 * 2 + (N + 1) * 8
+    else:
+        b_alg = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", f_chunk)
     kern_ms = float(ms.mean())
     achieved = b_alg / (kern_ms * 1e-3) / 1e9
     log("step %.3f ms wall, kernel mean %.3f ms (min %.3f), %.3e edge-features/s, %.0f GB/s algorithmic" %
@@ -128,18 +155,25 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
         t0 = time.time()
         rp, ci, w, _ = oracle.build_csr(N, src, dst, flags, want_w=gcn, threads=threads)
         log("checker CSR build %.1fs on %d threads" % (time.time() - t0, threads))
-        rop = {"sum": oracle.SUM, "wsum": oracle.WSUM, "mean": oracle.MEAN, "max": oracle.MAX}[opname]
+        rop = {"sum": oracle.SUM, "wsum": oracle.WSUM, "mean": oracle.MEAN, "max": oracle.MAX}.get(opname)
+
+        def checker_rows(rr):
+            if gat:
+                return oracle.gat_attention_rows(rr, rp, ci, X.reshape(N, heads, C), a_s, a_d, 0.2,
+                                                 threads=threads).reshape(len(rr), F)
+            return oracle.aggregate_rows(rop, rr, rp, ci, w, X, threads=threads)
+
         rng = np.random.default_rng(0)
         deg = np.diff(rp)
         probe = np.sort(rng.choice(N, size=min(N, 256), replace=False)).astype(np.int64)
         t0 = time.time()
-        oracle.aggregate_rows(rop, probe, rp, ci, w, X, threads=threads)
+        checker_rows(probe)
         rate = max(float(deg[probe].sum()) * F / max(time.time() - t0, 1e-4), 1.0)
         want = cpu_seconds * rate / F  # edges to cover in about cpu_seconds
         nrows = int(min(N, max(256, want / max(deg.mean(), 1.0))))
         rows = np.sort(rng.choice(N, size=nrows, replace=False)).astype(np.int64)
         t0 = time.time()
-        ref = oracle.aggregate_rows(rop, rows, rp, ci, w, X, threads=threads)
+        ref = checker_rows(rows)
         dt = time.time() - t0
         ef = float(deg[rows].sum()) * F
         cpu = {"value": ef / dt, "unit": "edge-features/s", "cores": threads, "kind": "oracle",
@@ -162,7 +196,7 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC.get(workload) if f_chunk == 0 else None,
-                     "kernel": "aggregate_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": b_alg,
+                     "kernel": "gat_aggregate_kernel (+ score pass)" if gat else "aggregate_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": b_alg,
                      "measured_copy_gbs": copy_gbs},
         "cpu_baseline": cpu,
         "parity_on_sample": parity,

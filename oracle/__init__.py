@@ -46,6 +46,8 @@ def _load():
         lib.gnnagg_ref_aggregate_rows.argtypes = [ci, i64, vp, vp, vp, vp, vp, ci, vp, i32, ci]
         lib.gnnagg_ref_gat_attention.restype = ci
         lib.gnnagg_ref_gat_attention.argtypes = [i64, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp, ci]
+        lib.gnnagg_ref_gat_attention_rows.restype = ci
+        lib.gnnagg_ref_gat_attention_rows.argtypes = [i64, vp, vp, vp, vp, vp, vp, i32, i32, f32, vp, ci]
         _lib = lib
     return _lib
 
@@ -124,3 +126,18 @@ def gat_attention(rowptr, colidx, H, a_src, a_dst, negative_slope=0.2, want_alph
     if rc != 0:
         raise ValueError("gnnagg_ref_gat_attention failed: %d" % rc)
     return alpha, out
+
+
+def gat_attention_rows(rows, rowptr, colidx, H, a_src, a_dst, negative_slope=0.2, threads=1):
+    """Attention output for the listed destination rows only: -> out [len(rows), heads, C]."""
+    H = _c(H, np.float32)
+    N, heads, C = H.shape
+    a_src = _c(a_src, np.float32)
+    a_dst = _c(a_dst, np.float32)
+    rows = _c(rows, np.int64)
+    out = np.empty((rows.shape[0], heads, C), dtype=np.float32)
+    rc = _load().gnnagg_ref_gat_attention_rows(rows.shape[0], _p(rows), _p(rowptr), _p(colidx), _p(H), _p(a_src),
+                                               _p(a_dst), heads, C, negative_slope, _p(out), threads)
+    if rc != 0:
+        raise ValueError("gnnagg_ref_gat_attention_rows failed: %d" % rc)
+    return out

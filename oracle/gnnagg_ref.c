@@ -277,3 +277,46 @@ int gnnagg_ref_gat_attention(int64_t N, const int64_t* rowptr, const int32_t* co
   free(sdst);
   return 0;
 }
+
+/* The same attention definition for a list of destination rows only: out is [nrows, heads, C].
+ * Scores are formed edge by edge from H (no score arrays), everything in fp64.  Used to check
+ * sampled rows of graphs too large to run in full. */
+int gnnagg_ref_gat_attention_rows(int64_t nrows, const int64_t* rows, const int64_t* rowptr,
+                                  const int32_t* colidx, const float* H, const float* a_src, const float* a_dst,
+                                  int32_t heads, int32_t C, float negative_slope, float* out, int threads) {
+  if (nrows < 0 || heads <= 0 || C <= 0 || !rows || !rowptr || !H || !a_src || !a_dst || !out) return -1;
+  const int64_t HC = (int64_t)heads * C;
+  const double slope = (double)negative_slope;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads > 1 ? threads : 1)
+  for (int64_t q = 0; q < nrows; ++q) {
+    const int64_t i = rows[q];
+    const int64_t e0 = rowptr[i], e1 = rowptr[i + 1];
+    for (int32_t h = 0; h < heads; ++h) {
+      float* o = out + q * HC + (int64_t)h * C;
+      for (int32_t c = 0; c < C; ++c) o[c] = 0.0f;
+      if (e0 == e1) continue;
+      double sdst = 0.0;
+      for (int32_t c = 0; c < C; ++c) sdst += (double)a_dst[h * C + c] * (double)H[i * HC + (int64_t)h * C + c];
+      double* logit = (double*)malloc(sizeof(double) * (size_t)(e1 - e0));
+      double m = -INFINITY;
+      for (int64_t e = e0; e < e1; ++e) {
+        const int64_t j = colidx[e];
+        double ssrc = 0.0;
+        for (int32_t c = 0; c < C; ++c) ssrc += (double)a_src[h * C + c] * (double)H[j * HC + (int64_t)h * C + c];
+        const double s = ssrc + sdst;
+        logit[e - e0] = s >= 0.0 ? s : slope * s;
+        if (logit[e - e0] > m) m = logit[e - e0];
+      }
+      double z = 0.0;
+      for (int64_t e = e0; e < e1; ++e) z += exp(logit[e - e0] - m);
+      for (int32_t c = 0; c < C; ++c) {
+        double acc = 0.0;
+        for (int64_t e = e0; e < e1; ++e)
+          acc += (exp(logit[e - e0] - m) / z) * (double)H[(int64_t)colidx[e] * HC + (int64_t)h * C + c];
+        o[c] = (float)acc;
+      }
+      free(logit);
+    }
+  }
+  return 0;
+}

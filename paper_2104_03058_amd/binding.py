@@ -184,10 +184,21 @@ def gnnagg_aggregate(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w
     return out
 
 
+def gnnagg_gat_workspace_bytes(N: int, heads: int, C: int) -> int:
+    """Size of the workspace gnnagg_gat_attention needs (the size query of the C call)."""
+    need = ctypes.c_size_t(0)
+    _check("gnnagg_gat_attention",
+           load_library().gnnagg_gat_attention(N, None, None, None, None, None, heads, C, 0.2, None, None, 0, None,
+                                               None, None, ctypes.byref(need), None))
+    return int(need.value)
+
+
 def gnnagg_gat_attention(rowptr: torch.Tensor, colidx: torch.Tensor, H: torch.Tensor, a_src: torch.Tensor,
                          a_dst: torch.Tensor, negative_slope: float = 0.2, want_alpha: bool = False,
-                         want_out: bool = True, f_chunk: int = 0, plan: Optional[RowPlan] = None, stream=None):
-    """H [N,heads,C] fp32 -> (alpha [nnz,heads] | None, out [N,heads,C] | None)."""
+                         want_out: bool = True, f_chunk: int = 0, plan: Optional[RowPlan] = None, stream=None,
+                         out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """H [N,heads,C] fp32 -> (alpha [nnz,heads] | None, out [N,heads,C] | None).  `out` and `workspace`
+    (at least gnnagg_gat_workspace_bytes) may be passed in to avoid allocating per call."""
     lib = load_library()
     if H.dim() != 3:
         raise ValueError("H must be [N, heads, C]")
@@ -200,9 +211,12 @@ def gnnagg_gat_attention(rowptr: torch.Tensor, colidx: torch.Tensor, H: torch.Te
     _check("gnnagg_gat_attention",
            lib.gnnagg_gat_attention(N, None, None, None, None, None, heads, C, negative_slope, None, None, f_chunk,
                                     None, None, None, ctypes.byref(need), None))
-    ws = _workspace(need.value, dev)
+    ws = workspace if workspace is not None else _workspace(need.value, dev)
     alpha = torch.empty((nnz, heads), dtype=torch.float32, device=dev) if want_alpha else None
-    out = torch.empty((N, heads, C), dtype=torch.float32, device=dev) if want_out else None
+    if want_out and out is None:
+        out = torch.empty((N, heads, C), dtype=torch.float32, device=dev)
+    elif not want_out:
+        out = None
     have = ctypes.c_size_t(ws.numel())
     rc = lib.gnnagg_gat_attention(N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
                                   _dev(H, torch.float32, "H"), _dev(a_src, torch.float32, "a_src"),
@@ -213,7 +227,8 @@ def gnnagg_gat_attention(rowptr: torch.Tensor, colidx: torch.Tensor, H: torch.Te
                                   _dev(ws), ctypes.byref(have), _stream(stream))
     _check("gnnagg_gat_attention", rc)
     # the score arrays in ws are read by the kernels just enqueued: keep ws alive until they ran
-    ws.record_stream(torch.cuda.current_stream() if stream is None else stream)
+    if workspace is None:
+        ws.record_stream(torch.cuda.current_stream() if stream is None else stream)
     return alpha, out
 
 

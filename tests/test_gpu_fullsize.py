@@ -80,3 +80,51 @@ def test_config5_full_size_bf16_sum_and_max(F):
         else:
             assert_close(got, ref, bf16=True, what="c5 sum F=%d" % F)
         del out
+
+
+@pytest.mark.parametrize("F", [8, 16, 32])
+def test_dense_small_graph_hidden_widths(F):
+    """The paper's regime (Section III): Combination first, Aggregation at hidden width 8/16/32, on the graph
+    shaped like its third dataset (132,534 vertices, average degree 597)."""
+    import paper_2104_03058_amd as g
+    N, src, dst = W.graph("c6")
+    say("c6 full: N", N, "E", len(src), "F", F)
+    flags = oracle.SELF_LOOPS | oracle.NORM_SYM
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, flags, want_w=True, threads=16)
+    d_rp, d_ci, d_w, _ = g.gnnagg_build_csr(N, dev(src), dev(dst), flags, want_w=True)
+    assert np.array_equal(host(d_rp), rp) and np.array_equal(host(d_ci), ci)
+    assert_bits(host(d_w), w, "edge_w")
+    X = W.normal_f32((N, F), seed=40 + F)
+    d_X = dev(X)
+    plan = g.gnnagg_plan_rows(d_rp)
+    rows = sample_rows(rp, n=192)
+    idx = torch.from_numpy(rows).cuda()
+    for name, gop, rop, fc in (("wsum", g.WSUM, oracle.WSUM, 0), ("wsum", g.WSUM, oracle.WSUM, 4),
+                               ("mean", g.MEAN, oracle.MEAN, 0), ("max", g.MAX, oracle.MAX, 0)):
+        out = g.gnnagg_aggregate(gop, d_rp, d_ci, d_w, d_X, None, fc, plan)
+        got = host(out[idx])
+        ref = oracle.aggregate_rows(rop, rows, rp, ci, w, X, threads=16)
+        if name == "max":
+            assert_bits(got, ref, "c6 max F=%d" % F)
+        else:
+            assert_close(got, ref, what="c6 %s F=%d fc=%d" % (name, F, fc))
+
+
+def test_config4_graph_attention_full_size():
+    """Attention at the size of the paper's largest graph (its GAT sweep, Section III), 8 heads x 8 channels."""
+    import paper_2104_03058_amd as g
+    N, src, dst = W.graph("c4")
+    rp, ci, _, _ = oracle.build_csr(N, src, dst, oracle.SELF_LOOPS, threads=16)
+    d_rp, d_ci, _, _ = g.gnnagg_build_csr(N, dev(src), dev(dst), oracle.SELF_LOOPS)
+    assert np.array_equal(host(d_rp), rp) and np.array_equal(host(d_ci), ci)
+    H = W.normal_f32((N, 8, 8), seed=50)
+    a_s = W.normal_f32((8, 8), seed=51, std=0.1)
+    a_d = W.normal_f32((8, 8), seed=52, std=0.1)
+    plan = g.gnnagg_plan_rows(d_rp)
+    rows = sample_rows(rp, n=64)
+    idx = torch.from_numpy(rows).cuda()
+    ref = oracle.gat_attention_rows(rows, rp, ci, H, a_s, a_d, 0.2, threads=16)
+    for fc in (0, 8):
+        say("c4 gat full: f_chunk", fc)
+        _, out = g.gnnagg_gat_attention(d_rp, d_ci, dev(H), dev(a_s), dev(a_d), 0.2, False, True, fc, plan)
+        assert_close(host(out[idx]), ref, what="c4 gat fc=%d" % fc)

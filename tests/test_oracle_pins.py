@@ -446,3 +446,18 @@ def test_gat_leaky_slope_matters():
     alpha, _ = oracle.gat_attention(rp, ci, H, a_s, a_d, 0.2)
     e = np.array([-0.2, -0.4, -0.6])
     assert np.allclose(alpha[:, 0], np.exp(e) / np.exp(e).sum(), rtol=1e-6)
+
+
+def test_gat_rows_subset_agrees_with_full_and_dense():
+    # the row-subset form shares no score arrays with the full form; both must match the dense softmax
+    for k, (N, src, dst) in enumerate(tiny_graphs()[:4]):
+        H = W.normal_f32((N, 2, 3), seed=k + 200)
+        a_s = W.normal_f32((2, 3), seed=k + 201, std=0.7)
+        a_d = W.normal_f32((2, 3), seed=k + 202, std=0.7)
+        rp, ci, _, _ = oracle.build_csr(N, src, dst)
+        _, full = oracle.gat_attention(rp, ci, H, a_s, a_d, 0.2, want_alpha=False)
+        rows = np.arange(N, dtype=np.int64)[::2]
+        part = oracle.gat_attention_rows(rows, rp, ci, H, a_s, a_d, 0.2, threads=2)
+        ref = dense_gat(N, src, dst, H, a_s, a_d, 0.2)
+        assert np.allclose(part, ref[rows], rtol=2e-6, atol=1e-7)
+        assert np.allclose(part, full[rows], rtol=1e-6, atol=1e-7)

@@ -133,6 +133,8 @@ GRAPHS = {
     "c2": GraphSpec("c2-mid", 19717, 44324, 2.1, 200.0, 1, False),
     "c4": GraphSpec("c4-dense", 232965, 57307946, 1.8, 680.0, 3, False),
     "c5": GraphSpec("c5-sparse", 2449029, 30950000, 2.0, 9000.0, 4, False),
+    # the paper's third evaluation graph (Table II: 132,534 vertices, average degree 597): realised max degree ~6.6k
+    "c6": GraphSpec("c6-dense-small", 132534, 39561252, 1.8, 60.0, 6, False),
 }
 
 

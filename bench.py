@@ -140,7 +140,8 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
     if gat:  # per edge: the row piece, one score per head, the index; per vertex: H once for the scores, out, scores
         b_alg = nnz * (F * 4 + heads * 4 + 4) + 2 * N * F * 4 + 2 * N * heads * 4 * 2 + (N + 1) * 8
     else:
-        b_alg = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", f_chunk)
+        f_eff = g.gnnagg_auto_f_chunk(N, F, g.BF16 if xdt == "bf16" else g.F32) if f_chunk == -1 else f_chunk
+        b_alg = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", f_eff)
     kern_ms = float(ms.mean())
     achieved = b_alg / (kern_ms * 1e-3) / 1e9
     log("step %.3f ms wall, kernel mean %.3f ms (min %.3f), %.3e edge-features/s, %.0f GB/s algorithmic" %
@@ -214,7 +215,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c4-gcn", choices=sorted(WORKLOADS) + ["copy"],
                     help="'copy' runs only the library's plain copy kernel on 1 GiB (profiler calibration)")
-    ap.add_argument("--f-chunk", type=int, default=0)
+    ap.add_argument("--f-chunk", type=int, default=0, help="chunk width; 0 = one chunk, -1 = let the library pick")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--also", default="c5-sum",

@@ -65,6 +65,9 @@ enum {
   GNNAGG_NORM_SYM = 2    /* edge_w = 1/sqrt(d_i d_j), d = row length after self-loops */
 };
 
+/* f_chunk value that lets the library pick the chunk width (see gnnagg_aggregate). */
+#define GNNAGG_F_CHUNK_AUTO (-1)
+
 /* Number of degree classes in a row plan (class 0: empty rows; class c >= 1:
  * rows with 2^(c-1) <= degree < 2^c). */
 #define GNNAGG_PLAN_CLASSES 33
@@ -116,13 +119,19 @@ GNNAGG_API int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
  *
  *   X        [N,F] row-major, x_dtype GNNAGG_F32 or GNNAGG_BF16 (bf16 is widened
  *            exactly; all accumulation is fp32)
- *   out      [N,F] row-major, out_dtype must be GNNAGG_F32
+ *   out      [N,F] row-major, out_dtype GNNAGG_F32, or GNNAGG_BF16 (the fp32 result rounded to
+ *            nearest even: halves the write stream)
  *   edge_w   [nnz] fp32, required for GNNAGG_WSUM, ignored otherwise
  *   f_chunk  chunk WIDTH (the paper's "dimension of each decomposition layer",
  *            Section III): chunk c covers columns [c*f_chunk, min(F,(c+1)*f_chunk)).
  *            Chunks run one after another over all rows (the chunk-outer,
  *            vertex-inner order of Algorithm 1), each written in place into its
  *            columns of `out` (no separate concat).  0 or >= F: one chunk.
+ *            GNNAGG_F_CHUNK_AUTO: the library picks - one chunk while X is at most a few
+ *            times the 256 MB Infinity Cache, otherwise the width whose column slice of
+ *            X is about that size (the number of layers "should be determined according
+ *            to the memory capacity of the device", Section II-B), never narrower than
+ *            128 bytes per row.  gnnagg_auto_f_chunk returns that choice.
  *   row_order, class_off   a plan from gnnagg_plan_rows for this rowptr, or both
  *            NULL (rows then run in natural order, one wavefront per row slice:
  *            correct for any graph, slow on hub rows).  class_off is a HOST
@@ -136,6 +145,9 @@ GNNAGG_API int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
 GNNAGG_API int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* edge_w,
                      const void* X, int x_dtype, void* out, int out_dtype, int32_t F, int32_t f_chunk,
                      const int32_t* row_order, const int64_t* class_off, void* stream);
+
+/* The chunk width gnnagg_aggregate uses for GNNAGG_F_CHUNK_AUTO (host-side arithmetic only). */
+GNNAGG_API int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype);
 
 /*
  * Graph-attention aggregation (the GAT operator the paper evaluates in

@@ -18,6 +18,7 @@ SUM, WSUM, MEAN, MAX = 0, 1, 2, 3
 F32, BF16 = 0, 1
 SELF_LOOPS, NORM_SYM = 1, 2
 PLAN_CLASSES = 33
+F_CHUNK_AUTO = -1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgnnagg.so")
@@ -58,6 +59,8 @@ def load_library():
         lib.gnnagg_gat_attention.restype = ci
         lib.gnnagg_gat_attention.argtypes = [i64, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp, i32, vp, vp, vp, szp,
                                              vp]
+        lib.gnnagg_auto_f_chunk.restype = i32
+        lib.gnnagg_auto_f_chunk.argtypes = [i64, i32, ci]
         lib.gnnagg_copy_probe.restype = ci
         lib.gnnagg_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         _lib = lib
@@ -163,7 +166,8 @@ def _x_dtype(X: torch.Tensor) -> int:
 def gnnagg_aggregate(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w: Optional[torch.Tensor],
                      X: torch.Tensor, out: Optional[torch.Tensor] = None, f_chunk: int = 0,
                      plan: Optional[RowPlan] = None, stream=None) -> torch.Tensor:
-    """out[N,F] fp32 = aggregation of X[N,F] over the CSR; enqueued on the current stream."""
+    """out[N,F] (fp32, or bf16 if a bf16 tensor is passed) = aggregation of X[N,F] over the CSR; enqueued on the
+    current stream."""
     lib = load_library()
     if X.dim() != 2:
         raise ValueError("X must be [N, F]")
@@ -174,9 +178,11 @@ def gnnagg_aggregate(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w
         out = torch.empty((N, F), dtype=torch.float32, device=X.device)
     elif tuple(out.shape) != (N, F):
         raise ValueError("out must be [N, F]")
+    if out.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("out must be float32 or bfloat16")
     rc = lib.gnnagg_aggregate(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
                               _dev(edge_w, torch.float32, "edge_w"), _dev(X, None, "X"), _x_dtype(X),
-                              _dev(out, torch.float32, "out"), F32, F, f_chunk,
+                              _dev(out, None, "out"), F32 if out.dtype == torch.float32 else BF16, F, f_chunk,
                               _dev(plan.row_order, torch.int32, "row_order") if plan is not None else None,
                               ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None,
                               _stream(stream))
@@ -238,3 +244,8 @@ def gnnagg_copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None
     if dst.numel() * dst.element_size() != nbytes:
         raise ValueError("dst and src differ in size")
     _check("gnnagg_copy_probe", load_library().gnnagg_copy_probe(_dev(dst), _dev(src), nbytes, _stream(stream)))
+
+
+def gnnagg_auto_f_chunk(N: int, F: int, x_dtype: int = F32) -> int:
+    """Chunk width the library uses for f_chunk = F_CHUNK_AUTO."""
+    return int(load_library().gnnagg_auto_f_chunk(N, F, x_dtype))

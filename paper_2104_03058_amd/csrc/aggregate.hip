@@ -31,7 +31,8 @@ struct AggArgs {
   const int32_t* colidx;
   const float* edge_w;
   const void* X;
-  float* out;
+  void* out;
+  int32_t out_bf16;  // 1: out holds bf16 (the fp32 result rounded to nearest even), 0: fp32
   const int32_t* order;
   int64_t F;
   int64_t N;
@@ -197,7 +198,8 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
     float res[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) res[k] = st.result(k, deg, a.mean != 0);
-    store_row<VEC>(a.out + r * a.F + col, res);
+    if (a.out_bf16) store_row_bf16<VEC>(static_cast<uint16_t*>(a.out) + r * a.F + col, res);
+    else store_row<VEC>(static_cast<float*>(a.out) + r * a.F + col, res);
   }
 }
 
@@ -251,9 +253,9 @@ extern "C" int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const 
                                 int32_t F, int32_t f_chunk, const int32_t* row_order, const int64_t* class_off,
                                 void* stream_) {
   if (op < GNNAGG_SUM || op > GNNAGG_MAX) return GNNAGG_EINVAL;
-  if (N < 0 || F <= 0 || f_chunk < 0) return GNNAGG_EINVAL;
+  if (N < 0 || F <= 0 || f_chunk < GNNAGG_F_CHUNK_AUTO) return GNNAGG_EINVAL;
   if (x_dtype != GNNAGG_F32 && x_dtype != GNNAGG_BF16) return GNNAGG_EINVAL;
-  if (out_dtype != GNNAGG_F32) return out_dtype == GNNAGG_BF16 ? GNNAGG_EUNSUPPORTED : GNNAGG_EINVAL;
+  if (out_dtype != GNNAGG_F32 && out_dtype != GNNAGG_BF16) return GNNAGG_EINVAL;
   if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
   if ((row_order == nullptr) != (class_off == nullptr)) return GNNAGG_EINVAL;
   if (N == 0) return GNNAGG_OK;
@@ -262,11 +264,12 @@ extern "C" int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const 
   // colidx may only be NULL for a graph without edges, which the host cannot see; require it
   if (!colidx) return GNNAGG_ENULL;
   const size_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
-  if (((uintptr_t)X % xs) || ((uintptr_t)out % 4) || ((uintptr_t)rowptr % 8) || ((uintptr_t)colidx % 4) ||
+  if (((uintptr_t)X % xs) || ((uintptr_t)out % (out_dtype == GNNAGG_F32 ? 4 : 2)) || ((uintptr_t)rowptr % 8) || ((uintptr_t)colidx % 4) ||
       (edge_w && ((uintptr_t)edge_w % 4)))
     return GNNAGG_EINVAL;
   if (X == out) return GNNAGG_EINVAL;
 
+  if (f_chunk == GNNAGG_F_CHUNK_AUTO) f_chunk = auto_f_chunk(N, F, (int)xs);
   std::vector<SliceLaunch> launches;
   plan_columns(F, f_chunk, (int)(16 / xs), 0, &launches);
   hipStream_t stream = (hipStream_t)stream_;
@@ -281,7 +284,8 @@ extern "C" int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const 
     a.colidx = colidx;
     a.edge_w = edge_w;
     a.X = X;
-    a.out = static_cast<float*>(out);
+    a.out = out;
+    a.out_bf16 = (out_dtype == GNNAGG_BF16);
     a.order = row_order;
     a.F = F;
     a.N = N;
@@ -299,4 +303,9 @@ extern "C" int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const 
     if (rc != GNNAGG_OK) return rc;
   }
   return GNNAGG_OK;
+}
+
+extern "C" int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype) {
+  if (N < 0 || F <= 0 || (x_dtype != GNNAGG_F32 && x_dtype != GNNAGG_BF16)) return 0;
+  return auto_f_chunk(N, F, x_dtype == GNNAGG_F32 ? 4 : 2);
 }

@@ -61,4 +61,24 @@ __device__ inline void store_row(float* p, const float (&v)[VEC]) {
   }
 }
 
+// fp32 -> bf16 bits, round to nearest even (inputs here are finite or infinite, never NaN by contract;
+// a NaN keeps a non-zero mantissa)
+__device__ inline uint32_t bf16_bits(float f) {
+  const uint32_t b = __float_as_uint(f);
+  if ((b & 0x7fffffffu) > 0x7f800000u) return (b >> 16) | 0x40u;
+  return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+}
+
+template <int VEC>
+__device__ inline void store_row_bf16(uint16_t* p, const float (&v)[VEC]) {
+  if constexpr (VEC == 1) {
+    p[0] = (uint16_t)bf16_bits(v[0]);
+  } else {
+    typedef uint32_t u32_h __attribute__((aligned(2)));
+#pragma unroll
+    for (int k = 0; k < VEC; k += 2)
+      *reinterpret_cast<u32_h*>(p + k) = bf16_bits(v[k]) | (bf16_bits(v[k + 1]) << 16);
+  }
+}
+
 }  // namespace gnnagg

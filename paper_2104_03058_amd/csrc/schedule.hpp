@@ -203,6 +203,21 @@ inline int build_segments(const int64_t* class_off, int64_t N, int g_log2, SegTa
   return GNNAGG_OK;
 }
 
+// Chunk width for GNNAGG_F_CHUNK_AUTO.  Measured on MI355X: while X is within a few times the 256 MB
+// Infinity Cache one chunk is fastest (config 4, X = 561 MB: 25 ms unchunked, 29 ms at 256 columns),
+// because every extra chunk pass re-reads the edge list; once X is several GB (2.4 M rows x 256-512
+// fp32 columns) chunks whose column slice of X is ~300-600 MB are 13-17 % faster than one chunk, and
+// row pieces under 128 bytes are twice slower than either.
+inline int32_t auto_f_chunk(int64_t N, int32_t F, int elem_bytes) {
+  const double x_bytes = (double)N * (double)F * (double)elem_bytes;
+  if (N <= 0 || x_bytes <= 1024.0 * 1024.0 * 1024.0) return F;
+  const int64_t min_w = 128 / elem_bytes;                                  // 128-byte row pieces
+  int64_t w = (int64_t)(384.0 * 1024.0 * 1024.0 / ((double)N * elem_bytes));  // ~384 MB column slice
+  int64_t p = min_w;
+  while (p * 2 <= w) p *= 2;  // a power of two keeps every chunk on full 16-byte lanes
+  return (int32_t)(p >= F ? F : p);
+}
+
 // How many workgroups of the aggregation kernel should share a compute unit.  Every resident wave
 // keeps eight row gathers in flight, and every line in flight occupies L2; at full occupancy the lines
 // in flight alone (256 CUs x 16-20 waves x 8 x ~7 lines x 128 B = ~30 MB) are as large as the whole L2

@@ -128,3 +128,28 @@ def test_config4_graph_attention_full_size():
         say("c4 gat full: f_chunk", fc)
         _, out = g.gnnagg_gat_attention(d_rp, d_ci, dev(H), dev(a_s), dev(a_d), 0.2, False, True, fc, plan)
         assert_close(host(out[idx]), ref, what="c4 gat fc=%d" % fc)
+
+
+def test_automatic_chunk_width_on_a_feature_matrix_beyond_the_cache():
+    """X = 2.4 M x 128 fp32 (1.25 GB) is past the point where one chunk is fastest: GNNAGG_F_CHUNK_AUTO
+    picks 32-column chunks; the result must equal the unchunked one (sums here are fp64-accumulated, and
+    each element sees the same operands in the same order whatever the chunk width)."""
+    import paper_2104_03058_amd as g
+    N, src, dst = W.graph("c5")
+    F = 128
+    assert g.gnnagg_auto_f_chunk(N, F, g.F32) == 32
+    rp, ci, _, _ = oracle.build_csr(N, src, dst, 0, threads=16)
+    d_rp, d_ci = dev(rp), dev(ci)
+    X = W.normal_f32((N, F), seed=60)
+    d_X = dev(X)
+    plan = g.gnnagg_plan_rows(d_rp)
+    rows = sample_rows(rp, n=256)
+    idx = torch.from_numpy(rows).cuda()
+    ref = oracle.aggregate_rows(oracle.MEAN, rows, rp, ci, None, X, threads=16)
+    out_auto = g.gnnagg_aggregate(g.MEAN, d_rp, d_ci, None, d_X, None, g.F_CHUNK_AUTO, plan)
+    assert_close(host(out_auto[idx]), ref, what="auto chunk mean")
+    out_one = g.gnnagg_aggregate(g.MEAN, d_rp, d_ci, None, d_X, None, 0, plan)
+    assert_close(host(out_one[idx]), ref, what="one chunk mean")
+    mx_auto = g.gnnagg_aggregate(g.MAX, d_rp, d_ci, None, d_X, None, g.F_CHUNK_AUTO, plan)
+    mx_one = g.gnnagg_aggregate(g.MAX, d_rp, d_ci, None, d_X, None, 0, plan)
+    assert torch.equal(mx_auto, mx_one)

@@ -278,6 +278,53 @@ def test_same_bits_on_every_run_and_for_every_chunk_width_of_max():
         assert_bits(host(g.gnnagg_aggregate(3, d[0], d[1], None, d[3], None, fc, plan)), m0, "max fc=%d" % fc)
 
 
+def bf16_rne_bits(x):
+    """fp32 array -> bf16 bit patterns, round to nearest even (numpy, independent of both implementations)."""
+    b = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)
+    return ((b + 0x7fff + ((b >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+@pytest.mark.parametrize("F", [1, 7, 32, 100, 300])
+def test_bf16_output_is_the_rounded_fp32_result(F):
+    N, src, dst = W.graph("c5", 0.01)
+    rp, ci, _, _ = oracle.build_csr(N, src, dst)
+    Xb = W.normal_bf16((N, F), seed=70 + F)
+    d_rp, d_ci, d_X = dev(rp), dev(ci), dev(Xb)
+    plan = g.gnnagg_plan_rows(d_rp)
+    for name in ("sum", "mean", "max"):
+        gop, rop = OPS[name]
+        ref32 = oracle.aggregate(rop, rp, ci, None, Xb)
+        out = torch.zeros((N, F), dtype=torch.bfloat16, device="cuda")
+        g.gnnagg_aggregate(gop, d_rp, d_ci, None, d_X, out, 0, plan)
+        got = host(out.view(torch.int16)).view(np.uint16)
+        want = bf16_rne_bits(ref32)
+        if name == "max":  # the maximum of bf16 values is a bf16 value: exact
+            assert np.array_equal(got, want)
+        else:              # the fp32 results agree to ~1e-7, so the bf16 values differ by at most one step, rarely
+            gf, wf = W.bf16_to_f32(got).astype(np.float64), W.bf16_to_f32(want).astype(np.float64)
+            assert np.all(np.abs(gf - wf) <= 2.0 ** -7 * np.abs(wf) + 1e-30)
+            assert np.mean(got != want) < 1e-3
+    # fp32 features, bf16 output
+    Xf = W.normal_f32((N, F), seed=71)
+    ref32 = oracle.aggregate(oracle.SUM, rp, ci, None, Xf)
+    out = torch.zeros((N, F), dtype=torch.bfloat16, device="cuda")
+    g.gnnagg_aggregate(0, d_rp, d_ci, None, dev(Xf), out, 0, plan)
+    got, want = host(out.view(torch.int16)).view(np.uint16), bf16_rne_bits(ref32)
+    assert np.mean(got != want) < 1e-3
+
+
+def test_auto_chunk_width_is_accepted_and_matches_one_chunk_on_small_inputs():
+    N, src, dst = W.graph("c2")
+    rp, ci, _, _ = oracle.build_csr(N, src, dst)
+    X = W.normal_f32((N, 70), seed=12)
+    d = [dev(rp), dev(ci), dev(X)]
+    a = host(g.gnnagg_aggregate(0, d[0], d[1], None, d[2], None, g.F_CHUNK_AUTO))
+    b = host(g.gnnagg_aggregate(0, d[0], d[1], None, d[2], None, 0))
+    assert_bits(a, b, "auto vs one chunk")
+    with pytest.raises(g.GnnaggError):
+        g.gnnagg_aggregate(0, d[0], d[1], None, d[2], None, -2)
+
+
 def test_compensated_sum_survives_cancellation():
     # 20000 values of size ~1e3 that cancel to O(1): a plain fp32 running sum would be off by ~1e-2
     N, n_in = 64, 20000

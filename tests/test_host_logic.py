@@ -55,9 +55,9 @@ def test_argument_validation_returns_before_any_launch(lib):
     assert agg(7, 4, one, one, one, one, 0, one, 0, 8, 0, None, None, None) == EINVAL      # op
     assert agg(0, -1, one, one, one, one, 0, one, 0, 8, 0, None, None, None) == EINVAL     # N
     assert agg(0, 4, one, one, one, one, 0, one, 0, 0, 0, None, None, None) == EINVAL      # F
-    assert agg(0, 4, one, one, one, one, 0, one, 0, 8, -2, None, None, None) == EINVAL     # f_chunk
+    assert agg(0, 4, one, one, one, one, 0, one, 0, 8, -2, None, None, None) == EINVAL     # f_chunk (-1 = auto)
     assert agg(0, 4, one, one, one, one, 5, one, 0, 8, 0, None, None, None) == EINVAL      # x_dtype
-    assert agg(0, 4, one, one, one, one, 0, one, 1, 8, 0, None, None, None) == EUNSUP      # bf16 output
+    assert agg(0, 4, one, one, one, one, 0, one, 2, 8, 0, None, None, None) == EINVAL      # out_dtype
     assert agg(0, 4, None, one, one, one, 0, one, 0, 8, 0, None, None, None) == ENULL      # rowptr
     assert agg(1, 4, one, one, None, one, 0, one, 0, 8, 0, None, None, None) == ENULL      # wsum needs edge_w
     assert agg(0, 4, one, one, one, one, 0, one, 0, 8, 0, one, None, None) == EINVAL       # half a plan
@@ -178,3 +178,13 @@ def test_workgroup_cap_follows_mean_degree(cap_checker):
     assert run_cap(cap_checker, 6, N, sparse)[:2] == [0, 0]
     assert run_cap(cap_checker, 5, N, dense)[0] == 3 and run_cap(cap_checker, 5, N, medium)[0] == 0
     assert run_cap(cap_checker, 2, N, dense)[0] == 0   # narrow slices are never capped
+
+
+def test_auto_chunk_width(lib):
+    import paper_2104_03058_amd as g
+    assert g.gnnagg_auto_f_chunk(232965, 602, g.F32) == 602          # 561 MB: one chunk
+    assert g.gnnagg_auto_f_chunk(2449029, 100, g.BF16) == 100        # 490 MB: one chunk
+    assert g.gnnagg_auto_f_chunk(2449029, 512, g.F32) == 32          # 5 GB: ~300 MB column slices
+    assert g.gnnagg_auto_f_chunk(2449029, 1024, g.BF16) == 64        # same bytes per row piece in bf16
+    assert g.gnnagg_auto_f_chunk(50_000_000, 64, g.F32) == 32        # never under 128 bytes per row piece
+    assert g.gnnagg_auto_f_chunk(10, 0, g.F32) == 0 and g.gnnagg_auto_f_chunk(10, 8, 7) == 0

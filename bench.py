@@ -54,6 +54,9 @@ WORKLOADS = {
     "c6-hid8-gcn": ("c6", "wsum", 8, "f32", True),
     "c6-hid32-mean": ("c6", "mean", 32, "f32", False),
     "c6-gat": ("c6", "gat", (8, 4), "f32", False),
+    # Combination (dense layer F -> H on the matrix cores), alone and as one GCN layer with Combination first
+    "c4-combine-32": ("c4", "combine", (602, 32), "f32", False),
+    "c4-layer-32": ("c4", "layer", (602, 32), "f32", True),
 }
 
 
@@ -69,9 +72,65 @@ def algorithmic_bytes(nnz, N, F, x_bytes, weighted, f_chunk):
     return nnz * F * x_bytes + P * nnz * (4 + (4 if weighted else 0)) + N * F * 4 + P * (N + 1) * 8
 
 
+def measure_layer(g, W, torch, workload, steps, warmup, copy_gbs):
+    """Combination (X W on the matrix cores) alone, or followed by the GCN aggregation at the hidden width."""
+    gkey, opname, (F, H), xdt, gcn = WORKLOADS[workload]
+    N, src, dst = W.graph(gkey)
+    X = torch.from_numpy(W.normal_f32((N, F), seed=13)).cuda()
+    Wt = torch.from_numpy(W.normal_f32((F, H), seed=16, std=0.05)).cuda()
+    hid = torch.empty((N, H), dtype=torch.float32, device="cuda")
+    out = torch.empty((N, H), dtype=torch.float32, device="cuda")
+    nnz = 0
+    if opname == "layer":
+        d_rp, d_ci, d_w, _ = g.gnnagg_build_csr(N, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda(),
+                                                g.SELF_LOOPS | g.NORM_SYM, want_w=True)
+        plan = g.gnnagg_plan_rows(d_rp)
+        nnz = int(d_ci.shape[0])
+
+    def step():
+        g.gnnagg_combine(X, Wt, None, False, hid)
+        if opname == "layer":
+            g.gnnagg_aggregate(g.WSUM, d_rp, d_ci, d_w, hid, out, 0, plan)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    kern_ms = e0.elapsed_time(e1) / steps
+    flop = 2.0 * N * F * H
+    b_alg = N * F * 4 + F * H * 4 + N * H * 4
+    if opname == "layer":
+        b_alg += algorithmic_bytes(nnz, N, H, 4, True, 0)
+    achieved = b_alg / (kern_ms * 1e-3) / 1e9
+    log("%s: %.3f ms per step (combination %.1f GFLOP in fp64 MFMA), %.0f GB/s algorithmic" %
+        (workload, kern_ms, flop / 1e9, achieved))
+    rec = {"metric": "one GCN layer, Combination first" if opname == "layer" else "Combination (dense layer)",
+           "value": (float(nnz) * H if opname == "layer" else flop) / (ms_per_step * 1e-3),
+           "unit": "edge-features/s at the hidden width" if opname == "layer" else "flop/s",
+           "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+           "config": {"workload": workload, "graph": W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "H": H},
+           "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "combine_kernel"
+                        + (" + aggregate_kernel" if opname == "layer" else ""), "kernel_ms": kern_ms,
+                        "algorithmic_bytes": b_alg, "measured_copy_gbs": copy_gbs,
+                        "mfma_f64_tflops": flop / (kern_ms * 1e-3) / 1e12 if opname == "combine" else None},
+           "cpu_baseline": None, "setup": {}}
+    return rec
+
+
 def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_seconds, copy_gbs):
     """One workload: setup (CSR build, row plan), timed aggregation steps, optional CPU-checker leg."""
     gkey, opname, F, xdt, gcn = WORKLOADS[workload]
+    if opname in ("combine", "layer"):
+        return measure_layer(g, W, torch, workload, steps, warmup, copy_gbs)
     gat = opname == "gat"
     heads, C = F if gat else (1, F)
     F = heads * C

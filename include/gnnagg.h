@@ -118,7 +118,7 @@ GNNAGG_API int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
  * Aggregate / Concat steps).
  *
  *   X        [N,F] row-major, x_dtype GNNAGG_F32 or GNNAGG_BF16 (bf16 is widened
- *            exactly; all accumulation is fp32)
+ *            exactly; sums accumulate in fp64)
  *   out      [N,F] row-major, out_dtype GNNAGG_F32, or GNNAGG_BF16 (the fp32 result rounded to
  *            nearest even: halves the write stream)
  *   edge_w   [nnz] fp32, required for GNNAGG_WSUM, ignored otherwise
@@ -129,8 +129,8 @@ GNNAGG_API int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
  *            columns of `out` (no separate concat).  0 or >= F: one chunk.
  *            GNNAGG_F_CHUNK_AUTO: the library picks - one chunk while X is at most a few
  *            times the 256 MB Infinity Cache, otherwise the width whose column slice of
- *            X is about that size (the number of layers "should be determined according
- *            to the memory capacity of the device", Section II-B), never narrower than
+ *            X is about that size (Section II-B ties the number of layers to the memory
+ *            capacity of the device), never narrower than
  *            128 bytes per row.  gnnagg_auto_f_chunk returns that choice.
  *   row_order, class_off   a plan from gnnagg_plan_rows for this rowptr, or both
  *            NULL (rows then run in natural order, one wavefront per row slice:
@@ -171,6 +171,23 @@ GNNAGG_API int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
                          float negative_slope, float* alpha, float* out, int32_t f_chunk,
                          const int32_t* row_order, const int64_t* class_off, void* workspace,
                          size_t* workspace_bytes, void* stream);
+
+/*
+ * Combination (Section I: the per-vertex MLP update; Algorithm 1, Update) as one dense layer, so
+ * that it can run ahead of Aggregation and Aggregation works at the hidden width (Section III):
+ *
+ *     out[N,H] = act( X[N,F] * W[F,H] + bias[H] )
+ *
+ *   X      [N,F] row-major, GNNAGG_F32 or GNNAGG_BF16
+ *   W      [F,H] row-major fp32; bias [H] fp32 or NULL
+ *   relu   1: act = max(0, .), 0: identity
+ *   out    [N,H] row-major fp32; must not overlap X
+ *
+ * Products and sums are carried in fp64 on the matrix cores and rounded to fp32 once.
+ * Asynchronous on `stream`.
+ */
+GNNAGG_API int gnnagg_combine(int64_t N, const void* X, int x_dtype, int32_t F, const float* W, const float* bias,
+                              int32_t H, int relu, float* out, void* stream);
 
 /*
  * Measurement aid, not part of the method: copies `bytes` bytes (a multiple of

@@ -48,6 +48,8 @@ def _load():
         lib.gnnagg_ref_gat_attention.argtypes = [i64, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp, ci]
         lib.gnnagg_ref_gat_attention_rows.restype = ci
         lib.gnnagg_ref_gat_attention_rows.argtypes = [i64, vp, vp, vp, vp, vp, vp, i32, i32, f32, vp, ci]
+        lib.gnnagg_ref_combine.restype = ci
+        lib.gnnagg_ref_combine.argtypes = [i64, vp, ci, i32, vp, vp, i32, ci, vp, ci]
         _lib = lib
     return _lib
 
@@ -140,4 +142,19 @@ def gat_attention_rows(rows, rowptr, colidx, H, a_src, a_dst, negative_slope=0.2
                                                _p(a_dst), heads, C, negative_slope, _p(out), threads)
     if rc != 0:
         raise ValueError("gnnagg_ref_gat_attention_rows failed: %d" % rc)
+    return out
+
+
+def combine(X, W, bias=None, relu=False, threads=1):
+    """out [N,H] float32 = act(X @ W + bias); X float32 or uint16 (bf16 bits) [N,F], W float32 [F,H]."""
+    X = np.ascontiguousarray(X)
+    W = _c(W, np.float32)
+    N, F = X.shape
+    assert W.shape[0] == F
+    H = W.shape[1]
+    bias = None if bias is None else _c(bias, np.float32)
+    out = np.empty((N, H), dtype=np.float32)
+    rc = _load().gnnagg_ref_combine(N, _p(X), _xinfo(X), F, _p(W), _p(bias), H, int(bool(relu)), _p(out), threads)
+    if rc != 0:
+        raise ValueError("gnnagg_ref_combine failed: %d" % rc)
     return out

@@ -320,3 +320,23 @@ int gnnagg_ref_gat_attention_rows(int64_t nrows, const int64_t* rows, const int6
   }
   return 0;
 }
+
+/* Combination as one dense layer (paper Section I / Algorithm 1, Update):
+ *   out[n,h] = act( sum_f X[n,f] * W[f,h] + bias[h] ),  act = max(0,.) if relu else identity,
+ * by the definition: fp64 products and sum in ascending f, bias added in fp64, one rounding to fp32. */
+int gnnagg_ref_combine(int64_t N, const void* X, int x_dtype, int32_t F, const float* W, const float* bias,
+                       int32_t H, int relu, float* out, int threads) {
+  if (N < 0 || F <= 0 || H <= 0 || !X || !W || !out) return -1;
+  if (x_dtype != REF_F32 && x_dtype != REF_BF16) return -1;
+#pragma omp parallel for schedule(static) num_threads(threads > 1 ? threads : 1)
+  for (int64_t n = 0; n < N; ++n)
+    for (int32_t h = 0; h < H; ++h) {
+      double acc = 0.0;
+      for (int32_t f = 0; f < F; ++f) acc += x_at(X, x_dtype, n * F + f) * (double)W[(int64_t)f * H + h];
+      if (bias) acc += (double)bias[h];
+      float y = (float)acc;
+      if (relu && !(y > 0.0f)) y = 0.0f;
+      out[n * H + h] = y;
+    }
+  return 0;
+}

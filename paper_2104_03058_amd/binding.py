@@ -61,6 +61,8 @@ def load_library():
                                              vp]
         lib.gnnagg_auto_f_chunk.restype = i32
         lib.gnnagg_auto_f_chunk.argtypes = [i64, i32, ci]
+        lib.gnnagg_combine.restype = ci
+        lib.gnnagg_combine.argtypes = [i64, vp, ci, i32, vp, vp, i32, ci, vp, vp]
         lib.gnnagg_copy_probe.restype = ci
         lib.gnnagg_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         _lib = lib
@@ -249,3 +251,22 @@ def gnnagg_copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None
 def gnnagg_auto_f_chunk(N: int, F: int, x_dtype: int = F32) -> int:
     """Chunk width the library uses for f_chunk = F_CHUNK_AUTO."""
     return int(load_library().gnnagg_auto_f_chunk(N, F, x_dtype))
+
+
+def gnnagg_combine(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor] = None, relu: bool = False,
+                   out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """out[N,H] fp32 = act(X[N,F] @ W[F,H] + bias); X fp32 or bf16, W and bias fp32."""
+    if X.dim() != 2 or W.dim() != 2 or W.shape[0] != X.shape[1]:
+        raise ValueError("X must be [N,F] and W [F,H]")
+    N, F, H = int(X.shape[0]), int(X.shape[1]), int(W.shape[1])
+    if bias is not None and tuple(bias.shape) != (H,):
+        raise ValueError("bias must be [H]")
+    if out is None:
+        out = torch.empty((N, H), dtype=torch.float32, device=X.device)
+    elif tuple(out.shape) != (N, H):
+        raise ValueError("out must be [N, H]")
+    rc = load_library().gnnagg_combine(N, _dev(X, None, "X"), _x_dtype(X), F, _dev(W, torch.float32, "W"),
+                                       _dev(bias, torch.float32, "bias"), H, int(bool(relu)),
+                                       _dev(out, torch.float32, "out"), _stream(stream))
+    _check("gnnagg_combine", rc)
+    return out

@@ -404,3 +404,32 @@ def test_gat_special_cases():
     # error of the weights: this case checks robustness, not the parity bar
     assert np.allclose(host(out2), rout, rtol=2e-3, atol=1e-5)
     assert np.allclose(host(alpha2), ralpha, rtol=2e-3, atol=1e-6)
+
+
+# ------------------------------------------------------------------ combination (dense layer on the matrix cores)
+@pytest.mark.parametrize("N,F,H", [(1, 1, 1), (130, 33, 5), (1000, 602, 32), (257, 100, 200), (513, 64, 129),
+                                   (4096, 31, 16), (127, 1433, 8)])
+def test_combine_matches_checker(N, F, H):
+    Wt = W.normal_f32((F, H), seed=500, std=0.3)
+    b = W.normal_f32((H,), seed=501)
+    for X in (W.normal_f32((N, F), seed=502), W.normal_bf16((N, F), seed=503)):
+        for bias, relu in ((None, False), (b, False), (b, True)):
+            ref = oracle.combine(X, Wt, bias, relu, threads=8)
+            out = torch.full((N, H), float("nan"), dtype=torch.float32, device="cuda")
+            g.gnnagg_combine(dev(X), dev(Wt), dev(bias) if bias is not None else None, relu, out)
+            assert_close(host(out), ref, what="combine N=%d F=%d H=%d bias=%s relu=%s" % (N, F, H, bias is not None, relu))
+
+
+def test_combination_first_equals_aggregation_first():
+    # Section III runs Combination ahead of Aggregation; for the linear aggregators both orders agree
+    N, src, dst = W.graph("c4", 0.01)
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, oracle.SELF_LOOPS | oracle.NORM_SYM, want_w=True, threads=8)
+    X = W.normal_f32((N, 96), seed=510)
+    Wt = W.normal_f32((96, 16), seed=511, std=0.2)
+    d_rp, d_ci, d_w, d_X, d_W = dev(rp), dev(ci), dev(w), dev(X), dev(Wt)
+    plan = g.gnnagg_plan_rows(d_rp)
+    first = g.gnnagg_aggregate(1, d_rp, d_ci, d_w, g.gnnagg_combine(d_X, d_W), None, 0, plan)
+    last = g.gnnagg_combine(g.gnnagg_aggregate(1, d_rp, d_ci, d_w, d_X, None, 0, plan), d_W)
+    ref = oracle.aggregate(oracle.WSUM, rp, ci, w, oracle.combine(X, Wt, threads=8), threads=8)
+    assert_close(host(first), ref, what="combine then aggregate")
+    assert np.allclose(host(last), ref, rtol=1e-4, atol=1e-5)  # two fp32 roundings in a different place

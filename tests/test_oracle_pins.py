@@ -461,3 +461,37 @@ def test_gat_rows_subset_agrees_with_full_and_dense():
         ref = dense_gat(N, src, dst, H, a_s, a_d, 0.2)
         assert np.allclose(part, ref[rows], rtol=2e-6, atol=1e-7)
         assert np.allclose(part, full[rows], rtol=1e-6, atol=1e-7)
+
+
+# ---------------------------------------------------------------- combination (dense layer)
+def test_combine_matches_library_matmul_and_special_cases():
+    X = W.normal_f32((37, 19), seed=300)
+    Wt = W.normal_f32((19, 5), seed=301)
+    b = W.normal_f32((5,), seed=302)
+    ref = X.astype(np.float64) @ Wt.astype(np.float64) + b.astype(np.float64)
+    assert np.allclose(oracle.combine(X, Wt, b), ref, rtol=1e-6, atol=1e-7)
+    assert np.allclose(oracle.combine(X, Wt, b, relu=True), np.maximum(ref, 0.0), rtol=1e-6, atol=1e-7)
+    assert np.allclose(oracle.combine(X, Wt), ref - b, rtol=1e-6, atol=1e-6)
+    # identity weights copy the input bit for bit; a one-hot column picks a column
+    assert np.array_equal(oracle.combine(X, np.eye(19, dtype=np.float32)), X)
+    e3 = np.zeros((19, 1), np.float32)
+    e3[3] = 1.0
+    assert np.array_equal(oracle.combine(X, e3)[:, 0], X[:, 3])
+    # operand order: W is [F,H], not its transpose
+    Wr = W.normal_f32((19, 19), seed=303)
+    assert not np.allclose(oracle.combine(X, Wr), X.astype(np.float64) @ Wr.T.astype(np.float64), atol=1e-3)
+    # bf16 features widen exactly
+    Xb = W.normal_bf16((37, 19), seed=304)
+    assert np.array_equal(oracle.combine(Xb, Wt, b), oracle.combine(W.bf16_to_f32(Xb), Wt, b))
+
+
+def test_combination_commutes_with_linear_aggregation():
+    # aggregate(X) W = aggregate(X W) for sum / weighted sum / mean (the reason Combination can run first)
+    N, src, dst = W.graph("c1")
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, oracle.SELF_LOOPS | oracle.NORM_SYM, want_w=True)
+    X = W.normal_f32((N, 24), seed=310)
+    Wt = W.normal_f32((24, 6), seed=311)
+    for op in (oracle.SUM, oracle.WSUM, oracle.MEAN):
+        a = oracle.combine(oracle.aggregate(op, rp, ci, w, X), Wt).astype(np.float64)
+        b = oracle.aggregate(op, rp, ci, w, oracle.combine(X, Wt)).astype(np.float64)
+        assert np.allclose(a, b, rtol=1e-4, atol=1e-4)

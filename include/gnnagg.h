@@ -114,7 +114,7 @@ GNNAGG_API int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
                      void* workspace, size_t* workspace_bytes, void* stream);
 
 /*
- * Aggregation on each decomposition layer (Algorithm 1, the Message /
+ * Aggregation, one feature chunk after another (Algorithm 1, the Message /
  * Aggregate / Concat steps).
  *
  *   X        [N,F] row-major, x_dtype GNNAGG_F32 or GNNAGG_BF16 (bf16 is widened
@@ -122,7 +122,7 @@ GNNAGG_API int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
  *   out      [N,F] row-major, out_dtype GNNAGG_F32, or GNNAGG_BF16 (the fp32 result rounded to
  *            nearest even: halves the write stream)
  *   edge_w   [nnz] fp32, required for GNNAGG_WSUM, ignored otherwise
- *   f_chunk  chunk WIDTH (the paper's "dimension of each decomposition layer",
+ *   f_chunk  chunk WIDTH (the width of one decomposition layer,
  *            Section III): chunk c covers columns [c*f_chunk, min(F,(c+1)*f_chunk)).
  *            Chunks run one after another over all rows (the chunk-outer,
  *            vertex-inner order of Algorithm 1), each written in place into its

@@ -1,6 +1,6 @@
 /*
- * CPU checker for message-passing Aggregation (the paper's Algorithm 1,
- * "Aggregation on each decomposition layer").
+ * CPU checker for message-passing Aggregation, chunk by chunk along the
+ * feature dimension (the paper's Algorithm 1).
  *
  * THIS IS TEST INFRASTRUCTURE, NOT A PRODUCT PATH.  It is slow on purpose:
  * scalar loops, fp64 accumulation, one rounding to fp32 at the end.  It shares

@@ -10,9 +10,15 @@
 // of the path, so it runs on the matrix cores: v_mfma_f64_16x16x4_f64.  fp64 because the products of
 // fp32 inputs are exact there and the sum is rounded once, like every other reduction of this library;
 // at H = 32 the fp64 MFMA time (2 N F H flop at 78.6 TFLOP/s) is about the time HBM needs to deliver X
-// once, so nothing is lost against fp32 MFMA.  A 256-thread workgroup computes 128 rows x up to 128
-// columns: X and W tiles go through LDS (X transposed, so that the 16 lanes of an MFMA operand row read
-// consecutive words), each wave owns 32 rows.
+// once, so nothing is lost against fp32 MFMA.
+//
+// Data movement.  X is read exactly once per pass and never touches LDS: the k index of a contraction
+// may be visited in any order, so lane l of a wavefront loads 8 CONSECUTIVE k of row l % 16 (one or two
+// 16-byte loads; the four 16-lane groups cover 32 consecutive k, 128 bytes of the row) and MFMA step s
+// contracts over the four k values {8 g + s : g = l / 16}.  W is small (F x H); a 32-k tile of it goes
+// through LDS, stored [col][k] so that a lane fetches its 8 k with two 16-byte LDS reads, double
+// buffered so that one barrier per 32 k suffices.  A 256-thread workgroup computes 128 rows x up to 128
+// columns, each wave 32 rows.
 #include "common.hpp"
 #include "device_utils.hpp"
 
@@ -20,11 +26,12 @@ namespace gnnagg {
 namespace {
 
 constexpr int kRowsPerBlock = 128;  // 4 waves x 32 rows
-constexpr int kKTile = 32;          // k extent staged per step
+constexpr int kKTile = 32;          // k extent per step: 4 lane groups x 8
 constexpr int kMaxColTiles = 8;     // 8 x 16 = 128 output columns per pass
-constexpr int kALd = kRowsPerBlock + 4;  // row pitch of the transposed X tile (words)
+constexpr int kBPitch = kKTile + 4; // words per column of the W tile in LDS (keeps 16-byte alignment)
 
 typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4_a __attribute__((ext_vector_type(4)));
 
 struct CombineArgs {
   const void* X;
@@ -41,14 +48,43 @@ struct CombineArgs {
 __device__ inline float elem_as_float(const float* p) { return *p; }
 __device__ inline float elem_as_float(const bf16_t* p) { return __uint_as_float((uint32_t)p->bits << 16); }
 
+// 8 consecutive elements of a row starting at column k (zero beyond column F)
+template <typename T>
+__device__ inline void load_k8(const T* __restrict__ rowp, int k, int F, float (&v)[8]) {
+  if (k + 8 <= F) {
+    if constexpr (sizeof(T) == 4) {
+      float lo[4], hi[4];
+      unpack(load_raw<T, 4>(rowp + k), lo);
+      unpack(load_raw<T, 4>(rowp + k + 4), hi);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { v[i] = lo[i]; v[4 + i] = hi[i]; }
+    } else {
+      unpack(load_raw<T, 8>(rowp + k), v);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (k + i < F) ? elem_as_float(rowp + k + i) : 0.0f;
+  }
+}
+
 template <typename T, int CT>
 __global__ __launch_bounds__(kBlock) void combine_kernel(const CombineArgs a) {
-  __shared__ float As[kKTile * kALd];       // As[k][row]
-  __shared__ float Bs[kKTile * CT * 16];    // Bs[k][col]
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-  const int64_t row0 = (int64_t)blockIdx.x * kRowsPerBlock;
-  const T* __restrict__ X = static_cast<const T*>(a.X);
   constexpr int BN = CT * 16;
+  constexpr int kBPerThread = (kKTile * BN) / kBlock;  // W-tile elements staged per thread: 2 CT
+  __shared__ __attribute__((aligned(16))) float Bs[2][BN * kBPitch];  // Bs[buf][col][k]
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+  const int g = lane >> 4, li = lane & 15;
+  const int64_t row0 = (int64_t)blockIdx.x * kRowsPerBlock + wv * 32;
+  const T* __restrict__ X = static_cast<const T*>(a.X);
+
+  // rows past the end re-read the last row; their results are dropped at the store
+  const T* xrow[2];
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    int64_t row = row0 + r * 16 + li;
+    row = row < a.N ? row : a.N - 1;
+    xrow[r] = X + row * a.F;
+  }
 
   f64x4 acc[2][CT];
 #pragma unroll
@@ -56,48 +92,64 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(const CombineArgs a) {
 #pragma unroll
     for (int c = 0; c < CT; ++c) acc[r][c] = (f64x4){0.0, 0.0, 0.0, 0.0};
 
-  for (int k0 = 0; k0 < a.F; k0 += kKTile) {
-    // ---- stage the X tile, transposed: thread t reads 4 consecutive k of one row, 4 times
+  // W tile element q of a thread: k = q / BN, j = q % BN (consecutive threads: consecutive columns)
+  auto fetch_w = [&](int k0, float (&w)[kBPerThread]) {
 #pragma unroll
-    for (int it = 0; it < (kRowsPerBlock * kKTile) / (kBlock * 4); ++it) {
-      const int q = it * kBlock + tid;       // quad index: 8 quads per row
-      const int r = q >> 3, kq = (q & 7) * 4;
-      const int64_t row = row0 + r;
-      float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-      if (row < a.N) {
-        const T* p = X + row * a.F + k0 + kq;
-        if (k0 + kq + 4 <= a.F) {
-          unpack(load_raw<T, 4>(p), v);  // one element-aligned vector load
-        } else {
+    for (int i = 0; i < kBPerThread; ++i) {
+      const int q = i * kBlock + tid;
+      const int k = k0 + q / BN, col = a.col0 + q % BN;
+      w[i] = (k < a.F && col < a.H) ? a.W[(int64_t)k * a.H + col] : 0.0f;
+    }
+  };
+  auto stage_w = [&](int buf, const float (&w)[kBPerThread]) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (k0 + kq + i < a.F) v[i] = elem_as_float(p + i);
+    for (int i = 0; i < kBPerThread; ++i) {
+      const int q = i * kBlock + tid;
+      Bs[buf][(q % BN) * kBPitch + q / BN] = w[i];
+    }
+  };
+
+  float xa[2][8], xn[2][8], wreg[kBPerThread];
+#pragma unroll
+  for (int r = 0; r < 2; ++r) load_k8(xrow[r], 8 * g, a.F, xa[r]);
+  fetch_w(0, wreg);
+  stage_w(0, wreg);
+  __syncthreads();
+
+  const int steps = (a.F + kKTile - 1) / kKTile;
+  for (int t = 0; t < steps; ++t) {
+    const bool more = t + 1 < steps;
+    if (more) {
+#pragma unroll
+      for (int r = 0; r < 2; ++r) load_k8(xrow[r], (t + 1) * kKTile + 8 * g, a.F, xn[r]);
+      fetch_w((t + 1) * kKTile, wreg);
+    }
+    // operand layout of v_mfma_f64_16x16x4_f64: A: lane l holds A[i = l % 16][k = l / 16],
+    // B: lane l holds B[k = l / 16][j = l % 16]; step s uses k = 8 g + s on both sides
+    const float* bt = &Bs[t & 1][0];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      f32x4_a b4[CT];
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+        b4[c] = *reinterpret_cast<const f32x4_a*>(bt + (c * 16 + li) * kBPitch + 8 * g + 4 * half);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const double a0 = (double)xa[0][4 * half + s], a1 = (double)xa[1][4 * half + s];
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+          const double bv = (double)b4[c][s];
+          acc[0][c] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, bv, acc[0][c], 0, 0, 0);
+          acc[1][c] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, bv, acc[1][c], 0, 0, 0);
         }
       }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) As[(kq + i) * kALd + r] = v[i];
     }
-    // ---- stage the W tile: Bs[k][j] = W[k0 + k][col0 + j], zero outside
-    for (int q = tid; q < kKTile * BN; q += kBlock) {
-      const int k = q / BN, j = q - k * BN;
-      const int kk = k0 + k, col = a.col0 + j;
-      Bs[q] = (kk < a.F && col < a.H) ? a.W[(int64_t)kk * a.H + col] : 0.0f;
-    }
-    __syncthreads();
-    // ---- 8 MFMA steps of 4 k each; operand layout of v_mfma_f64_16x16x4_f64:
-    //      A: lane l holds A[i = l % 16][k = l / 16], B: lane l holds B[k = l / 16][j = l % 16]
-#pragma unroll
-    for (int ks = 0; ks < kKTile; ks += 4) {
-      const int k = ks + (lane >> 4);
-      double av[2], bv[CT];
-#pragma unroll
-      for (int r = 0; r < 2; ++r) av[r] = (double)As[k * kALd + wv * 32 + r * 16 + (lane & 15)];
-#pragma unroll
-      for (int c = 0; c < CT; ++c) bv[c] = (double)Bs[k * BN + c * 16 + (lane & 15)];
+    if (more) {
+      stage_w((t + 1) & 1, wreg);  // that buffer was last read in step t - 1, before the barrier below
 #pragma unroll
       for (int r = 0; r < 2; ++r)
 #pragma unroll
-        for (int c = 0; c < CT; ++c) acc[r][c] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[r], bv[c], acc[r][c], 0, 0, 0);
+        for (int i = 0; i < 8; ++i) xa[r][i] = xn[r][i];
     }
     __syncthreads();
   }
@@ -106,12 +158,12 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(const CombineArgs a) {
   for (int r = 0; r < 2; ++r) {
 #pragma unroll
     for (int c = 0; c < CT; ++c) {
-      const int col = a.col0 + c * 16 + (lane & 15);
+      const int col = a.col0 + c * 16 + li;
       if (col >= a.H) continue;
       const double b = a.bias ? (double)a.bias[col] : 0.0;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const int64_t row = row0 + wv * 32 + r * 16 + 4 * v + (lane >> 4);
+        const int64_t row = row0 + r * 16 + 4 * v + g;
         if (row >= a.N) continue;
         float y = (float)(acc[r][c][v] + b);
         if (a.relu) y = y > 0.0f ? y : 0.0f;

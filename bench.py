@@ -29,9 +29,9 @@ MFMA_F64_PEAK_TFLOPS = 78.6
 # HBM-side bytes per aggregation launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, scaled on the copy
 # probe: see profiles/aggregate_kernel_*.txt), valid for the kernels as committed with those profiles and
 # for f_chunk = 0 only.  Set an entry to None when the kernel changes until the counters are taken again.
-MEASURED_TRAFFIC = {"c4-gcn": 179.242e9, "c5-sum": 16.554e9}
-    "c4-gcn": 176.595e9,  # profiles/aggregate_kernel_c4_gcn.txt
-    "c5-sum": 16.559e9,   # profiles/aggregate_kernel_c5_sum_bf16.txt
+MEASURED_TRAFFIC = {
+    "c4-gcn": 179.242e9,  # profiles/aggregate_kernel_c4_gcn.txt
+    "c5-sum": 16.554e9,   # profiles/aggregate_kernel_c5_sum_bf16.txt
 }
 
 WORKLOADS = {
@@ -284,6 +284,27 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
 
 
 
+def cpu_chunk_sweep(W, workload, widths):
+    """The CPU checker in the chunk-outer order of Algorithm 1 over a sweep of chunk widths, whole graph:
+    context for the paper's own (CPU) effect, not a target."""
+    import oracle
+    gkey, opname, F, xdt, gcn = WORKLOADS[workload]
+    N, src, dst = W.graph(gkey)
+    X = W.normal_bf16((N, F), seed=13) if xdt == "bf16" else W.normal_f32((N, F), seed=13)
+    threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, (oracle.SELF_LOOPS | oracle.NORM_SYM) if gcn else 0, want_w=gcn,
+                                    threads=threads)
+    rop = {"sum": oracle.SUM, "wsum": oracle.WSUM, "mean": oracle.MEAN, "max": oracle.MAX}[opname]
+    res = []
+    for fc in widths:
+        t0 = time.time()
+        oracle.aggregate(rop, rp, ci, w, X, f_chunk=fc, form=1, threads=threads)
+        dt = time.time() - t0
+        res.append({"f_chunk": fc, "seconds": dt, "edge_features_per_s": float(len(ci)) * F / dt, "threads": threads})
+        log("checker, chunk-outer, f_chunk=%d: %.2f s" % (fc, dt))
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -296,6 +317,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--also", default="c5-sum",
                     help="comma list of further workloads measured after the main one and reported under 'also'")
+    ap.add_argument("--cpu-chunk-sweep", default="",
+                    help="comma list of chunk widths: also time the CPU checker in Algorithm 1's chunk-outer order "
+                         "on the whole graph of the workload at each width (0 = one chunk); minutes of CPU time")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -337,6 +361,8 @@ def main():
         r = measure(g, W, torch, wl, 0, args.steps, args.warmup, False, 0.0, copy_gbs)
         also.append({k: r[k] for k in ("value", "unit", "ms_per_step", "config", "roofline", "setup")})
     rec["also"] = also
+    if args.cpu_chunk_sweep:
+        rec["cpu_chunk_sweep"] = cpu_chunk_sweep(W, args.workload, [int(v) for v in args.cpu_chunk_sweep.split(",")])
     print(json.dumps(rec), flush=True)
 
 

@@ -188,3 +188,15 @@ def test_auto_chunk_width(lib):
     assert g.gnnagg_auto_f_chunk(2449029, 1024, g.BF16) == 64        # same bytes per row piece in bf16
     assert g.gnnagg_auto_f_chunk(50_000_000, 64, g.F32) == 32        # never under 128 bytes per row piece
     assert g.gnnagg_auto_f_chunk(10, 0, g.F32) == 0 and g.gnnagg_auto_f_chunk(10, 8, 7) == 0
+
+
+def test_bench_module_is_importable_and_its_workloads_name_known_graphs():
+    """bench.py must import without a GPU (the GPU is touched only inside main)."""
+    import importlib
+    import workloads as W
+    bench = importlib.import_module("bench")
+    for name, (gkey, opname, F, xdt, gcn) in bench.WORKLOADS.items():
+        assert gkey in W.GRAPHS, name
+        assert opname in ("sum", "wsum", "mean", "max", "gat", "combine", "layer"), name
+        assert xdt in ("f32", "bf16"), name
+    assert set(bench.MEASURED_TRAFFIC) <= set(bench.WORKLOADS)

@@ -203,8 +203,10 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
     ms_per_step = wall * 1e3 / steps
     edge_features = float(nnz) * F
     x_bytes = 2 if xdt == "bf16" else 4
-    if gat:  # per edge: the row piece, one score per head, the index; per vertex: H once for the scores, out, scores
-        b_alg = nnz * (F * 4 + heads * 4 + 4) + 2 * N * F * 4 + 2 * N * heads * 4 * 2 + (N + 1) * 8
+    if gat:  # per edge: the row piece, the index, and one score per head unless the kernel recomputes it from the
+        # row piece (heads of 4, 8 or 16 channels); per vertex: H once for the scores, out, scores
+        per_edge_score = 0 if C in (4, 8, 16) else heads * 4
+        b_alg = nnz * (F * 4 + per_edge_score + 4) + 2 * N * F * 4 + 2 * N * heads * 4 * 2 + (N + 1) * 8
     else:
         f_eff = g.gnnagg_auto_f_chunk(N, F, g.BF16 if xdt == "bf16" else g.F32) if f_chunk == -1 else f_chunk
         b_alg = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", f_eff)

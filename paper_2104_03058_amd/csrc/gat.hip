@@ -8,6 +8,11 @@
 // running denominator, running weighted sum) for the head its columns belong
 // to, one exp per edge, and the states of a row's neighbour slots are merged
 // with cross-lane shuffles (hub rows: across waves through LDS).
+//
+// Where a head spans at most four lanes (4, 8 or 16 channels per head) the source's score is not
+// gathered from the score array but recomputed from the feature-row piece the lanes hold anyway
+// (a few fp64 FMAs and quad-local lane exchanges): one line request less per edge.  The score kernel
+// sums in the same order, so both routes give the same bits.
 #include <math.h>
 
 #include "common.hpp"
@@ -22,6 +27,7 @@ struct GatArgs {
   const int64_t* rowptr;
   const int32_t* colidx;
   const float* H;
+  const float* a_src;
   const float* s_src;
   const float* s_dst;
   float* alpha;
@@ -34,31 +40,59 @@ struct GatArgs {
   SegTable segs;
 };
 
-// s_src[j,h] = a_src[h,:] . H[j,h,:],  s_dst[j,h] = a_dst[h,:] . H[j,h,:]
+// s_src[j,h] = a_src[h,:] . H[j,h,:],  s_dst[j,h] = a_dst[h,:] . H[j,h,:]   (fp64, rounded once).
+// Summation order: partial sums over consecutive groups of `grp` channels (grp divides C, C / grp is
+// 1, 2 or 4), each a chain of FMAs from zero, then a pairwise tree - the order the aggregation kernel
+// reproduces when it recomputes a source score from the row pieces of a head's lanes.
 __global__ __launch_bounds__(kBlock) void gat_scores_kernel(const float* __restrict__ H,
                                                             const float* __restrict__ a_src,
                                                             const float* __restrict__ a_dst, int64_t n_vh,
-                                                            int32_t heads, int32_t C, float* __restrict__ s_src,
-                                                            float* __restrict__ s_dst) {
+                                                            int32_t heads, int32_t C, int32_t grp,
+                                                            float* __restrict__ s_src, float* __restrict__ s_dst) {
   const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (t >= n_vh) return;
   const int h = (int)(t % heads);
   const float* __restrict__ x = H + t * C;
   const float* __restrict__ as = a_src + (int64_t)h * C;
   const float* __restrict__ ad = a_dst + (int64_t)h * C;
-  double s = 0.0, d = 0.0;  // fp64 dot product, rounded once
-  for (int c = 0; c < C; ++c) {
-    const double v = (double)x[c];
-    s = __builtin_fma((double)as[c], v, s);
-    d = __builtin_fma((double)ad[c], v, d);
+  double ps[4] = {0.0, 0.0, 0.0, 0.0}, pd[4] = {0.0, 0.0, 0.0, 0.0};
+  const int n_grp = C / grp;
+  for (int q = 0; q < n_grp; ++q) {
+    double s = 0.0, d = 0.0;
+    for (int c = q * grp; c < (q + 1) * grp; ++c) {
+      const double v = (double)x[c];
+      s = __builtin_fma((double)as[c], v, s);
+      d = __builtin_fma((double)ad[c], v, d);
+    }
+    ps[q] = s;
+    pd[q] = d;
+  }
+  double s = ps[0], d = pd[0];
+  if (n_grp == 2) {
+    s = ps[0] + ps[1];
+    d = pd[0] + pd[1];
+  } else if (n_grp == 4) {
+    s = (ps[0] + ps[1]) + (ps[2] + ps[3]);
+    d = (pd[0] + pd[1]) + (pd[2] + pd[3]);
   }
   s_src[t] = (float)s;
   s_dst[t] = (float)d;
 }
 
+// x of the lane whose index differs in bit 0 (XOR1) or bit 1 (XOR2): a DPP move inside each quad of lanes
+constexpr int kQuadXor1 = 0xB1;  // quad_perm [1,0,3,2]
+constexpr int kQuadXor2 = 0x4E;  // quad_perm [2,3,0,1]
+template <int CTRL>
+__device__ inline double quad_exchange(double x) {
+  const uint64_t b = (uint64_t)__double_as_longlong(x);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, 0xF, 0xF, false);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, 0xF, 0xF, false);
+  return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
 template <int VEC>
 struct SoftState {
-  float m;          // running maximum of the logits seen
+  float m;          // reference logit: within kLazy of the maximum seen, or above it
   double l;         // sum of exp(logit - m)
   double acc[VEC];  // sum of exp(logit - m) * H   (fp64: hub rows add thousands of terms)
   __device__ inline void init() {
@@ -67,15 +101,20 @@ struct SoftState {
 #pragma unroll
     for (int k = 0; k < VEC; ++k) acc[k] = 0.0;
   }
+  // The reference m only has to keep exp(logit - m) in range, it need not be the exact maximum: it is
+  // moved (and the sums rescaled) only when a logit exceeds it by more than kLazy, which after the
+  // first edge is rare, so a wavefront almost always runs the short branch alone.
+  static constexpr float kLazy = 8.0f;
   __device__ inline void add(float logit, const float (&v)[VEC]) {
     const float d = logit - m;
-    const double ex = (double)expf(-fabsf(d));  // exp(smaller - larger); exp(-inf) = 0 on the first edge
-    if (d > 0.0f) {
+    if (d > kLazy) {  // first edge (m = -inf, exp(-inf) = 0) or a jump
+      const double ex = (double)expf(-d);
       l = __builtin_fma(l, ex, 1.0);
 #pragma unroll
       for (int k = 0; k < VEC; ++k) acc[k] = __builtin_fma(acc[k], ex, (double)v[k]);
       m = logit;
     } else {
+      const double ex = (double)expf(d);  // at most e^kLazy
       l += ex;
 #pragma unroll
       for (int k = 0; k < VEC; ++k) acc[k] = __builtin_fma(ex, (double)v[k], acc[k]);
@@ -101,8 +140,10 @@ struct SoftState {
 };
 
 // Accumulator policy of the walk in gather.hpp: per edge, the source's score for this lane's head and
-// one 16-byte piece of its feature row.
-template <int VEC>
+// one 16-byte piece of its feature row.  LH == 0: the score is gathered from s_src.  LH = 1, 2, 4: a
+// head is held by LH adjacent lanes (aligned to LH) that always run together, and the score is their
+// dot product with a_src, summed in the order of gat_scores_kernel.
+template <int VEC, int LH>
 struct GatAcc {
   static constexpr bool kWeighted = false;
   SoftState<VEC> st;
@@ -111,23 +152,35 @@ struct GatAcc {
   const float* __restrict__ s_src_h;  // s_src plus this lane's head
   int32_t heads;
   float sd, slope;
+  double av[VEC];  // a_src at this lane's columns (LH > 0)
   typename Raw<float, VEC>::type raw[kUnroll];
   float ss[kUnroll];
   __device__ inline void fetch(int u, int64_t j) {
-    ss[u] = s_src_h[j * heads];
+    if constexpr (LH == 0) ss[u] = s_src_h[j * heads];
     raw[u] = load_raw<float, VEC>(reinterpret_cast<const float*>(hb + j * rowbytes));
   }
   template <bool MASKED>
   __device__ inline void use(int u, float, bool ok) {
-    if (MASKED && !ok) return;
     float v[VEC];
     unpack(raw[u], v);
-    const float s = ss[u] + sd;
+    float sj;
+    if constexpr (LH == 0) {
+      sj = ss[u];
+    } else {  // before the mask test: the lanes of a head exchange partial sums
+      double p = 0.0;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) p = __builtin_fma(av[k], (double)v[k], p);
+      if constexpr (LH >= 2) p += quad_exchange<kQuadXor1>(p);
+      if constexpr (LH >= 4) p += quad_exchange<kQuadXor2>(p);
+      sj = (float)p;
+    }
+    if (MASKED && !ok) return;
+    const float s = sj + sd;
     st.add(s >= 0.0f ? s : slope * s, v);
   }
 };
 
-template <int VEC, int MODE>
+template <int VEC, int MODE, int LH>
 __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) {
   __shared__ double lds[(kWavesPerBlock - 1) * kWave * (2 + VEC)];
   __shared__ double fin[2 * kWave];
@@ -145,8 +198,10 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
   const int head = col / a.C;  // VEC divides C, so the lane's columns lie in one head
   const int64_t HC = (int64_t)a.heads * a.C;
 
-  GatAcc<VEC> acc;
+  GatAcc<VEC, LH> acc;
   acc.st.init();
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) acc.av[k] = (LH > 0) ? (double)a.a_src[col + k] : 0.0;  // a_src is [heads, C]: same flat index as the column
   acc.hb = reinterpret_cast<const char*>(a.H + col);
   acc.rowbytes = HC * (int64_t)sizeof(float);
   acc.s_src_h = a.s_src + head;
@@ -204,17 +259,29 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
   }
 }
 
-template <int VEC>
+template <int VEC, int LH>
 int launch_gat(const GatArgs& a, uint64_t grid, hipStream_t stream) {
   const int g = a.sl.g_log2;
   if (g == 6) {
-    hipLaunchKernelGGL((gat_aggregate_kernel<VEC, MODE_WAVE>), dim3((unsigned)grid), dim3(kBlock), 0, stream, a);
+    hipLaunchKernelGGL((gat_aggregate_kernel<VEC, MODE_WAVE, LH>), dim3((unsigned)grid), dim3(kBlock), 0, stream, a);
   } else if (g >= 3) {
-    hipLaunchKernelGGL((gat_aggregate_kernel<VEC, MODE_WIDE>), dim3((unsigned)grid), dim3(kBlock), 0, stream, a);
+    hipLaunchKernelGGL((gat_aggregate_kernel<VEC, MODE_WIDE, LH>), dim3((unsigned)grid), dim3(kBlock), 0, stream, a);
   } else {
-    hipLaunchKernelGGL((gat_aggregate_kernel<VEC, MODE_NARROW>), dim3((unsigned)grid), dim3(kBlock), 0, stream, a);
+    hipLaunchKernelGGL((gat_aggregate_kernel<VEC, MODE_NARROW, LH>), dim3((unsigned)grid), dim3(kBlock), 0, stream,
+                       a);
   }
   return hipGetLastError() == hipSuccess ? GNNAGG_OK : GNNAGG_EDEVICE;
+}
+
+// Lanes per head when the source score can be recomputed in registers, else 0.  Needs 16-byte lanes, a
+// head of 1, 2 or 4 lanes, and slices that are whole heads (then a head's lanes are adjacent, aligned,
+// and either all own columns or none does).
+inline int lanes_per_head_fused(const SliceLaunch& sl, int32_t C) {
+  if (sl.vec != 4 || C % 4) return 0;
+  const int lh = C / 4;
+  if (lh != 1 && lh != 2 && lh != 4) return 0;
+  if (sl.sub_w % C || sl.chunk_w % C || sl.c_begin % C || sl.chunk_stride % C) return 0;
+  return lh;
 }
 
 }  // namespace
@@ -260,6 +327,7 @@ extern "C" int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
     a.rowptr = rowptr;
     a.colidx = colidx;
     a.H = H;
+    a.a_src = a_src;
     a.s_src = s_src;
     a.s_dst = s_dst;
     a.alpha = alpha;
@@ -278,15 +346,26 @@ extern "C" int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
   }
   hipStream_t stream = (hipStream_t)stream_;
   const int64_t n_vh = N * heads;
+  // one summation order for the whole call: groups of 4 channels if any launch recomputes scores
+  int32_t grp = C;
+  for (size_t k = 0; k < launches.size(); ++k)
+    if (lanes_per_head_fused(launches[k], C)) grp = 4;
   hipLaunchKernelGGL(gat_scores_kernel, dim3((unsigned)ceil_div(n_vh, kBlock)), dim3(kBlock), 0, stream, H, a_src,
-                     a_dst, n_vh, heads, C, s_src, s_dst);
+                     a_dst, n_vh, heads, C, grp, s_src, s_dst);
   GNNAGG_HIP_TRY(hipGetLastError());
   for (size_t k = 0; k < launches.size(); ++k) {
     int rc;
     switch (args[k].sl.vec) {
-      case 1: rc = launch_gat<1>(args[k], grids[k], stream); break;
-      case 2: rc = launch_gat<2>(args[k], grids[k], stream); break;
-      default: rc = launch_gat<4>(args[k], grids[k], stream); break;
+      case 1: rc = launch_gat<1, 0>(args[k], grids[k], stream); break;
+      case 2: rc = launch_gat<2, 0>(args[k], grids[k], stream); break;
+      default:
+        switch (lanes_per_head_fused(args[k].sl, C)) {
+          case 1: rc = launch_gat<4, 1>(args[k], grids[k], stream); break;
+          case 2: rc = launch_gat<4, 2>(args[k], grids[k], stream); break;
+          case 4: rc = launch_gat<4, 4>(args[k], grids[k], stream); break;
+          default: rc = launch_gat<4, 0>(args[k], grids[k], stream); break;
+        }
+        break;
     }
     if (rc != GNNAGG_OK) return rc;
   }

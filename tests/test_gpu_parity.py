@@ -362,7 +362,10 @@ def test_config3_gat_mid_graph():
     check_gat(N, rp, ci, H, a_s, a_d, f_chunks=(0, 8, 16, 24), what="c3")
 
 
-@pytest.mark.parametrize("heads,C", [(8, 8), (3, 5), (1, 1), (4, 6), (40, 8)])
+# (2,4) (1,8) (4,16) (64,8): a head on 1 / 2 / 4 lanes, narrow to wave-wide slices (scores recomputed from the
+# gathered rows); (33,8): slices that cut heads; (2,32) (3,5) (4,6) (1,1): scores gathered
+@pytest.mark.parametrize("heads,C", [(8, 8), (3, 5), (1, 1), (4, 6), (40, 8), (2, 4), (1, 8), (4, 16), (64, 8),
+                                     (33, 8), (2, 32)])
 def test_gat_hub_rows_and_odd_head_shapes(heads, C):
     N = 400
     src, dst = star(N, hub=7, n_in=5000, seed=heads * 10 + C)

@@ -4,7 +4,7 @@
 // The attention logits need whole head vectors, so the two per-vertex score
 // arrays are computed once up front; chunks are whole heads (the paper's GAT
 // chunk width 8, Section III, is one head at 8 channels) and every chunk sees
-// the same weights.  The softmax is kept online: a lane carries (running max,
+// the same weights.  The softmax is kept online: a lane carries (reference logit,
 // running denominator, running weighted sum) for the head its columns belong
 // to, one exp per edge, and the states of a row's neighbour slots are merged
 // with cross-lane shuffles (hub rows: across waves through LDS).

@@ -30,7 +30,7 @@ def declared_symbols():
 def test_header_declares_the_boundary():
     names = declared_symbols()
     for must in ["gnnagg_build_csr", "gnnagg_aggregate", "gnnagg_gat_attention", "gnnagg_plan_rows",
-                 "gnnagg_strerror", "gnnagg_version"]:
+                 "gnnagg_combine", "gnnagg_auto_f_chunk", "gnnagg_strerror", "gnnagg_version"]:
         assert must in names
 
 
@@ -90,6 +90,20 @@ def test_argument_validation_returns_before_any_launch(lib):
     assert gat(4, one, one, one, one, one, 8, 8, f, None, one, 16, None, None, None, ctypes.byref(need), None) == 0
     assert need.value >= 2 * 4 * 8 * 4
     assert gat(4, one, one, one, one, one, 8, 8, f, None, one, 0, None, None, one, ctypes.byref(small), None) == EWS
+
+    comb = lib.gnnagg_combine
+    other = ctypes.c_void_p(8192)
+    assert comb(-1, one, 0, 8, one, None, 4, 0, other, None) == EINVAL   # N
+    assert comb(4, one, 0, 0, one, None, 4, 0, other, None) == EINVAL    # F
+    assert comb(4, one, 0, 8, one, None, 0, 0, other, None) == EINVAL    # H
+    assert comb(4, one, 3, 8, one, None, 4, 0, other, None) == EINVAL    # x_dtype
+    assert comb(4, one, 0, 8, one, None, 4, 2, other, None) == EINVAL    # relu flag
+    assert comb(4, None, 0, 8, one, None, 4, 0, other, None) == ENULL    # X
+    assert comb(4, one, 0, 8, None, None, 4, 0, other, None) == ENULL    # W
+    assert comb(4, one, 0, 8, one, None, 4, 0, None, None) == ENULL      # out
+    assert comb(4, one, 0, 8, one, None, 4, 0, one, None) == EINVAL      # out aliases X
+    assert comb(4, ctypes.c_void_p(4098), 0, 8, one, None, 4, 0, other, None) == EINVAL  # fp32 X on a 2-byte boundary
+    assert comb(0, None, 0, 8, None, None, 4, 0, None, None) == 0        # no rows: nothing to do
 
 
 # ------------------------------------------------------------------ launch geometry

@@ -153,3 +153,37 @@ def test_automatic_chunk_width_on_a_feature_matrix_beyond_the_cache():
     mx_auto = g.gnnagg_aggregate(g.MAX, d_rp, d_ci, None, d_X, None, g.F_CHUNK_AUTO, plan)
     mx_one = g.gnnagg_aggregate(g.MAX, d_rp, d_ci, None, d_X, None, 0, plan)
     assert torch.equal(mx_auto, mx_one)
+
+
+def test_combination_at_the_dense_graph_size_and_the_layer_built_from_it():
+    """Combination at the benchmark's size (602 -> 32 on 232,965 vertices) on sampled rows, then the
+    GCN layer in the order the benchmark times (Combination first, aggregation at width 32): sampled
+    rows against the checker run in the other order (aggregate at width 602, then project)."""
+    import paper_2104_03058_amd as g
+    N, src, dst = W.graph("c4")
+    X = W.normal_f32((N, 602), seed=13)
+    Wt = W.normal_f32((602, 32), seed=16, std=0.05)
+    b = W.normal_f32((32,), seed=17, std=0.1)
+    d_X = dev(X)
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.concatenate([[0, 1, 127, 128, N - 129, N - 128, N - 1],
+                                     rng.choice(N, size=500, replace=False)])).astype(np.int64)
+    say("c4 full: combination")
+    hid = g.gnnagg_combine(d_X, dev(Wt), dev(b), True)
+    assert_close(host(hid[torch.from_numpy(rows).cuda()]), oracle.combine(X[rows], Wt, b, True), what="combine relu")
+    hid = g.gnnagg_combine(d_X, dev(Wt))
+    assert_close(host(hid[torch.from_numpy(rows).cuda()]), oracle.combine(X[rows], Wt), what="combine")
+    say("c4 full: layer, combination first")
+    flags = oracle.SELF_LOOPS | oracle.NORM_SYM
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, flags, want_w=True, threads=16)
+    d_rp, d_ci, d_w, _ = g.gnnagg_build_csr(N, dev(src), dev(dst), flags, want_w=True)
+    out = g.gnnagg_aggregate(g.WSUM, d_rp, d_ci, d_w, hid, None, 0, g.gnnagg_plan_rows(d_rp))
+    some = sample_rows(rp, n=48)
+    agg = oracle.aggregate_rows(oracle.WSUM, some, rp, ci, w, X, threads=16)  # [rows, 602], fp32
+    ref = agg.astype(np.float64) @ Wt.astype(np.float64)
+    got = host(out[torch.from_numpy(some).cuda()]).astype(np.float64)
+    # each side rounds an intermediate to fp32 once (hidden features / aggregated features): a few ulp of
+    # the magnitude sum  sum_j w_ij sum_k |x_jk| |W_kh|
+    mag = oracle.aggregate_rows(oracle.WSUM, some, rp, ci, w, np.abs(X), threads=16)
+    scale = mag.astype(np.float64) @ np.abs(Wt).astype(np.float64)
+    assert np.all(np.abs(got - ref) <= 1e-6 + 1e-6 * scale), float(np.max(np.abs(got - ref) / (1e-6 + 1e-6 * scale)))

@@ -90,6 +90,11 @@ __device__ inline double quad_exchange(double x) {
   return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
 }
 
+// exp through the hardware exp2 (argument scaled by log2 e in fp32): relative error about 1e-7 |x|, i.e.
+// below 2e-6 for every term within e^-16 of a row's largest, against a parity bar of 1e-5; a fraction of
+// the instructions of the correctly rounded routine, which showed in the run time (about 10 %).
+__device__ inline float exp_fast(float x) { return __expf(x); }
+
 template <int VEC>
 struct SoftState {
   float m;          // reference logit: within kLazy of the maximum seen, or above it
@@ -108,13 +113,13 @@ struct SoftState {
   __device__ inline void add(float logit, const float (&v)[VEC]) {
     const float d = logit - m;
     if (d > kLazy) {  // first edge (m = -inf, exp(-inf) = 0) or a jump
-      const double ex = (double)expf(-d);
+      const double ex = (double)exp_fast(-d);
       l = __builtin_fma(l, ex, 1.0);
 #pragma unroll
       for (int k = 0; k < VEC; ++k) acc[k] = __builtin_fma(acc[k], ex, (double)v[k]);
       m = logit;
     } else {
-      const double ex = (double)expf(d);  // at most e^kLazy
+      const double ex = (double)exp_fast(d);  // at most e^kLazy
       l += ex;
 #pragma unroll
       for (int k = 0; k < VEC; ++k) acc[k] = __builtin_fma(ex, (double)v[k], acc[k]);
@@ -122,8 +127,8 @@ struct SoftState {
   }
   __device__ inline void merge(const SoftState& o) {
     const float mm = fmaxf(m, o.m);
-    const double sa = (m == mm) ? 1.0 : (double)expf(m - mm);
-    const double sb = (o.m == mm) ? 1.0 : (double)expf(o.m - mm);
+    const double sa = (m == mm) ? 1.0 : (double)exp_fast(m - mm);
+    const double sb = (o.m == mm) ? 1.0 : (double)exp_fast(o.m - mm);
     l = l * sa + o.l * sb;
 #pragma unroll
     for (int k = 0; k < VEC; ++k) acc[k] = acc[k] * sa + o.acc[k] * sb;
@@ -254,7 +259,7 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
     for (int64_t e = e0 + ng; e < e1; e += P) {
       const float s = a.s_src[(int64_t)a.colidx[e] * a.heads + head] + sd;
       const float logit = s >= 0.0f ? s : a.slope * s;
-      a.alpha[e * a.heads + head] = (float)((double)expf(logit - st.m) / st.l);
+      a.alpha[e * a.heads + head] = (float)((double)exp_fast(logit - st.m) / st.l);
     }
   }
 }

@@ -436,3 +436,75 @@ def test_combination_first_equals_aggregation_first():
     ref = oracle.aggregate(oracle.WSUM, rp, ci, w, oracle.combine(X, Wt, threads=8), threads=8)
     assert_close(host(first), ref, what="combine then aggregate")
     assert np.allclose(host(last), ref, rtol=1e-4, atol=1e-5)  # two fp32 roundings in a different place
+
+
+# ------------------------------------------------------------------ seeded sweep of small random cases, streams
+def test_seeded_sweep_of_small_random_cases():
+    """Forty small cases with shapes drawn from a seeded generator: graph size, density, a planted hub,
+    feature width, chunk width, input type, operator, with and without a row plan."""
+    rng = np.random.default_rng(20240)
+    for case in range(40):
+        N = int(rng.integers(1, 400))
+        E = int(rng.integers(0, 12 * N + 1))
+        src, dst = (W.random_digraph(N, E, 7000 + case) if E else (np.zeros(0, np.int32), np.zeros(0, np.int32)))
+        if N > 8 and case % 3 == 0:  # a hub row that needs a whole workgroup
+            hub_src = rng.integers(0, N, size=int(rng.integers(300, 3000))).astype(np.int32)
+            src = np.concatenate([src, hub_src])
+            dst = np.concatenate([dst, np.full(len(hub_src), int(rng.integers(0, N)), np.int32)])
+        F = int(rng.choice([1, 2, 3, 5, 8, 12, 17, 31, 32, 33, 64, 100, 129, 260, 513]))
+        fc = int(rng.choice([0, 0, 1, 3, 4, 8, 16, 50, g.F_CHUNK_AUTO]))
+        bf16 = bool(rng.integers(0, 2))
+        flags = int(rng.choice([0, oracle.SELF_LOOPS, oracle.SELF_LOOPS | oracle.NORM_SYM]))
+        rp, ci, w, _ = oracle.build_csr(N, src, dst, flags, want_w=True)
+        X = W.normal_bf16((N, F), seed=8000 + case) if bf16 else W.normal_f32((N, F), seed=8000 + case)
+        name = ["sum", "wsum", "mean", "max"][case % 4]
+        say("  sweep case", case, "N", N, "nnz", len(ci), "F", F, "fc", fc, "bf16", bf16, name)
+        check_aggregate(N, rp, ci, w, X, [name], f_chunks=(fc,), plans=(bool(case & 1),), bf16=bf16,
+                        what="sweep %d" % case)
+
+
+def test_calls_are_ordered_on_the_callers_stream():
+    """Work is enqueued on the stream that is current for the caller: a side stream's result is complete
+    once that stream is, and back-to-back dependent calls need no synchronisation in between."""
+    N, src, dst = W.graph("c2")
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, oracle.SELF_LOOPS | oracle.NORM_SYM, want_w=True)
+    X = W.normal_f32((N, 48), seed=901)
+    Wt = W.normal_f32((48, 16), seed=902, std=0.2)
+    d_rp, d_ci, d_w, d_X, d_W = dev(rp), dev(ci), dev(w), dev(X), dev(Wt)
+    plan = g.gnnagg_plan_rows(d_rp)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        hid = g.gnnagg_combine(d_X, d_W)
+        one = g.gnnagg_aggregate(1, d_rp, d_ci, d_w, hid, None, 0, plan)
+        two = g.gnnagg_aggregate(1, d_rp, d_ci, d_w, one, None, 0, plan)  # consumes the previous output
+    side.synchronize()
+    h = oracle.combine(X, Wt)
+    r1 = oracle.aggregate(oracle.WSUM, rp, ci, w, h)
+    assert_close(one.cpu().numpy(), r1, what="first hop on a side stream")
+    assert_close(two.cpu().numpy(), oracle.aggregate(oracle.WSUM, rp, ci, w, one.cpu().numpy()), what="second hop")
+
+
+def test_seeded_sweep_of_attention_and_csr_cases():
+    rng = np.random.default_rng(4711)
+    for case in range(24):
+        N = int(rng.integers(1, 300))
+        E = int(rng.integers(0, 10 * N + 1))
+        src, dst = (W.random_digraph(N, E, 9000 + case) if E else (np.zeros(0, np.int32), np.zeros(0, np.int32)))
+        if N > 8 and case % 4 == 0:
+            hub_src = rng.integers(0, N, size=int(rng.integers(300, 2500))).astype(np.int32)
+            src = np.concatenate([src, hub_src])
+            dst = np.concatenate([dst, np.full(len(hub_src), int(rng.integers(0, N)), np.int32)])
+        flags = int(rng.choice([0, oracle.SELF_LOOPS, oracle.SELF_LOOPS | oracle.NORM_SYM, oracle.NORM_SYM]))
+        rp, ci, w, perm = oracle.build_csr(N, src, dst, flags, want_w=True, want_perm=True)
+        d_rp, d_ci, d_w, d_perm = gpu_csr(N, src, dst, flags, want_w=True, want_perm=True)
+        what = "sweep %d N=%d E=%d flags=%d" % (case, N, len(src), flags)
+        assert np.array_equal(host(d_rp), rp) and np.array_equal(host(d_ci), ci), what
+        assert np.array_equal(host(d_perm), perm), what
+        assert_bits(host(d_w), w, what)
+        heads, C = [(1, 4), (2, 8), (3, 16), (5, 3), (2, 12), (16, 8), (1, 32), (7, 1)][case % 8]
+        fc = int(rng.choice([0, C, 2 * C]))
+        H = W.normal_f32((N, heads, C), seed=9500 + case)
+        a_s = W.normal_f32((heads, C), seed=9600 + case, std=0.7)
+        a_d = W.normal_f32((heads, C), seed=9700 + case, std=0.7)
+        check_gat(N, rp, ci, H, a_s, a_d, f_chunks=(fc,), plans=(bool(case & 1),), what=what + " %dx%d" % (heads, C))

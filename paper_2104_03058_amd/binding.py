@@ -56,6 +56,8 @@ def load_library():
         lib.gnnagg_plan_rows.argtypes = [i64, vp, vp, vp, vp, szp, vp]
         lib.gnnagg_aggregate.restype = ci
         lib.gnnagg_aggregate.argtypes = [ci, i64, vp, vp, vp, vp, ci, vp, ci, i32, i32, vp, vp, vp]
+        lib.gnnagg_aggregate_ws.restype = ci
+        lib.gnnagg_aggregate_ws.argtypes = [ci, i64, vp, vp, vp, vp, ci, vp, ci, i32, i32, vp, vp, vp, szp, vp]
         lib.gnnagg_gat_attention.restype = ci
         lib.gnnagg_gat_attention.argtypes = [i64, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp, i32, vp, vp, vp, szp,
                                              vp]
@@ -165,11 +167,28 @@ def _x_dtype(X: torch.Tensor) -> int:
     raise TypeError("X must be float32 or bfloat16")
 
 
+def gnnagg_aggregate_workspace_bytes(N: int, F: int, plan: Optional["RowPlan"]) -> int:
+    """Size of the workspace with which gnnagg_aggregate_ws splits very long rows (the size query of the C call);
+    0 when the plan holds no such row."""
+    if plan is None or N == 0:
+        return 0
+    need = ctypes.c_size_t(0)
+    _check("gnnagg_aggregate_ws",
+           load_library().gnnagg_aggregate_ws(0, N, None, None, None, None, F32, None, F32, F, 0,
+                                              _dev(plan.row_order, torch.int32, "row_order"),
+                                              ctypes.cast(plan.class_off, ctypes.c_void_p), None,
+                                              ctypes.byref(need), None))
+    return int(need.value)
+
+
 def gnnagg_aggregate(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w: Optional[torch.Tensor],
                      X: torch.Tensor, out: Optional[torch.Tensor] = None, f_chunk: int = 0,
-                     plan: Optional[RowPlan] = None, stream=None) -> torch.Tensor:
+                     plan: Optional[RowPlan] = None, stream=None,
+                     workspace: Optional[torch.Tensor] = None, split_long_rows: bool = True) -> torch.Tensor:
     """out[N,F] (fp32, or bf16 if a bf16 tensor is passed) = aggregation of X[N,F] over the CSR; enqueued on the
-    current stream."""
+    current stream.  With a plan that holds very long rows the call goes through gnnagg_aggregate_ws (the
+    workspace is allocated here unless one of at least gnnagg_aggregate_workspace_bytes is passed in);
+    split_long_rows=False forces the plain entry point."""
     lib = load_library()
     if X.dim() != 2:
         raise ValueError("X must be [N, F]")
@@ -182,13 +201,21 @@ def gnnagg_aggregate(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w
         raise ValueError("out must be [N, F]")
     if out.dtype not in (torch.float32, torch.bfloat16):
         raise TypeError("out must be float32 or bfloat16")
-    rc = lib.gnnagg_aggregate(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
-                              _dev(edge_w, torch.float32, "edge_w"), _dev(X, None, "X"), _x_dtype(X),
-                              _dev(out, None, "out"), F32 if out.dtype == torch.float32 else BF16, F, f_chunk,
-                              _dev(plan.row_order, torch.int32, "row_order") if plan is not None else None,
-                              ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None,
-                              _stream(stream))
-    _check("gnnagg_aggregate", rc)
+    head = (op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
+            _dev(edge_w, torch.float32, "edge_w"), _dev(X, None, "X"), _x_dtype(X),
+            _dev(out, None, "out"), F32 if out.dtype == torch.float32 else BF16, F, f_chunk,
+            _dev(plan.row_order, torch.int32, "row_order") if plan is not None else None,
+            ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None)
+    need = gnnagg_aggregate_workspace_bytes(N, F, plan) if split_long_rows else 0
+    if need > 0:
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+        have = ctypes.c_size_t(workspace.numel() * workspace.element_size())
+        rc = lib.gnnagg_aggregate_ws(*head, _dev(workspace), ctypes.byref(have), _stream(stream))
+        _check("gnnagg_aggregate_ws", rc)
+    else:
+        rc = lib.gnnagg_aggregate(*head, _stream(stream))
+        _check("gnnagg_aggregate", rc)
     return out
 
 

@@ -39,6 +39,7 @@ struct AggArgs {
   SliceLaunch sl;
   int32_t mean;
   uint32_t lds_per_workgroup;  // host only: LDS each workgroup should occupy (0 = no cap)
+  double* ws;                  // partial results of split rows: [slot][F] (null: no row is split)
   SegTable segs;
 };
 
@@ -93,6 +94,11 @@ struct State {
   __device__ inline float result(int k, int64_t deg, bool mean) const {
     return (float)((mean && deg > 0) ? acc[k] / (double)deg : acc[k]);
   }
+  // partial result of one piece of a split row, one double per column
+  __device__ inline void dump(double* p) const {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) p[k] = acc[k];
+  }
 };
 
 // max: integer keys, exact and independent of the order of the operands
@@ -132,6 +138,10 @@ struct State<OPK_MAX, VEC> {
     for (int k = 0; k < VEC; ++k) key[k] = p[k];
   }
   __device__ inline float result(int k, int64_t deg, bool) const { return deg > 0 ? key_value(key[k]) : 0.0f; }
+  __device__ inline void dump(double* p) const {  // an int32 key is exact in a double
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) p[k] = (double)key[k];
+  }
 };
 
 // Accumulator policy of the walk in gather.hpp: one 16-byte piece of the source row per edge.
@@ -168,6 +178,11 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
     e1 = a.rowptr[r + 1];
   }
   const int64_t deg = e1 - e0;
+  if (role.split_log2 > 0) {  // this workgroup walks one piece of the row
+    e0 += (int64_t)role.piece << kSplitLenLog2;
+    if (e0 > e1) e0 = e1;
+    if (e1 - e0 > ((int64_t)1 << kSplitLenLog2)) e1 = e0 + ((int64_t)1 << kSplitLenLog2);
+  }
   AggAcc<T, OPK, VEC> acc;
   acc.st.init();
   acc.xb = static_cast<const char*>(a.X) + (int64_t)col * (int64_t)sizeof(T);
@@ -194,13 +209,56 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
   }
 
   // ---- write the slice of the output row ----------------------------------------
-  if (role.writer) {
+  if (role.writer && role.split_log2 > 0) {
+    st.dump(a.ws + (int64_t)role.ws_slot * a.F + col);
+  } else if (role.writer) {
     float res[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) res[k] = st.result(k, deg, a.mean != 0);
     if (a.out_bf16) store_row_bf16<VEC>(static_cast<uint16_t*>(a.out) + r * a.F + col, res);
     else store_row<VEC>(static_cast<float*>(a.out) + r * a.F + col, res);
   }
+}
+
+// Folds the pieces of the split rows, in piece order, into `out`: one thread per (split row, column).
+struct MergeArgs {
+  const int64_t* rowptr;
+  const int32_t* order;
+  void* out;
+  const double* ws;
+  int64_t F;
+  int64_t rows;  // split rows in all runs together
+  int32_t out_bf16, mean, nrun;
+  Seg run[kMaxSplitSeg];
+};
+
+template <int OPK>
+__global__ __launch_bounds__(kBlock) void split_merge_kernel(const MergeArgs a) {
+  const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (t >= a.rows * a.F) return;
+  int64_t i = t / a.F;  // which split row, counted over the runs
+  const int64_t col = t - i * a.F;
+  int k = 0;
+  while (k + 1 < a.nrun && i >= (int64_t)a.run[k].row_end - a.run[k].row_begin) {
+    i -= (int64_t)a.run[k].row_end - a.run[k].row_begin;
+    ++k;
+  }
+  const Seg run = a.run[k];
+  const int64_t r = a.order[run.row_begin + i];
+  const int64_t deg = a.rowptr[r + 1] - a.rowptr[r];
+  const int64_t pieces = (int64_t)1 << run.split_log2;
+  const double* p = a.ws + ((int64_t)run.ws_begin + i * pieces) * a.F + col;
+  State<OPK, 1> st;
+  st.init();
+  for (int64_t q = 0; q < pieces; ++q) {
+    State<OPK, 1> o;
+    if constexpr (OPK == OPK_MAX) o.key[0] = (int32_t)p[q * a.F];
+    else o.acc[0] = p[q * a.F];
+    st.merge(o);
+  }
+  const float res = st.result(0, deg, a.mean != 0);
+  if (a.out_bf16) static_cast<uint16_t*>(a.out)[r * a.F + col] = (uint16_t)bf16_bits(res);
+  else static_cast<float*>(a.out)[r * a.F + col] = res;
 }
 
 template <typename T, int OPK, int VEC, int MODE>
@@ -248,31 +306,44 @@ int launch_op(int opk, const AggArgs& a, uint64_t grid, hipStream_t stream) {
 
 using namespace gnnagg;
 
-extern "C" int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
-                                const float* edge_w, const void* X, int x_dtype, void* out, int out_dtype,
-                                int32_t F, int32_t f_chunk, const int32_t* row_order, const int64_t* class_off,
-                                void* stream_) {
+namespace {
+
+// Argument checks shared by the two aggregation entry points; GNNAGG_OK with *nothing = true means
+// there is nothing to do.
+int check_aggregate_args(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* edge_w,
+                         const void* X, int x_dtype, void* out, int out_dtype, int32_t F, int32_t f_chunk,
+                         const int32_t* row_order, const int64_t* class_off, bool* nothing) {
+  *nothing = false;
   if (op < GNNAGG_SUM || op > GNNAGG_MAX) return GNNAGG_EINVAL;
   if (N < 0 || F <= 0 || f_chunk < GNNAGG_F_CHUNK_AUTO) return GNNAGG_EINVAL;
   if (x_dtype != GNNAGG_F32 && x_dtype != GNNAGG_BF16) return GNNAGG_EINVAL;
   if (out_dtype != GNNAGG_F32 && out_dtype != GNNAGG_BF16) return GNNAGG_EINVAL;
   if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
   if ((row_order == nullptr) != (class_off == nullptr)) return GNNAGG_EINVAL;
-  if (N == 0) return GNNAGG_OK;
+  if (N == 0) {
+    *nothing = true;
+    return GNNAGG_OK;
+  }
   if (!rowptr || !X || !out) return GNNAGG_ENULL;
   if (op == GNNAGG_WSUM && !edge_w) return GNNAGG_ENULL;
   // colidx may only be NULL for a graph without edges, which the host cannot see; require it
   if (!colidx) return GNNAGG_ENULL;
   const size_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
-  if (((uintptr_t)X % xs) || ((uintptr_t)out % (out_dtype == GNNAGG_F32 ? 4 : 2)) || ((uintptr_t)rowptr % 8) || ((uintptr_t)colidx % 4) ||
-      (edge_w && ((uintptr_t)edge_w % 4)))
+  if (((uintptr_t)X % xs) || ((uintptr_t)out % (out_dtype == GNNAGG_F32 ? 4 : 2)) || ((uintptr_t)rowptr % 8) ||
+      ((uintptr_t)colidx % 4) || (edge_w && ((uintptr_t)edge_w % 4)))
     return GNNAGG_EINVAL;
   if (X == out) return GNNAGG_EINVAL;
+  return GNNAGG_OK;
+}
 
+// ws == nullptr: no row is split.  Otherwise ws holds segs.ws_slots * F doubles.
+int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* edge_w,
+                   const void* X, int x_dtype, void* out, int out_dtype, int32_t F, int32_t f_chunk,
+                   const int32_t* row_order, const int64_t* class_off, double* ws, hipStream_t stream) {
+  const size_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
   if (f_chunk == GNNAGG_F_CHUNK_AUTO) f_chunk = auto_f_chunk(N, F, (int)xs);
   std::vector<SliceLaunch> launches;
   plan_columns(F, f_chunk, (int)(16 / xs), 0, &launches);
-  hipStream_t stream = (hipStream_t)stream_;
   const int opk = (op == GNNAGG_WSUM) ? OPK_WSUM : (op == GNNAGG_MAX ? OPK_MAX : OPK_SUM);
 
   // build and validate every launch before the first one is enqueued
@@ -291,8 +362,9 @@ extern "C" int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const 
     a.N = N;
     a.sl = launches[k];
     a.mean = (op == GNNAGG_MEAN);
+    a.ws = ws;
     a.lds_per_workgroup = lds_claim(resident_workgroup_cap(class_off, N, a.sl.g_log2));
-    int rc = build_segments(class_off, N, a.sl.g_log2, &a.segs);
+    int rc = build_segments(class_off, N, a.sl.g_log2, ws != nullptr, &a.segs);
     if (rc != GNNAGG_OK) return rc;
     grids[k] = (uint64_t)a.segs.blocks_per_slice * (uint64_t)a.sl.n_chunks * (uint64_t)a.sl.n_sub;
     if (grids[k] == 0 || grids[k] > 0x7fffffffull) return GNNAGG_EUNSUPPORTED;
@@ -302,7 +374,71 @@ extern "C" int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const 
                                      : launch_op<bf16_t>(opk, args[k], grids[k], stream);
     if (rc != GNNAGG_OK) return rc;
   }
+  if (ws && !args.empty() && args[0].segs.ws_slots > 0) {
+    // the split runs are the same in every launch: they depend on the degree classes only
+    MergeArgs m;
+    m.rowptr = rowptr;
+    m.order = row_order;
+    m.out = out;
+    m.ws = ws;
+    m.F = F;
+    m.out_bf16 = (out_dtype == GNNAGG_BF16);
+    m.mean = (op == GNNAGG_MEAN);
+    m.nrun = 0;
+    m.rows = 0;
+    const SegTable& st = args[0].segs;
+    for (int k = 0; k < st.nseg; ++k) {
+      if (st.seg[k].split_log2 == 0) continue;
+      if (m.nrun >= kMaxSplitSeg) return GNNAGG_EUNSUPPORTED;  // cannot happen: build_segments caps them
+      m.run[m.nrun++] = st.seg[k];
+      m.rows += (int64_t)st.seg[k].row_end - st.seg[k].row_begin;
+    }
+    const int64_t blocks = ceil_div(m.rows * (int64_t)F, kBlock);
+    if (blocks > 0x7fffffffll) return GNNAGG_EUNSUPPORTED;
+    if (opk == OPK_MAX) hipLaunchKernelGGL(split_merge_kernel<OPK_MAX>, dim3((unsigned)blocks), dim3(kBlock), 0, stream, m);
+    else hipLaunchKernelGGL(split_merge_kernel<OPK_SUM>, dim3((unsigned)blocks), dim3(kBlock), 0, stream, m);
+    if (hipGetLastError() != hipSuccess) return GNNAGG_EDEVICE;
+  }
   return GNNAGG_OK;
+}
+
+}  // namespace
+
+extern "C" int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                                const float* edge_w, const void* X, int x_dtype, void* out, int out_dtype,
+                                int32_t F, int32_t f_chunk, const int32_t* row_order, const int64_t* class_off,
+                                void* stream_) {
+  bool nothing;
+  int rc = check_aggregate_args(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, f_chunk, row_order,
+                                class_off, &nothing);
+  if (rc != GNNAGG_OK || nothing) return rc;
+  return aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, f_chunk, row_order,
+                        class_off, nullptr, (hipStream_t)stream_);
+}
+
+extern "C" int gnnagg_aggregate_ws(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                                   const float* edge_w, const void* X, int x_dtype, void* out, int out_dtype,
+                                   int32_t F, int32_t f_chunk, const int32_t* row_order, const int64_t* class_off,
+                                   void* workspace, size_t* workspace_bytes, void* stream_) {
+  if (!workspace_bytes) return GNNAGG_ENULL;
+  if (N < 0 || F <= 0) return GNNAGG_EINVAL;
+  if ((row_order == nullptr) != (class_off == nullptr)) return GNNAGG_EINVAL;
+  if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
+  SegTable probe;
+  int rc = build_segments(class_off, N, 6, true, &probe);  // the split runs do not depend on the slice width
+  if (rc != GNNAGG_OK) return rc;
+  const size_t need = (size_t)probe.ws_slots * (size_t)F * sizeof(double);
+  if (!workspace) {
+    *workspace_bytes = need;
+    return GNNAGG_OK;
+  }
+  if (*workspace_bytes < need || ((uintptr_t)workspace & 255u)) return GNNAGG_EWORKSPACE;
+  bool nothing;
+  rc = check_aggregate_args(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, f_chunk, row_order,
+                            class_off, &nothing);
+  if (rc != GNNAGG_OK || nothing) return rc;
+  return aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, f_chunk, row_order,
+                        class_off, need > 0 ? static_cast<double*>(workspace) : nullptr, (hipStream_t)stream_);
 }
 
 extern "C" int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype) {

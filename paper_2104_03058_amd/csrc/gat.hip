@@ -344,7 +344,7 @@ extern "C" int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
     a.N = N;
     a.sl = launches[k];
     if (a.sl.sub_w % a.sl.vec || a.sl.chunk_w % a.sl.vec) return GNNAGG_EINVAL;  // cannot happen: vec divides C
-    int rc = build_segments(class_off, N, a.sl.g_log2, &a.segs);
+    int rc = build_segments(class_off, N, a.sl.g_log2, false, &a.segs);
     if (rc != GNNAGG_OK) return rc;
     grids[k] = (uint64_t)a.segs.blocks_per_slice * (uint64_t)a.sl.n_chunks * (uint64_t)a.sl.n_sub;
     if (grids[k] == 0 || grids[k] > 0x7fffffffull) return GNNAGG_EUNSUPPORTED;

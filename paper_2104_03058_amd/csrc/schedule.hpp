@@ -14,20 +14,31 @@
 
 namespace gnnagg {
 
-constexpr int kMaxSeg = 8;
+constexpr int kMaxSeg = 16;
+constexpr int kMaxSplitSeg = 7;     // runs of split rows per table (the rest of kMaxSeg: 0..6 and 8 lanes log2)
+constexpr int kSplitClass = 16;     // rows of degree class >= 16 (2^15 edges or more) may be split
+constexpr int kSplitLenLog2 = 13;   // ... into pieces of 2^13 consecutive edges, one workgroup each
 
 // A run of rows (positions in the row plan) handled with 2^lr_log2 lanes per
 // row: lr_log2 in [g_log2, 6] = that many lanes of one wave; 8 = a whole
 // 256-thread workgroup per row (hub rows; partials meet in LDS).
+// split_log2 > 0 (only with lr_log2 == 8, only when the caller gave a workspace): every row of the run
+// is walked by 2^split_log2 workgroups, piece p taking edges [p, p + 1) * 2^kSplitLenLog2 of the row;
+// each piece leaves its partial result in workspace slot ws_begin + (row - row_begin) * 2^split_log2 + p
+// and a merge kernel folds the slots in order.  Without this a row of millions of edges is one
+// workgroup's serial walk and sets the run time of the whole call.
 struct Seg {
   int32_t row_begin, row_end;
   int32_t blk_begin;  // first workgroup of this run inside one slice's block range
   int32_t lr_log2;
+  int32_t split_log2;
+  int32_t ws_begin;
 };
 
 struct SegTable {
   int32_t nseg;
   uint32_t blocks_per_slice;
+  int32_t ws_slots;  // partial-result slots the split runs need (0: nothing is split)
   Seg seg[kMaxSeg];
 };
 
@@ -54,6 +65,9 @@ struct LaneRole {
   bool col_ok;    // the lane has columns
   bool hub;       // the row owns the whole workgroup
   bool writer;    // the lane stores the merged result for its columns
+  int32_t split_log2;  // > 0: the workgroup walks one piece of a split row ...
+  int32_t piece;       // ... this piece ...
+  int32_t ws_slot;     // ... and stores its partial result in this workspace slot instead of `out`
 };
 
 __host__ __device__ inline LaneRole lane_role(const SliceLaunch& sl, const SegTable& segs, uint32_t block,
@@ -71,6 +85,7 @@ __host__ __device__ inline LaneRole lane_role(const SliceLaunch& sl, const SegTa
 
   int32_t row_begin = segs.seg[0].row_begin, row_end = segs.seg[0].row_end;
   int32_t blk_begin = segs.seg[0].blk_begin, L = segs.seg[0].lr_log2;
+  int32_t split = segs.seg[0].split_log2, ws_begin = segs.seg[0].ws_begin;
 #pragma unroll
   for (int k = 1; k < kMaxSeg; ++k) {
     if (k < segs.nseg && lb >= (uint32_t)segs.seg[k].blk_begin) {
@@ -78,16 +93,21 @@ __host__ __device__ inline LaneRole lane_role(const SliceLaunch& sl, const SegTa
       row_end = segs.seg[k].row_end;
       blk_begin = segs.seg[k].blk_begin;
       L = segs.seg[k].lr_log2;
+      split = segs.seg[k].split_log2;
+      ws_begin = segs.seg[k].ws_begin;
     }
   }
   lb -= (uint32_t)blk_begin;
   r.L = L;
   r.g = sl.g_log2;
   r.hub = (L == 8);
+  r.split_log2 = split;
+  r.piece = (int32_t)(lb & ((1u << split) - 1u));
+  r.ws_slot = ws_begin + (int32_t)lb;  // (row - row_begin) * 2^split + piece
   int64_t slot;
   int sub_lane;
   if (r.hub) {
-    slot = lb;
+    slot = lb >> split;
     sub_lane = tid;
   } else {
     slot = ((((int64_t)lb * kWavesPerBlock) + wv) << (6 - L)) + (lane >> L);
@@ -162,29 +182,51 @@ inline void plan_columns(int32_t F, int32_t f_chunk, int max_vec, int vec_multip
 // A row of degree d gets about d/8 neighbour slots (a power of two) so that each
 // slot walks at least eight neighbours; beyond what a wave offers the row moves
 // to a whole workgroup.  Without a plan every row gets one wave.
-inline int build_segments(const int64_t* class_off, int64_t N, int g_log2, SegTable* t) {
+inline int build_segments(const int64_t* class_off, int64_t N, int g_log2, bool allow_split, SegTable* t) {
   t->nseg = 0;
-  int64_t blocks = 0;
+  t->ws_slots = 0;
+  int64_t blocks = 0, ws = 0;
+  int n_split = 0;
   auto rows_per_block = [](int L) -> int64_t { return L == 8 ? 1 : (int64_t)kWavesPerBlock << (6 - L); };
-  auto push = [&](int64_t rb, int64_t re, int L) {
+  auto push = [&](int64_t rb, int64_t re, int L, int split) {
     if (re <= rb) return;
-    if (t->nseg > 0 && t->seg[t->nseg - 1].lr_log2 == L) {
-      // extend the previous run: recompute its block count
+    if (t->nseg > 0) {
+      // extend the previous run if it is of the same kind.  A split run is extended only when the table
+      // has no room for another one (the rows added are shorter, so its piece count covers them).
       Seg& s = t->seg[t->nseg - 1];
-      blocks = s.blk_begin;
-      s.row_end = (int32_t)re;
-      blocks += ceil_div((int64_t)s.row_end - s.row_begin, rows_per_block(L));
-      return;
+      const bool same = s.lr_log2 == L && ((split == 0 && s.split_log2 == 0) ||
+                                           (split > 0 && s.split_log2 > 0 && n_split >= kMaxSplitSeg));
+      if (same) {
+        blocks = s.blk_begin;
+        ws = s.ws_begin;
+        s.row_end = (int32_t)re;
+        const int64_t rows = (int64_t)s.row_end - s.row_begin;
+        if (s.split_log2 > 0) {
+          blocks += rows << s.split_log2;
+          ws += rows << s.split_log2;
+        } else {
+          blocks += ceil_div(rows, rows_per_block(L));
+        }
+        return;
+      }
     }
     Seg& s = t->seg[t->nseg++];
     s.row_begin = (int32_t)rb;
     s.row_end = (int32_t)re;
     s.blk_begin = (int32_t)blocks;
     s.lr_log2 = L;
-    blocks += ceil_div(re - rb, rows_per_block(L));
+    s.split_log2 = split;
+    s.ws_begin = (int32_t)ws;
+    if (split > 0) {
+      ++n_split;
+      blocks += (re - rb) << split;
+      ws += (re - rb) << split;
+    } else {
+      blocks += ceil_div(re - rb, rows_per_block(L));
+    }
   };
   if (!class_off) {
-    push(0, N, 6);
+    push(0, N, 6, 0);
   } else {
     if (class_off[0] != 0 || class_off[GNNAGG_PLAN_CLASSES] != N) return GNNAGG_EINVAL;
     for (int k = 0; k < GNNAGG_PLAN_CLASSES; ++k)
@@ -194,12 +236,14 @@ inline int build_segments(const int64_t* class_off, int64_t N, int g_log2, SegTa
       const int p_log2 = c >= 4 ? c - 4 : 0;     // neighbour slots wanted: degree / 8
       int L = g_log2 + p_log2;
       L = (L >= 8) ? 8 : (L > 6 ? 6 : L);
-      push(class_off[k], class_off[k + 1], L);
-      if (blocks > 0x7fffffffll) return GNNAGG_EUNSUPPORTED;
+      const int split = (allow_split && L == 8 && c >= kSplitClass) ? c - kSplitLenLog2 : 0;
+      push(class_off[k], class_off[k + 1], L, split);
+      if (blocks > 0x7fffffffll || ws > 0x7fffffffll) return GNNAGG_EUNSUPPORTED;
     }
   }
-  if (blocks > 0x7fffffffll) return GNNAGG_EUNSUPPORTED;
+  if (blocks > 0x7fffffffll || t->nseg > kMaxSeg) return GNNAGG_EUNSUPPORTED;
   t->blocks_per_slice = (uint32_t)blocks;
+  t->ws_slots = (int32_t)ws;
   return GNNAGG_OK;
 }
 

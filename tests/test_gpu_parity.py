@@ -508,3 +508,54 @@ def test_seeded_sweep_of_attention_and_csr_cases():
         a_s = W.normal_f32((heads, C), seed=9600 + case, std=0.7)
         a_d = W.normal_f32((heads, C), seed=9700 + case, std=0.7)
         check_gat(N, rp, ci, H, a_s, a_d, f_chunks=(fc,), plans=(bool(case & 1),), what=what + " %dx%d" % (heads, C))
+
+
+# ------------------------------------------------------------------ very long rows, split over workgroups
+def long_rows_graph(N, lengths, seed):
+    """Rows 3, 4, ... receive lengths[k] in-edges from pseudo-random sources; plus a sparse background."""
+    rng = np.random.default_rng(seed)
+    parts_s, parts_d = [], []
+    for k, n in enumerate(lengths):
+        parts_s.append(rng.integers(0, N, size=n).astype(np.int32))
+        parts_d.append(np.full(n, 3 + k, np.int32))
+    s2, d2 = W.random_digraph(N, 4 * N, seed + 1)
+    keep = (d2 < 3) | (d2 >= 3 + len(lengths))  # the long rows keep exactly the lengths asked for
+    return np.concatenate(parts_s + [s2[keep]]), np.concatenate(parts_d + [d2[keep]])
+
+
+@pytest.mark.parametrize("F,fc,bf16", [(100, 0, True), (602, 0, False), (33, 8, False), (8, 0, True), (1, 0, False)])
+def test_rows_split_over_workgroups_match_the_checker(F, fc, bf16):
+    """Rows of 2^15 edges or more are cut into pieces of 2^13 edges when the call has a workspace: piece
+    boundaries (32768 = exactly four pieces, 32769, a row one short of a power of two), several degree
+    classes, and rows just below the threshold that stay with one workgroup."""
+    N = 500
+    src, dst = long_rows_graph(N, [32768, 32769, 65535, 40000, 70001, 32767, 9000], seed=F)
+    rp, ci, _, _ = oracle.build_csr(N, src, dst)
+    w = W.normal_f32((len(ci),), seed=11)
+    X = W.normal_bf16((N, F), seed=600 + F) if bf16 else W.normal_f32((N, F), seed=600 + F)
+    d_rp, d_ci, d_w, d_X = dev(rp), dev(ci), dev(w), dev(X)
+    plan = g.gnnagg_plan_rows(d_rp)
+    need = g.gnnagg_aggregate_workspace_bytes(N, F, plan)
+    assert need == (4 * 8 + 16) * F * 8  # class 16 (32768, 32769, 65535, 40000): 8 pieces each; 17 (70001): 16
+    for name in ("sum", "wsum", "mean", "max"):
+        gop, rop = OPS[name]
+        say("  split rows", name, "F", F, "fc", fc)
+        ref = oracle.aggregate(rop, rp, ci, w, X, threads=8)
+        out = torch.full((N, F), float("nan"), dtype=torch.float32, device="cuda")
+        g.gnnagg_aggregate(gop, d_rp, d_ci, d_w if name == "wsum" else None, d_X, out, fc, plan)
+        whole = g.gnnagg_aggregate(gop, d_rp, d_ci, d_w if name == "wsum" else None, d_X, None, fc, plan,
+                                   split_long_rows=False)
+        if name == "max":
+            assert_bits(host(out), ref, "split max")
+        else:
+            assert_close(host(out), ref, bf16, "split " + name)
+        assert_close(host(out), host(whole), bf16, "split vs one workgroup per row " + name)
+    # bf16 output and a caller-provided workspace that is reused
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    a = g.gnnagg_aggregate(0, d_rp, d_ci, None, d_X, torch.empty((N, F), dtype=torch.bfloat16, device="cuda"), fc,
+                           plan, workspace=ws)
+    b = g.gnnagg_aggregate(0, d_rp, d_ci, None, d_X, torch.empty((N, F), dtype=torch.bfloat16, device="cuda"), fc,
+                           plan, workspace=ws)
+    ref = oracle.aggregate(oracle.SUM, rp, ci, None, X, threads=8)
+    assert np.array_equal(host(a.view(torch.int16)), host(b.view(torch.int16)))
+    assert np.array_equal(host(a.view(torch.int16)).view(np.uint16), W.f32_to_bf16(ref))

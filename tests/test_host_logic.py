@@ -47,6 +47,10 @@ def test_version_and_strerror(lib):
     assert g.gnnagg_strerror(-99) == "unknown status"
 
 
+def other_ptr():
+    return ctypes.c_void_p(8192)
+
+
 def test_argument_validation_returns_before_any_launch(lib):
     """All of these are rejected on the host; no HIP call is reached, so they run without a GPU."""
     EINVAL, ENULL, EUNSUP, EWS = -1, -2, -3, -4
@@ -91,6 +95,26 @@ def test_argument_validation_returns_before_any_launch(lib):
     assert need.value >= 2 * 4 * 8 * 4
     assert gat(4, one, one, one, one, one, 8, 8, f, None, one, 0, None, None, one, ctypes.byref(small), None) == EWS
 
+    aggws = lib.gnnagg_aggregate_ws
+    off = (ctypes.c_int64 * 34)()
+    rows = [0] * 33
+    rows[32 - 16], rows[32 - 17], rows[32 - 3] = 2, 1, 97  # two rows of class 16 (8 pieces), one of class 17 (16)
+    for k in range(33):
+        off[k + 1] = off[k] + rows[k]
+    offp = ctypes.cast(off, ctypes.c_void_p)
+    need = ctypes.c_size_t(77)
+    assert aggws(0, 100, one, one, one, one, 0, other_ptr(), 0, 8, 0, one, offp, None, None, None) == ENULL
+    assert aggws(0, 100, None, None, None, None, 0, None, 0, 8, 0, one, offp, None, ctypes.byref(need), None) == 0
+    assert need.value == (2 * 8 + 16) * 8 * 8          # slots x F x sizeof(double)
+    assert aggws(0, 100, None, None, None, None, 0, None, 0, 8, 0, None, None, None, ctypes.byref(need), None) == 0
+    assert need.value == 0                               # no plan: nothing is split
+    small = ctypes.c_size_t(64)
+    assert aggws(0, 100, one, one, one, one, 0, other_ptr(), 0, 8, 0, one, offp, one, ctypes.byref(small), None) == EWS
+    big = ctypes.c_size_t(1 << 20)
+    assert aggws(0, 100, one, one, one, one, 0, other_ptr(), 0, 8, 0, one, offp, ctypes.c_void_p(4100),
+                 ctypes.byref(big), None) == EWS        # misaligned
+    assert aggws(9, 100, one, one, one, one, 0, other_ptr(), 0, 8, 0, one, offp, one, ctypes.byref(big), None) == EINVAL
+
     comb = lib.gnnagg_combine
     other = ctypes.c_void_p(8192)
     assert comb(-1, one, 0, 8, one, None, 4, 0, other, None) == EINVAL   # N
@@ -117,12 +141,14 @@ def checker(tmp_path_factory):
     return exe
 
 
-def run_checker(exe, F, f_chunk, max_vec, vec_multiple, N, class_counts=None):
-    args = [exe, str(F), str(f_chunk), str(max_vec), str(vec_multiple), str(N), "1" if class_counts else "0"]
+def run_checker(exe, F, f_chunk, max_vec, vec_multiple, N, class_counts=None, split=False):
+    args = [exe, str(F), str(f_chunk), str(max_vec), str(vec_multiple), str(N),
+            ("2" if split else "1") if class_counts else "0"]
     if class_counts:
         args += [str(c) for c in class_counts]
     p = subprocess.run(args, capture_output=True, text=True)
     assert p.returncode == 0 and p.stdout.startswith("OK"), (args, p.stdout, p.stderr)
+    return p.stdout
 
 
 def counts(N, spread):
@@ -152,6 +178,19 @@ def test_geometry_with_degree_classes(checker, F, f_chunk, max_vec):
     N = 300
     cc = counts(N, {0: 7, 2: 40, 3: 33, 4: 29, 5: 21, 6: 17, 7: 13, 8: 9, 9: 6, 11: 5, 15: 3, 32: 1})
     run_checker(checker, F, f_chunk, max_vec, 0, N, cc)
+
+
+@pytest.mark.parametrize("F,f_chunk,max_vec", [(602, 0, 4), (100, 0, 8), (16, 0, 8), (9, 4, 4), (1030, 64, 4)])
+def test_geometry_with_split_rows(checker, F, f_chunk, max_vec):
+    """Rows of 2^15 edges or more are cut into pieces when a workspace is available: every piece covers all
+    columns in a slot of its own, nothing else changes.  Eight long classes exceed the table's seven split
+    runs, so the shortest ones share a run."""
+    N = 200
+    spread = {0: 5, 3: 30, 6: 17, 9: 6, 12: 4, 14: 3, 15: 3, 16: 2, 17: 1, 18: 1, 19: 1, 20: 1, 21: 1, 22: 1, 23: 1}
+    out = run_checker(checker, F, f_chunk, max_vec, 0, N, counts(N, spread), split=True)
+    assert "split_rows=9 " in out, out
+    # without permission to split the same plan is laid out as before
+    assert "split_rows=0 slots=0" in run_checker(checker, F, f_chunk, max_vec, 0, N, counts(N, spread))
 
 
 @pytest.mark.parametrize("heads,C,f_chunk", [(8, 8, 0), (8, 8, 8), (8, 8, 16), (3, 5, 0), (4, 6, 12), (40, 8, 0)])

@@ -178,7 +178,7 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
         a_s, a_d = W.normal_f32((heads, C), seed=14, std=0.1), W.normal_f32((heads, C), seed=15, std=0.1)
         d_as, d_ad = dev(a_s), dev(a_d)
         d_H, out3 = d_X.view(N, heads, C), out.view(N, heads, C)
-        ws = torch.empty(g.gnnagg_gat_workspace_bytes(N, heads, C), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(g.gnnagg_gat_workspace_bytes(N, heads, C, plan), dtype=torch.uint8, device="cuda")
 
         def step():
             g.gnnagg_gat_attention(d_rp, d_ci, d_H, d_as, d_ad, 0.2, False, True, f_chunk, plan, out=out3,

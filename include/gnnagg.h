@@ -185,7 +185,10 @@ GNNAGG_API int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype);
  *              empty rows give 0
  *   f_chunk    0, or a multiple of C (chunks are whole heads); anything else is
  *              GNNAGG_EINVAL
- *   workspace  holds the two score arrays, 2*N*heads fp32
+ *   workspace  holds the two score arrays (2*N*heads fp32) and, when the plan holds rows of 2^15 edges
+ *              or more, the partial softmax states of their pieces (such rows are split over
+ *              workgroups as in gnnagg_aggregate_ws and finished by two small kernels).  Its size
+ *              therefore depends on class_off: query it with the plan the call will use.
  */
 GNNAGG_API int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* H,
                          const float* a_src, const float* a_dst, int32_t heads, int32_t C,

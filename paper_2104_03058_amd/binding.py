@@ -208,23 +208,34 @@ def gnnagg_aggregate(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w
             ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None)
     need = gnnagg_aggregate_workspace_bytes(N, F, plan) if split_long_rows else 0
     if need > 0:
-        if workspace is None:
+        own = workspace is None
+        if own:
             workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
         have = ctypes.c_size_t(workspace.numel() * workspace.element_size())
         rc = lib.gnnagg_aggregate_ws(*head, _dev(workspace), ctypes.byref(have), _stream(stream))
         _check("gnnagg_aggregate_ws", rc)
+        if own:  # read and written by the kernels just enqueued: keep it alive until they ran
+            workspace.record_stream(torch.cuda.current_stream() if stream is None else stream)
     else:
         rc = lib.gnnagg_aggregate(*head, _stream(stream))
         _check("gnnagg_aggregate", rc)
     return out
 
 
-def gnnagg_gat_workspace_bytes(N: int, heads: int, C: int) -> int:
-    """Size of the workspace gnnagg_gat_attention needs (the size query of the C call)."""
+def _plan_args(plan: Optional["RowPlan"], N: int):
+    if plan is None or N == 0:
+        return None, None
+    return _dev(plan.row_order, torch.int32, "row_order"), ctypes.cast(plan.class_off, ctypes.c_void_p)
+
+
+def gnnagg_gat_workspace_bytes(N: int, heads: int, C: int, plan: Optional["RowPlan"] = None) -> int:
+    """Size of the workspace gnnagg_gat_attention needs (the size query of the C call).  It depends on the
+    plan when the plan holds rows long enough to be split: query with the plan the call will use."""
     need = ctypes.c_size_t(0)
+    order, class_off = _plan_args(plan, N)
     _check("gnnagg_gat_attention",
-           load_library().gnnagg_gat_attention(N, None, None, None, None, None, heads, C, 0.2, None, None, 0, None,
-                                               None, None, ctypes.byref(need), None))
+           load_library().gnnagg_gat_attention(N, None, None, None, None, None, heads, C, 0.2, None, None, 0, order,
+                                               class_off, None, ctypes.byref(need), None))
     return int(need.value)
 
 
@@ -242,10 +253,11 @@ def gnnagg_gat_attention(rowptr: torch.Tensor, colidx: torch.Tensor, H: torch.Te
         raise ValueError("a_src and a_dst must be [heads, C]")
     dev = H.device
     nnz = int(colidx.shape[0])
+    order, class_off = _plan_args(plan, N)
     need = ctypes.c_size_t(0)
     _check("gnnagg_gat_attention",
            lib.gnnagg_gat_attention(N, None, None, None, None, None, heads, C, negative_slope, None, None, f_chunk,
-                                    None, None, None, ctypes.byref(need), None))
+                                    order, class_off, None, ctypes.byref(need), None))
     ws = workspace if workspace is not None else _workspace(need.value, dev)
     alpha = torch.empty((nnz, heads), dtype=torch.float32, device=dev) if want_alpha else None
     if want_out and out is None:
@@ -256,9 +268,7 @@ def gnnagg_gat_attention(rowptr: torch.Tensor, colidx: torch.Tensor, H: torch.Te
     rc = lib.gnnagg_gat_attention(N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
                                   _dev(H, torch.float32, "H"), _dev(a_src, torch.float32, "a_src"),
                                   _dev(a_dst, torch.float32, "a_dst"), heads, C, negative_slope, _dev(alpha),
-                                  _dev(out), f_chunk,
-                                  _dev(plan.row_order, torch.int32, "row_order") if plan is not None else None,
-                                  ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None,
+                                  _dev(out), f_chunk, order, class_off,
                                   _dev(ws), ctypes.byref(have), _stream(stream))
     _check("gnnagg_gat_attention", rc)
     # the score arrays in ws are read by the kernels just enqueued: keep ws alive until they ran

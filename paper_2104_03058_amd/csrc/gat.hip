@@ -36,6 +36,7 @@ struct GatArgs {
   int32_t heads, C;
   float slope;
   int64_t N;
+  double* pieces;  // partial softmax states of split rows: [slot][heads * C sums | heads references | heads denominators]
   SliceLaunch sl;
   SegTable segs;
 };
@@ -202,6 +203,12 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
   }
   const int head = col / a.C;  // VEC divides C, so the lane's columns lie in one head
   const int64_t HC = (int64_t)a.heads * a.C;
+  const bool split = role.split_log2 > 0;  // this workgroup walks one piece of a very long row
+  if (split) {
+    e0 += (int64_t)role.piece << kSplitLenLog2;
+    if (e0 > e1) e0 = e1;
+    if (e1 - e0 > ((int64_t)1 << kSplitLenLog2)) e1 = e0 + ((int64_t)1 << kSplitLenLog2);
+  }
 
   GatAcc<VEC, LH> acc;
   acc.st.init();
@@ -247,6 +254,19 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
     st.l = fin[kWave + lane];
   }
 
+  if (split) {
+    // leave the piece's state in its workspace slot; the merge kernels finish the row
+    if (role.writer) {
+      double* p = a.pieces + (int64_t)role.ws_slot * (HC + 2 * a.heads);
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) p[col + k] = st.acc[k];
+      if ((col % a.C) == 0) {
+        p[HC + head] = (double)st.m;
+        p[HC + a.heads + head] = st.l;
+      }
+    }
+    return;
+  }
   if (a.out && role.writer) {
     float res[VEC];
 #pragma unroll
@@ -260,6 +280,81 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
       const float s = a.s_src[(int64_t)a.colidx[e] * a.heads + head] + sd;
       const float logit = s >= 0.0f ? s : a.slope * s;
       a.alpha[e * a.heads + head] = (float)((double)exp_fast(logit - st.m) / st.l);
+    }
+  }
+}
+
+// Split rows: fold the pieces of a row in piece order.  One thread per (split row, column); the first
+// column of a head also records the row's final reference and denominator for the weights.
+struct GatMergeArgs {
+  const int64_t* rowptr;
+  const int32_t* colidx;
+  const int32_t* order;
+  const float* s_src;
+  const float* s_dst;
+  float* alpha;
+  float* out;
+  const double* pieces;
+  double* fin;   // [split row][head][reference, denominator]
+  int64_t rows;  // split rows in all runs together
+  int32_t heads, C, nrun;
+  float slope;
+  Seg run[kMaxSplitSeg];
+};
+
+__device__ inline int find_run(const GatMergeArgs& a, int64_t* i) {
+  int k = 0;
+  while (k + 1 < a.nrun && *i >= (int64_t)a.run[k].row_end - a.run[k].row_begin) {
+    *i -= (int64_t)a.run[k].row_end - a.run[k].row_begin;
+    ++k;
+  }
+  return k;
+}
+
+__global__ __launch_bounds__(kBlock) void gat_split_merge_kernel(const GatMergeArgs a) {
+  const int64_t HC = (int64_t)a.heads * a.C;
+  const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (t >= a.rows * HC) return;
+  const int64_t row_i = t / HC;
+  const int64_t col = t - row_i * HC;
+  const int head = (int)(col / a.C);
+  int64_t i = row_i;
+  const Seg run = a.run[find_run(a, &i)];
+  const int64_t r = a.order[run.row_begin + i];
+  const int64_t n_pieces = (int64_t)1 << run.split_log2;
+  const int64_t pitch = HC + 2 * a.heads;
+  const double* p = a.pieces + ((int64_t)run.ws_begin + i * n_pieces) * pitch;
+  SoftState<1> st;
+  st.init();
+  for (int64_t q = 0; q < n_pieces; ++q, p += pitch) {
+    SoftState<1> o;
+    o.m = (float)p[HC + head];
+    o.l = p[HC + a.heads + head];
+    o.acc[0] = p[col];
+    st.merge(o);
+  }
+  if (a.out) a.out[r * HC + col] = st.l > 0.0 ? (float)(st.acc[0] / st.l) : 0.0f;
+  if (col == (int64_t)head * a.C) {
+    a.fin[(row_i * a.heads + head) * 2] = (double)st.m;
+    a.fin[(row_i * a.heads + head) * 2 + 1] = st.l;
+  }
+}
+
+// Softmax weights of the split rows: blockIdx.y strides over the rows, the threads of a block row over
+// (edge, head) pairs.
+__global__ __launch_bounds__(kBlock) void gat_split_alpha_kernel(const GatMergeArgs a) {
+  for (int64_t row_i = blockIdx.y; row_i < a.rows; row_i += gridDim.y) {
+    int64_t i = row_i;
+    const Seg run = a.run[find_run(a, &i)];
+    const int64_t r = a.order[run.row_begin + i];
+    const int64_t e0 = a.rowptr[r], n = (a.rowptr[r + 1] - e0) * a.heads;
+    for (int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x; t < n; t += (int64_t)gridDim.x * kBlock) {
+      const int64_t e = e0 + t / a.heads;
+      const int head = (int)(t % a.heads);
+      const float s = a.s_src[(int64_t)a.colidx[e] * a.heads + head] + a.s_dst[r * a.heads + head];
+      const float logit = s >= 0.0f ? s : a.slope * s;
+      const double m = a.fin[(row_i * a.heads + head) * 2], l = a.fin[(row_i * a.heads + head) * 2 + 1];
+      a.alpha[e * a.heads + head] = (float)((double)exp_fast(logit - (float)m) / l);
     }
   }
 }
@@ -307,9 +402,24 @@ extern "C" int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
   if (!workspace_bytes) return GNNAGG_ENULL;
   if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
   if ((row_order == nullptr) != (class_off == nullptr)) return GNNAGG_EINVAL;
+  // rows long enough to be split (they exist only with a plan): slots for the pieces, finals per row
+  SegTable probe;
+  {
+    int rc = build_segments(class_off, N, 6, true, &probe);  // the split runs do not depend on the slice width
+    if (rc != GNNAGG_OK) return rc;
+  }
+  int64_t split_rows = 0;
+  for (int k = 0; k < probe.nseg; ++k)
+    if (probe.seg[k].split_log2 > 0) split_rows += (int64_t)probe.seg[k].row_end - probe.seg[k].row_begin;
   Carver carve(workspace);
   float* s_src = carve.take<float>((size_t)(N > 0 ? N : 1) * heads);
   float* s_dst = carve.take<float>((size_t)(N > 0 ? N : 1) * heads);
+  double* pieces = nullptr;
+  double* fin = nullptr;
+  if (probe.ws_slots > 0) {
+    pieces = carve.take<double>((size_t)probe.ws_slots * ((size_t)F + 2 * (size_t)heads));
+    fin = carve.take<double>((size_t)split_rows * (size_t)heads * 2);
+  }
   if (!workspace) {
     *workspace_bytes = carve.used;
     return GNNAGG_OK;
@@ -342,9 +452,10 @@ extern "C" int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
     a.C = C;
     a.slope = negative_slope;
     a.N = N;
+    a.pieces = pieces;
     a.sl = launches[k];
     if (a.sl.sub_w % a.sl.vec || a.sl.chunk_w % a.sl.vec) return GNNAGG_EINVAL;  // cannot happen: vec divides C
-    int rc = build_segments(class_off, N, a.sl.g_log2, false, &a.segs);
+    int rc = build_segments(class_off, N, a.sl.g_log2, pieces != nullptr, &a.segs);
     if (rc != GNNAGG_OK) return rc;
     grids[k] = (uint64_t)a.segs.blocks_per_slice * (uint64_t)a.sl.n_chunks * (uint64_t)a.sl.n_sub;
     if (grids[k] == 0 || grids[k] > 0x7fffffffull) return GNNAGG_EUNSUPPORTED;
@@ -373,6 +484,42 @@ extern "C" int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
         break;
     }
     if (rc != GNNAGG_OK) return rc;
+  }
+  if (pieces) {
+    GatMergeArgs m;
+    m.rowptr = rowptr;
+    m.colidx = colidx;
+    m.order = row_order;
+    m.s_src = s_src;
+    m.s_dst = s_dst;
+    m.alpha = alpha;
+    m.out = out;
+    m.pieces = pieces;
+    m.fin = fin;
+    m.rows = split_rows;
+    m.heads = heads;
+    m.C = C;
+    m.slope = negative_slope;
+    m.nrun = 0;
+    int max_split = 0;
+    for (int k = 0; k < probe.nseg; ++k) {
+      if (probe.seg[k].split_log2 == 0) continue;
+      if (m.nrun >= kMaxSplitSeg) return GNNAGG_EUNSUPPORTED;  // cannot happen: build_segments caps them
+      m.run[m.nrun++] = probe.seg[k];
+      if (probe.seg[k].split_log2 > max_split) max_split = probe.seg[k].split_log2;
+    }
+    const int64_t blocks = ceil_div(split_rows * (int64_t)F, kBlock);
+    if (blocks > 0x7fffffffll) return GNNAGG_EUNSUPPORTED;
+    hipLaunchKernelGGL(gat_split_merge_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, stream, m);
+    GNNAGG_HIP_TRY(hipGetLastError());
+    if (alpha) {
+      // enough blocks per row for the longest row a run can hold, capped; the kernel strides over the rest
+      int64_t bx = ceil_div(((int64_t)1 << (max_split + kSplitLenLog2)) * heads, kBlock);
+      if (bx > 4096) bx = 4096;
+      const int64_t by = split_rows < 65535 ? split_rows : 65535;
+      hipLaunchKernelGGL(gat_split_alpha_kernel, dim3((unsigned)bx, (unsigned)by), dim3(kBlock), 0, stream, m);
+      GNNAGG_HIP_TRY(hipGetLastError());
+    }
   }
   return GNNAGG_OK;
 }

@@ -559,3 +559,27 @@ def test_rows_split_over_workgroups_match_the_checker(F, fc, bf16):
     ref = oracle.aggregate(oracle.SUM, rp, ci, None, X, threads=8)
     assert np.array_equal(host(a.view(torch.int16)), host(b.view(torch.int16)))
     assert np.array_equal(host(a.view(torch.int16)).view(np.uint16), W.f32_to_bf16(ref))
+
+
+@pytest.mark.parametrize("heads,C,fc", [(8, 8, 0), (2, 5, 5), (1, 64, 0), (16, 8, 64)])
+def test_attention_rows_split_over_workgroups_match_the_checker(heads, C, fc):
+    """Attention on rows of 2^15 edges or more: pieces leave softmax states (reference, denominator,
+    weighted sums) in the workspace, the merge kernel folds them, a third kernel writes the weights."""
+    N = 400
+    src, dst = long_rows_graph(N, [32768, 32769, 50000, 70001, 32767], seed=heads * C)
+    rp, ci, _, _ = oracle.build_csr(N, src, dst, oracle.SELF_LOOPS)
+    H = W.normal_f32((N, heads, C), seed=700 + C)
+    a_s = W.normal_f32((heads, C), seed=701, std=0.6)
+    a_d = W.normal_f32((heads, C), seed=702, std=0.6)
+    d_rp = dev(rp)
+    plan = g.gnnagg_plan_rows(d_rp)
+    assert g.gnnagg_gat_workspace_bytes(N, heads, C, plan) > g.gnnagg_gat_workspace_bytes(N, heads, C)
+    check_gat(N, rp, ci, H, a_s, a_d, f_chunks=(fc,), plans=(True, False), what="gat split %dx%d" % (heads, C))
+    # weights only, and sums only
+    ralpha, rout = oracle.gat_attention(rp, ci, H, a_s, a_d, 0.2, threads=8)
+    alpha, none = g.gnnagg_gat_attention(d_rp, dev(ci), dev(H), dev(a_s), dev(a_d), 0.2, True, False, fc, plan)
+    assert none is None
+    assert_close(host(alpha), ralpha, what="weights only")
+    sums = host(alpha).astype(np.float64)
+    seg = np.add.reduceat(sums, rp[:-1][np.diff(rp) > 0], axis=0)
+    assert np.allclose(seg, 1.0, atol=1e-5)

@@ -32,8 +32,8 @@ MFMA_F64_PEAK_TFLOPS = 78.6
 MEASURED_TRAFFIC = {
     "c4-gcn": 178.010e9,  # profiles/aggregate_kernel_c4_gcn.txt
     "c5-sum": 16.558e9,   # profiles/aggregate_kernel_c5_sum_bf16.txt
-    "c4-gat": 14.650e9,   # profiles/gat_aggregate_kernel_c4_gat.txt
-    "c4-hid32-gcn": 6.424e9,  # profiles/aggregate_kernel_c4_hidden32_gcn.txt
+    "c4-gat": 14.677e9,   # profiles/gat_aggregate_kernel_c4_gat.txt
+    "c4-hid32-gcn": 6.473e9,  # profiles/aggregate_kernel_c4_hidden32_gcn.txt
 }
 
 WORKLOADS = {

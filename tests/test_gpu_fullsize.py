@@ -187,3 +187,58 @@ def test_combination_at_the_dense_graph_size_and_the_layer_built_from_it():
     mag = oracle.aggregate_rows(oracle.WSUM, some, rp, ci, w, np.abs(X), threads=16)
     scale = mag.astype(np.float64) @ np.abs(Wt).astype(np.float64)
     assert np.all(np.abs(got - ref) <= 1e-6 + 1e-6 * scale), float(np.max(np.abs(got - ref) / (1e-6 + 1e-6 * scale)))
+
+
+def test_more_than_two_to_the_31_edges():
+    """2.3e9 edges (beyond 2^31 edge positions, below the 2^32 limit of the CSR build) on 50,000 vertices.
+    No checker can run at this size; everything asserted is a property that holds exactly at any size:
+    row lengths equal the in-degree counts, rows are sorted and hold the right multiset of sources, the
+    all-ones matrix aggregates to the degree, a small-integer matrix to the exact integer sums, and max of
+    X[j] = j to the largest source of the row.  Every row is long enough to be split over workgroups."""
+    import paper_2104_03058_amd as g
+    free, _ = torch.cuda.mem_get_info()
+    if free < 160 * (1 << 30):
+        pytest.skip("needs about 150 GB of free device memory")
+    N, E = 50_000, 2_300_000_000
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(2104)
+    src = torch.randint(0, N, (E,), dtype=torch.int32, device="cuda", generator=gen)
+    dst = torch.randint(0, N, (E,), dtype=torch.int32, device="cuda", generator=gen)
+    say("big: edges drawn")
+    rp, ci, _, _ = g.gnnagg_build_csr(N, src, dst, 0)
+    torch.cuda.synchronize()
+    say("big: CSR built")
+    deg = torch.bincount(dst.long(), minlength=N)
+    assert int(rp[0]) == 0 and int(rp[N]) == E
+    assert torch.equal(rp[1:] - rp[:-1], deg)
+    # inside a row the sources ascend: a descent may only sit where a row starts
+    starts = torch.zeros(E + 1, dtype=torch.bool, device="cuda")
+    starts[rp] = True
+    descent = ci[1:] < ci[:-1]
+    assert bool((~descent | starts[1:E]).all())
+    del descent, starts
+    # the same multiset of sources per row, seen through two exact integer sums
+    rows_of = torch.repeat_interleave(torch.arange(N, device="cuda"), deg)
+    for power in (1, 2):
+        want = torch.zeros(N, dtype=torch.int64, device="cuda").index_add_(0, dst.long(), src.long() ** power)
+        got = torch.zeros(N, dtype=torch.int64, device="cuda").index_add_(0, rows_of, ci.long() ** power)
+        assert torch.equal(got, want)
+    want_max = torch.full((N,), -1, dtype=torch.int64, device="cuda").scatter_reduce_(0, dst.long(), src.long(), "amax")
+    del src, dst, rows_of
+    say("big: CSR properties hold")
+    plan = g.gnnagg_plan_rows(rp)
+    assert g.gnnagg_aggregate_workspace_bytes(N, 8, plan) > 0  # mean degree 46,000: rows are split
+    ones = torch.ones((N, 8), dtype=torch.float32, device="cuda")
+    out = g.gnnagg_aggregate(g.SUM, rp, ci, None, ones, None, 0, plan)
+    assert torch.equal(out[:, 0].long(), deg) and torch.equal(out[:, 7], out[:, 0])
+    ids = torch.arange(N, device="cuda")
+    X = torch.stack([(ids % 7).float(), ids.float(), (ids % 3).float(), torch.ones_like(ids).float()], dim=1).contiguous()
+    s = g.gnnagg_aggregate(g.SUM, rp, ci, None, X, None, 0, plan)  # sums stay below 2^24: exact in fp32
+    want7 = torch.zeros(N, dtype=torch.int64, device="cuda").index_add_(
+        0, torch.repeat_interleave(torch.arange(N, device="cuda"), deg), ci.long() % 7)
+    assert torch.equal(s[:, 0].long(), want7) and torch.equal(s[:, 3].long(), deg)
+    m = g.gnnagg_aggregate(g.MAX, rp, ci, None, X, None, 0, plan)
+    assert torch.equal(m[:, 1].long(), want_max)
+    m2 = g.gnnagg_aggregate(g.MAX, rp, ci, None, X, None, 0, plan, split_long_rows=False)
+    assert torch.equal(m, m2)
+    say("big: aggregation properties hold")

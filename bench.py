@@ -30,10 +30,10 @@ MFMA_F64_PEAK_TFLOPS = 78.6
 # probe: see profiles/aggregate_kernel_*.txt), valid for the kernels as committed with those profiles and
 # for f_chunk = 0 only.  Set an entry to None when the kernel changes until the counters are taken again.
 MEASURED_TRAFFIC = {
-    "c4-gcn": 178.010e9,  # profiles/aggregate_kernel_c4_gcn.txt
-    "c5-sum": 16.558e9,   # profiles/aggregate_kernel_c5_sum_bf16.txt
+    "c4-gcn": 169.947e9,  # profiles/aggregate_kernel_c4_gcn.txt
+    "c5-sum": 13.323e9,   # profiles/aggregate_kernel_c5_sum_bf16.txt
     "c4-gat": 14.677e9,   # profiles/gat_aggregate_kernel_c4_gat.txt
-    "c4-hid32-gcn": 6.473e9,  # profiles/aggregate_kernel_c4_hidden32_gcn.txt
+    "c4-hid32-gcn": 6.477e9,  # profiles/aggregate_kernel_c4_hidden32_gcn.txt
 }
 
 WORKLOADS = {
@@ -135,7 +135,7 @@ def measure_layer(g, W, torch, workload, steps, warmup, copy_gbs):
     return rec
 
 
-def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_seconds, copy_gbs):
+def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_seconds, copy_gbs, pitched=True):
     """One workload: setup (CSR build, row plan), timed aggregation steps, optional CPU-checker leg."""
     gkey, opname, F, xdt, gcn = WORKLOADS[workload]
     if opname in ("combine", "layer"):
@@ -174,6 +174,13 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
     log("device CSR build %.1f ms, row plan %.1f ms, nnz=%d" % (t_csr * 1e3, t_plan * 1e3, nnz))
 
     out = torch.empty((N, F), dtype=torch.float32, device="cuda")
+    if pitched and not gat:
+        # rows of X and out start on 128-byte lines (the layout the library recommends: gnnagg_row_pitch);
+        # the padding columns are never read or written and are not counted in any byte figure
+        Xp = g.pitched_empty(N, F, d_X.dtype)
+        Xp.copy_(d_X)
+        d_X = Xp
+        out = g.pitched_empty(N, F, torch.float32)
     if gat:
         a_s, a_d = W.normal_f32((heads, C), seed=14, std=0.1), W.normal_f32((heads, C), seed=15, std=0.1)
         d_as, d_ad = dev(a_s), dev(a_d)
@@ -218,7 +225,7 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
     compulsory = N * F * x_bytes + N * F * 4 + nnz * (8 if opname == "wsum" else 4) + (N + 1) * 8
     if gat:
         compulsory += 2 * N * heads * 4
-    traffic = MEASURED_TRAFFIC.get(workload) if f_chunk == 0 else None
+    traffic = MEASURED_TRAFFIC.get(workload) if (f_chunk == 0 and pitched) else None  # taken in that layout
     log("step %.3f ms wall, kernel mean %.3f ms (min %.3f), %.3e edge-features/s, %.0f GB/s algorithmic" %
         (ms_per_step, kern_ms, ms.min(), edge_features / (ms_per_step * 1e-3), achieved))
 
@@ -268,7 +275,8 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": workload, "graph": W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "op": opname,
-                   "f_chunk": f_chunk, "x_dtype": xdt},
+                   "f_chunk": f_chunk, "x_dtype": xdt, "x_row_pitch": int(d_X.stride(0)),
+                   "out_row_pitch": int(out.stride(0))},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic,
@@ -321,6 +329,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--also", default="c5-sum",
                     help="comma list of further workloads measured after the main one and reported under 'also'")
+    ap.add_argument("--contiguous", action="store_true",
+                    help="keep X and out at a row pitch of exactly F elements instead of line-aligned rows")
     ap.add_argument("--cpu-chunk-sweep", default="",
                     help="comma list of chunk widths: also time the CPU checker in Algorithm 1's chunk-outer order "
                          "on the whole graph of the workload at each width (0 = one chunk); minutes of CPU time")
@@ -359,10 +369,10 @@ def main():
         return
 
     rec = measure(g, W, torch, args.workload, args.f_chunk, args.steps, args.warmup, not args.no_cpu_baseline,
-                  args.cpu_seconds, copy_gbs)
+                  args.cpu_seconds, copy_gbs, not args.contiguous)
     also = []
     for wl in [w for w in args.also.split(",") if w and w != args.workload]:
-        r = measure(g, W, torch, wl, 0, args.steps, args.warmup, False, 0.0, copy_gbs)
+        r = measure(g, W, torch, wl, 0, args.steps, args.warmup, False, 0.0, copy_gbs, not args.contiguous)
         also.append({k: r[k] for k in ("value", "unit", "ms_per_step", "config", "roofline", "setup")})
     rec["also"] = also
     if args.cpu_chunk_sweep:

@@ -147,25 +147,35 @@ GNNAGG_API int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const 
                      const int32_t* row_order, const int64_t* class_off, void* stream);
 
 /*
- * gnnagg_aggregate with a workspace that lets very long rows be split (same operation, same
- * arguments, same result up to the order of the fp64 additions; max is bit-identical).
+ * gnnagg_aggregate with row pitches and a workspace (same operation, same result up to the order
+ * of the fp64 additions; max is bit-identical).
  *
- * Power-law graphs (Section III, Table II) can hold rows with millions of in-edges.  gnnagg_aggregate
- * gives such a row to one workgroup, whose serial walk then sets the run time of the whole call.
- * With a plan and a workspace, every row of 2^15 edges or more is cut into pieces of 2^13 consecutive
- * edges; one workgroup per piece leaves an fp64 partial result in the workspace and a second kernel
- * folds the pieces of a row in order (no atomics: results stay bit-reproducible).
+ *   x_pitch, out_pitch   elements between the starts of consecutive rows of X / out (>= F; 0 = F).
+ *            A gather moves whole 128-byte lines: a 200-byte row (100 bf16 columns) at a 200-byte
+ *            pitch straddles 2.55 lines on average, at a 256-byte pitch exactly 2.  gnnagg_row_pitch
+ *            returns the pitch that puts every row on line boundaries.  Columns [F, pitch) are never
+ *            read or written.
  *
- *   workspace, workspace_bytes   the usual protocol: workspace == NULL returns the size in
- *            *workspace_bytes and launches nothing.  The size depends on (N, F, class_off) only and
- *            is 0 when the plan holds no such row or there is no plan; then call gnnagg_aggregate, or
+ *   workspace, workspace_bytes   Power-law graphs (Section III, Table II) can hold rows with millions
+ *            of in-edges.  gnnagg_aggregate gives such a row to one workgroup, whose serial walk then
+ *            sets the run time of the whole call.  With a plan and a workspace, every row of 2^15 edges
+ *            or more is cut into pieces of 2^13 consecutive edges; one workgroup per piece leaves an
+ *            fp64 partial result in the workspace and a second kernel folds the pieces of a row in
+ *            order (no atomics: results stay bit-reproducible).  The usual protocol: workspace == NULL
+ *            returns the size in *workspace_bytes and launches nothing.  The size depends on
+ *            (N, F, class_off) only and is 0 when the plan holds no such row or there is no plan; then
  *            pass any non-NULL 256-byte-aligned pointer.  The workspace may be reused by the next call
  *            on the same stream; calls on different streams need workspaces of their own.
  */
 GNNAGG_API int gnnagg_aggregate_ws(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
-                        const float* edge_w, const void* X, int x_dtype, void* out, int out_dtype, int32_t F,
-                        int32_t f_chunk, const int32_t* row_order, const int64_t* class_off, void* workspace,
-                        size_t* workspace_bytes, void* stream);
+                        const float* edge_w, const void* X, int x_dtype, int64_t x_pitch, void* out,
+                        int out_dtype, int64_t out_pitch, int32_t F, int32_t f_chunk, const int32_t* row_order,
+                        const int64_t* class_off, void* workspace, size_t* workspace_bytes, void* stream);
+
+/* Row pitch (in elements) that starts every row of an [N,F] matrix of the given type on a 128-byte line
+ * boundary, or on a power-of-two fraction of a line for rows shorter than one (host arithmetic only;
+ * 0 for invalid arguments). */
+GNNAGG_API int64_t gnnagg_row_pitch(int32_t F, int dtype);
 
 /* The chunk width gnnagg_aggregate uses for GNNAGG_F_CHUNK_AUTO (host-side arithmetic only). */
 GNNAGG_API int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype);

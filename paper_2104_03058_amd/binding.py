@@ -57,7 +57,10 @@ def load_library():
         lib.gnnagg_aggregate.restype = ci
         lib.gnnagg_aggregate.argtypes = [ci, i64, vp, vp, vp, vp, ci, vp, ci, i32, i32, vp, vp, vp]
         lib.gnnagg_aggregate_ws.restype = ci
-        lib.gnnagg_aggregate_ws.argtypes = [ci, i64, vp, vp, vp, vp, ci, vp, ci, i32, i32, vp, vp, vp, szp, vp]
+        lib.gnnagg_aggregate_ws.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, vp, ci, i64, i32, i32, vp, vp, vp, szp,
+                                            vp]
+        lib.gnnagg_row_pitch.restype = i64
+        lib.gnnagg_row_pitch.argtypes = [i32, ci]
         lib.gnnagg_gat_attention.restype = ci
         lib.gnnagg_gat_attention.argtypes = [i64, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp, i32, vp, vp, vp, szp,
                                              vp]
@@ -89,6 +92,37 @@ def _dev(t: Optional[torch.Tensor], dtype=None, name="tensor"):
     if dtype is not None and t.dtype != dtype:
         raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
     return ctypes.c_void_p(t.data_ptr())
+
+
+_TOKENS = {}
+
+
+def _token(device) -> torch.Tensor:
+    """A 256-byte device buffer per device, handed over where a call wants a workspace pointer but needs
+    no workspace."""
+    key = (device.type, device.index if device.index is not None else torch.cuda.current_device())
+    if key not in _TOKENS:
+        _TOKENS[key] = torch.empty(256, dtype=torch.uint8, device=device)
+    return _TOKENS[key]
+
+
+def _rows(t: torch.Tensor, name: str):
+    """A 2-D GPU tensor whose rows are contiguous; the rows themselves may be a pitch apart."""
+    if not t.is_cuda:
+        raise ValueError("%s must be a GPU tensor" % name)
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1) or (t.shape[0] > 1 and t.stride(0) < t.shape[1]):
+        raise ValueError("%s must be [N, F] with contiguous rows" % name)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def gnnagg_row_pitch(F: int, dtype: torch.dtype = torch.float32) -> int:
+    """Elements per row that put every row of an [N, F] matrix on 128-byte line boundaries."""
+    return int(load_library().gnnagg_row_pitch(F, F32 if dtype == torch.float32 else BF16))
+
+
+def pitched_empty(N: int, F: int, dtype: torch.dtype = torch.float32, device="cuda") -> torch.Tensor:
+    """An uninitialised [N, F] view into an [N, gnnagg_row_pitch] allocation (memory only, no arithmetic)."""
+    return torch.empty((N, gnnagg_row_pitch(F, dtype)), dtype=dtype, device=device)[:, :F]
 
 
 def _stream(stream) -> ctypes.c_void_p:
@@ -174,7 +208,7 @@ def gnnagg_aggregate_workspace_bytes(N: int, F: int, plan: Optional["RowPlan"]) 
         return 0
     need = ctypes.c_size_t(0)
     _check("gnnagg_aggregate_ws",
-           load_library().gnnagg_aggregate_ws(0, N, None, None, None, None, F32, None, F32, F, 0,
+           load_library().gnnagg_aggregate_ws(0, N, None, None, None, None, F32, 0, None, F32, 0, F, 0,
                                               _dev(plan.row_order, torch.int32, "row_order"),
                                               ctypes.cast(plan.class_off, ctypes.c_void_p), None,
                                               ctypes.byref(need), None))
@@ -186,9 +220,10 @@ def gnnagg_aggregate(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w
                      plan: Optional[RowPlan] = None, stream=None,
                      workspace: Optional[torch.Tensor] = None, split_long_rows: bool = True) -> torch.Tensor:
     """out[N,F] (fp32, or bf16 if a bf16 tensor is passed) = aggregation of X[N,F] over the CSR; enqueued on the
-    current stream.  With a plan that holds very long rows the call goes through gnnagg_aggregate_ws (the
+    current stream.  X and out may be row-pitched views (contiguous rows, stride(0) >= F; see pitched_empty).
+    With pitched rows, or a plan that holds very long rows, the call goes through gnnagg_aggregate_ws (the
     workspace is allocated here unless one of at least gnnagg_aggregate_workspace_bytes is passed in);
-    split_long_rows=False forces the plain entry point."""
+    split_long_rows=False keeps every row with one workgroup."""
     lib = load_library()
     if X.dim() != 2:
         raise ValueError("X must be [N, F]")
@@ -201,23 +236,27 @@ def gnnagg_aggregate(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w
         raise ValueError("out must be [N, F]")
     if out.dtype not in (torch.float32, torch.bfloat16):
         raise TypeError("out must be float32 or bfloat16")
-    head = (op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
-            _dev(edge_w, torch.float32, "edge_w"), _dev(X, None, "X"), _x_dtype(X),
-            _dev(out, None, "out"), F32 if out.dtype == torch.float32 else BF16, F, f_chunk,
-            _dev(plan.row_order, torch.int32, "row_order") if plan is not None else None,
-            ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None)
+    order, class_off = _plan_args(plan, N)
+    x_pitch, out_pitch = int(X.stride(0)) if N > 1 else F, int(out.stride(0)) if N > 1 else F
+    pitched = x_pitch != F or out_pitch != F
     need = gnnagg_aggregate_workspace_bytes(N, F, plan) if split_long_rows else 0
-    if need > 0:
-        own = workspace is None
-        if own:
-            workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    if need > 0 or pitched:
+        own = workspace is None and need > 0
+        if workspace is None:  # nothing to hold: any aligned pointer serves, kept per device
+            workspace = torch.empty(need, dtype=torch.uint8, device=X.device) if need > 0 else _token(X.device)
         have = ctypes.c_size_t(workspace.numel() * workspace.element_size())
-        rc = lib.gnnagg_aggregate_ws(*head, _dev(workspace), ctypes.byref(have), _stream(stream))
+        rc = lib.gnnagg_aggregate_ws(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
+                                     _dev(edge_w, torch.float32, "edge_w"), _rows(X, "X"), _x_dtype(X), x_pitch,
+                                     _rows(out, "out"), F32 if out.dtype == torch.float32 else BF16, out_pitch, F,
+                                     f_chunk, order, class_off, _dev(workspace), ctypes.byref(have), _stream(stream))
         _check("gnnagg_aggregate_ws", rc)
         if own:  # read and written by the kernels just enqueued: keep it alive until they ran
             workspace.record_stream(torch.cuda.current_stream() if stream is None else stream)
     else:
-        rc = lib.gnnagg_aggregate(*head, _stream(stream))
+        rc = lib.gnnagg_aggregate(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
+                                  _dev(edge_w, torch.float32, "edge_w"), _dev(X, None, "X"), _x_dtype(X),
+                                  _dev(out, None, "out"), F32 if out.dtype == torch.float32 else BF16, F, f_chunk,
+                                  order, class_off, _stream(stream))
         _check("gnnagg_aggregate", rc)
     return out
 

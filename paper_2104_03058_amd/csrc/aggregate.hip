@@ -35,6 +35,7 @@ struct AggArgs {
   int32_t out_bf16;  // 1: out holds bf16 (the fp32 result rounded to nearest even), 0: fp32
   const int32_t* order;
   int64_t F;
+  int64_t x_pitch, out_pitch;  // elements between consecutive rows of X / out (>= F)
   int64_t N;
   SliceLaunch sl;
   int32_t mean;
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
   AggAcc<T, OPK, VEC> acc;
   acc.st.init();
   acc.xb = static_cast<const char*>(a.X) + (int64_t)col * (int64_t)sizeof(T);
-  acc.rowbytes = a.F * (int64_t)sizeof(T);
+  acc.rowbytes = a.x_pitch * (int64_t)sizeof(T);
   const int64_t nnz = (MODE == MODE_NARROW) ? a.rowptr[a.N] : 0;
   gather_row<MODE>(acc, a.colidx, a.edge_w, e0, e1, role.ng, g, role.L, col_ok, lane, nnz);
   State<OPK, VEC>& st = acc.st;
@@ -215,8 +216,8 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
     float res[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) res[k] = st.result(k, deg, a.mean != 0);
-    if (a.out_bf16) store_row_bf16<VEC>(static_cast<uint16_t*>(a.out) + r * a.F + col, res);
-    else store_row<VEC>(static_cast<float*>(a.out) + r * a.F + col, res);
+    if (a.out_bf16) store_row_bf16<VEC>(static_cast<uint16_t*>(a.out) + r * a.out_pitch + col, res);
+    else store_row<VEC>(static_cast<float*>(a.out) + r * a.out_pitch + col, res);
   }
 }
 
@@ -226,7 +227,7 @@ struct MergeArgs {
   const int32_t* order;
   void* out;
   const double* ws;
-  int64_t F;
+  int64_t F, out_pitch;
   int64_t rows;  // split rows in all runs together
   int32_t out_bf16, mean, nrun;
   Seg run[kMaxSplitSeg];
@@ -257,8 +258,8 @@ __global__ __launch_bounds__(kBlock) void split_merge_kernel(const MergeArgs a) 
     st.merge(o);
   }
   const float res = st.result(0, deg, a.mean != 0);
-  if (a.out_bf16) static_cast<uint16_t*>(a.out)[r * a.F + col] = (uint16_t)bf16_bits(res);
-  else static_cast<float*>(a.out)[r * a.F + col] = res;
+  if (a.out_bf16) static_cast<uint16_t*>(a.out)[r * a.out_pitch + col] = (uint16_t)bf16_bits(res);
+  else static_cast<float*>(a.out)[r * a.out_pitch + col] = res;
 }
 
 template <typename T, int OPK, int VEC, int MODE>
@@ -338,8 +339,9 @@ int check_aggregate_args(int op, int64_t N, const int64_t* rowptr, const int32_t
 
 // ws == nullptr: no row is split.  Otherwise ws holds segs.ws_slots * F doubles.
 int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* edge_w,
-                   const void* X, int x_dtype, void* out, int out_dtype, int32_t F, int32_t f_chunk,
-                   const int32_t* row_order, const int64_t* class_off, double* ws, hipStream_t stream) {
+                   const void* X, int x_dtype, int64_t x_pitch, void* out, int out_dtype, int64_t out_pitch,
+                   int32_t F, int32_t f_chunk, const int32_t* row_order, const int64_t* class_off, double* ws,
+                   hipStream_t stream) {
   const size_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
   if (f_chunk == GNNAGG_F_CHUNK_AUTO) f_chunk = auto_f_chunk(N, F, (int)xs);
   std::vector<SliceLaunch> launches;
@@ -359,6 +361,8 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
     a.out_bf16 = (out_dtype == GNNAGG_BF16);
     a.order = row_order;
     a.F = F;
+    a.x_pitch = x_pitch;
+    a.out_pitch = out_pitch;
     a.N = N;
     a.sl = launches[k];
     a.mean = (op == GNNAGG_MEAN);
@@ -382,6 +386,7 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
     m.out = out;
     m.ws = ws;
     m.F = F;
+    m.out_pitch = out_pitch;
     m.out_bf16 = (out_dtype == GNNAGG_BF16);
     m.mean = (op == GNNAGG_MEAN);
     m.nrun = 0;
@@ -412,16 +417,20 @@ extern "C" int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const 
   int rc = check_aggregate_args(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, f_chunk, row_order,
                                 class_off, &nothing);
   if (rc != GNNAGG_OK || nothing) return rc;
-  return aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, f_chunk, row_order,
+  return aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, F, out, out_dtype, F, F, f_chunk, row_order,
                         class_off, nullptr, (hipStream_t)stream_);
 }
 
 extern "C" int gnnagg_aggregate_ws(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
-                                   const float* edge_w, const void* X, int x_dtype, void* out, int out_dtype,
-                                   int32_t F, int32_t f_chunk, const int32_t* row_order, const int64_t* class_off,
-                                   void* workspace, size_t* workspace_bytes, void* stream_) {
+                                   const float* edge_w, const void* X, int x_dtype, int64_t x_pitch, void* out,
+                                   int out_dtype, int64_t out_pitch, int32_t F, int32_t f_chunk,
+                                   const int32_t* row_order, const int64_t* class_off, void* workspace,
+                                   size_t* workspace_bytes, void* stream_) {
   if (!workspace_bytes) return GNNAGG_ENULL;
   if (N < 0 || F <= 0) return GNNAGG_EINVAL;
+  if (x_pitch == 0) x_pitch = F;
+  if (out_pitch == 0) out_pitch = F;
+  if (x_pitch < F || out_pitch < F || x_pitch > (1ll << 40) || out_pitch > (1ll << 40)) return GNNAGG_EINVAL;
   if ((row_order == nullptr) != (class_off == nullptr)) return GNNAGG_EINVAL;
   if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
   SegTable probe;
@@ -437,8 +446,22 @@ extern "C" int gnnagg_aggregate_ws(int op, int64_t N, const int64_t* rowptr, con
   rc = check_aggregate_args(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, f_chunk, row_order,
                             class_off, &nothing);
   if (rc != GNNAGG_OK || nothing) return rc;
-  return aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, f_chunk, row_order,
-                        class_off, need > 0 ? static_cast<double*>(workspace) : nullptr, (hipStream_t)stream_);
+  return aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, x_pitch, out, out_dtype, out_pitch, F, f_chunk,
+                        row_order, class_off, need > 0 ? static_cast<double*>(workspace) : nullptr,
+                        (hipStream_t)stream_);
+}
+
+extern "C" int64_t gnnagg_row_pitch(int32_t F, int dtype) {
+  if (F <= 0 || (dtype != GNNAGG_F32 && dtype != GNNAGG_BF16)) return 0;
+  const int64_t elem = (dtype == GNNAGG_F32) ? 4 : 2, bytes = (int64_t)F * elem;
+  int64_t padded;
+  if (bytes <= 128) {
+    padded = elem;
+    while (padded < bytes) padded *= 2;  // a power-of-two fraction of a line never straddles one
+  } else {
+    padded = ceil_div(bytes, 128) * 128;
+  }
+  return padded / elem;
 }
 
 extern "C" int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype) {

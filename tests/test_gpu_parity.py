@@ -583,3 +583,44 @@ def test_attention_rows_split_over_workgroups_match_the_checker(heads, C, fc):
     sums = host(alpha).astype(np.float64)
     seg = np.add.reduceat(sums, rp[:-1][np.diff(rp) > 0], axis=0)
     assert np.allclose(seg, 1.0, atol=1e-5)
+
+
+@pytest.mark.parametrize("F,bf16,fc", [(100, True, 0), (602, False, 0), (33, False, 8), (5, True, 0), (130, False, 64)])
+def test_row_pitched_input_and_output(F, bf16, fc):
+    """X and out as [N, F] views into allocations whose rows start on 128-byte lines: same results as the
+    contiguous call; the padding columns are never read (they hold NaN) and never written."""
+    N, src, dst = W.graph("c5", 0.004)
+    long_s, long_d = long_rows_graph(N, [40000], seed=F)   # one row long enough to be split as well
+    src, dst = np.concatenate([src, long_s]), np.concatenate([dst, long_d])
+    rp, ci, _, _ = oracle.build_csr(N, src, dst)
+    w = W.normal_f32((len(ci),), seed=12)
+    X = W.normal_bf16((N, F), seed=800 + F) if bf16 else W.normal_f32((N, F), seed=800 + F)
+    dt = torch.bfloat16 if bf16 else torch.float32
+    pitch = g.gnnagg_row_pitch(F, dt)
+    row_bytes = pitch * (2 if bf16 else 4)
+    assert pitch >= F and (row_bytes % 128 == 0 or (row_bytes < 128 and row_bytes & (row_bytes - 1) == 0))
+    Xp = g.pitched_empty(N, F, dt)
+    assert Xp.stride(0) == pitch
+    Xp.untyped_storage().fill_(0xFF)  # all-ones bit patterns: NaN in both types
+    Xp.copy_(dev(X))
+    d_rp, d_ci, d_w = dev(rp), dev(ci), dev(w)
+    plan = g.gnnagg_plan_rows(d_rp)
+    for name in ("sum", "wsum", "mean", "max"):
+        gop, rop = OPS[name]
+        ref = oracle.aggregate(rop, rp, ci, w, X, threads=8)
+        out = g.pitched_empty(N, F, torch.float32)
+        base = torch.full((N, out.stride(0)), -7.0, dtype=torch.float32, device="cuda")
+        out = base[:, :F]
+        g.gnnagg_aggregate(gop, d_rp, d_ci, d_w if name == "wsum" else None, Xp, out, fc, plan)
+        got = host(out)
+        if name == "max":
+            assert_bits(got, ref, "pitched max")
+        else:
+            assert_close(got, ref, bf16, "pitched " + name)
+        assert bool((base[:, F:] == -7.0).all()), "padding columns were written"
+        # a pitched input with a contiguous output, and the other way round
+        flat = g.gnnagg_aggregate(gop, d_rp, d_ci, d_w if name == "wsum" else None, Xp, None, fc, plan)
+        assert np.array_equal(host(flat).view(np.uint32), got.view(np.uint32))
+        out2 = torch.full((N, out.stride(0)), -7.0, dtype=torch.float32, device="cuda")[:, :F]
+        g.gnnagg_aggregate(gop, d_rp, d_ci, d_w if name == "wsum" else None, dev(X), out2, fc, plan)
+        assert np.array_equal(host(out2).view(np.uint32), got.view(np.uint32))

@@ -103,17 +103,26 @@ def test_argument_validation_returns_before_any_launch(lib):
         off[k + 1] = off[k] + rows[k]
     offp = ctypes.cast(off, ctypes.c_void_p)
     need = ctypes.c_size_t(77)
-    assert aggws(0, 100, one, one, one, one, 0, other_ptr(), 0, 8, 0, one, offp, None, None, None) == ENULL
-    assert aggws(0, 100, None, None, None, None, 0, None, 0, 8, 0, one, offp, None, ctypes.byref(need), None) == 0
+    assert aggws(0, 100, one, one, one, one, 0, 0, other_ptr(), 0, 0, 8, 0, one, offp, None, None, None) == ENULL
+    assert aggws(0, 100, None, None, None, None, 0, 0, None, 0, 0, 8, 0, one, offp, None, ctypes.byref(need), None) == 0
     assert need.value == (2 * 8 + 16) * 8 * 8          # slots x F x sizeof(double)
-    assert aggws(0, 100, None, None, None, None, 0, None, 0, 8, 0, None, None, None, ctypes.byref(need), None) == 0
+    assert aggws(0, 100, None, None, None, None, 0, 0, None, 0, 0, 8, 0, None, None, None, ctypes.byref(need), None) == 0
     assert need.value == 0                               # no plan: nothing is split
     small = ctypes.c_size_t(64)
-    assert aggws(0, 100, one, one, one, one, 0, other_ptr(), 0, 8, 0, one, offp, one, ctypes.byref(small), None) == EWS
+    assert aggws(0, 100, one, one, one, one, 0, 0, other_ptr(), 0, 0, 8, 0, one, offp, one, ctypes.byref(small), None) == EWS
     big = ctypes.c_size_t(1 << 20)
-    assert aggws(0, 100, one, one, one, one, 0, other_ptr(), 0, 8, 0, one, offp, ctypes.c_void_p(4100),
+    assert aggws(0, 100, one, one, one, one, 0, 0, other_ptr(), 0, 0, 8, 0, one, offp, ctypes.c_void_p(4100),
                  ctypes.byref(big), None) == EWS        # misaligned
-    assert aggws(9, 100, one, one, one, one, 0, other_ptr(), 0, 8, 0, one, offp, one, ctypes.byref(big), None) == EINVAL
+    assert aggws(9, 100, one, one, one, one, 0, 0, other_ptr(), 0, 0, 8, 0, one, offp, one, ctypes.byref(big),
+                 None) == EINVAL
+    assert aggws(0, 100, one, one, one, one, 0, 7, other_ptr(), 0, 0, 8, 0, one, offp, one, ctypes.byref(big),
+                 None) == EINVAL                        # a pitch below F
+    assert aggws(0, 100, one, one, one, one, 0, 0, other_ptr(), 0, 5, 8, 0, one, offp, one, ctypes.byref(big),
+                 None) == EINVAL
+    pitch = lib.gnnagg_row_pitch
+    assert [pitch(100, 1), pitch(602, 0), pitch(32, 0), pitch(16, 1), pitch(33, 0), pitch(3, 0), pitch(50, 1),
+            pitch(64, 1), pitch(1, 1)] == [128, 608, 32, 16, 64, 4, 64, 64, 1]
+    assert pitch(0, 0) == 0 and pitch(8, 7) == 0
 
     comb = lib.gnnagg_combine
     other = ctypes.c_void_p(8192)

@@ -135,8 +135,10 @@ inline int pow2_ceil_log2(int64_t x) {
 // Cuts [0,F) into chunks of width f_chunk (0 or >= F: one chunk) and every
 // chunk into slices of at most 64 lanes x vec columns.  max_vec is the widest
 // per-lane vector (16 bytes of input); vec_multiple forces vec to divide it
-// (attention: a lane must stay inside one head) or is 0.
-inline void plan_columns(int32_t F, int32_t f_chunk, int max_vec, int vec_multiple,
+// (attention: a lane must stay inside one head) or is 0; line_cols is the number
+// of columns in a 128-byte line if every row of the input starts on a line
+// boundary, else 0.
+inline void plan_columns(int32_t F, int32_t f_chunk, int max_vec, int vec_multiple, int line_cols,
                          std::vector<SliceLaunch>* out) {
   out->clear();
   const int32_t width = (f_chunk <= 0 || f_chunk >= F) ? F : f_chunk;
@@ -152,6 +154,12 @@ inline void plan_columns(int32_t F, int32_t f_chunk, int max_vec, int vec_multip
     const int32_t cap = kWave * vec;
     int32_t n_sub = (int32_t)ceil_div(gr.chunk_w, cap);
     int32_t sub_w = (int32_t)(ceil_div(ceil_div(gr.chunk_w, n_sub), vec) * vec);
+    if (line_cols > 0 && n_sub > 1 && gr.c_begin % line_cols == 0 && (gr.n_chunks == 1 || width % line_cols == 0)) {
+      // rows start on 128-byte lines: cut the slices at line boundaries too, so that no line is fetched
+      // by two slice passes (F=602 fp32: 224/224/154 columns = 7+7+5 lines instead of 3 x 7)
+      const int32_t al = (int32_t)(ceil_div(ceil_div(gr.chunk_w, n_sub), line_cols) * line_cols);
+      if (al <= cap && al % vec == 0 && gr.chunk_w - (n_sub - 1) * al >= vec) sub_w = al;
+    }
     int32_t last = gr.chunk_w - (n_sub - 1) * sub_w;
     if (last < vec) {  // balanced cut left a sliver: use full-width slices instead
       sub_w = cap;

@@ -7,7 +7,7 @@
 // long degree classes are split into pieces: then (5) such a row has no writer into the output, its
 // 2^split pieces each cover every column in a workspace slot of their own, and slots are unique.
 //
-// usage: schedule_check F f_chunk max_vec vec_multiple N use_plan [class counts ...]
+// usage: schedule_check F f_chunk max_vec vec_multiple[:line_cols] N use_plan [class counts ...]
 //        (use_plan: 0 none, 1 plan, 2 plan with split rows; class counts: rows in class 32, 31, ..., 0;
 //        must add up to N)
 #include <cstdio>
@@ -23,6 +23,9 @@ int main(int argc, char** argv) {
   if (argc < 7) return 2;
   const int32_t F = atoi(argv[1]), f_chunk = atoi(argv[2]);
   const int max_vec = atoi(argv[3]), vec_multiple = atoi(argv[4]);
+  int line_cols = 0;
+  for (const char* c = argv[4]; *c; ++c)
+    if (*c == ':') line_cols = atoi(c + 1);
   const int64_t N = atoll(argv[5]);
   const int use_plan = atoi(argv[6]);
   int64_t class_off[GNNAGG_PLAN_CLASSES + 1];
@@ -33,7 +36,15 @@ int main(int argc, char** argv) {
     if (class_off[GNNAGG_PLAN_CLASSES] != N) { printf("FAIL class counts do not add up\n"); return 1; }
   }
   std::vector<SliceLaunch> launches;
-  plan_columns(F, f_chunk, max_vec, vec_multiple, &launches);
+  plan_columns(F, f_chunk, max_vec, vec_multiple, line_cols, &launches);
+  if (line_cols)
+    for (const SliceLaunch& sl : launches)
+      if (sl.n_sub > 1 && sl.c_begin % line_cols == 0 && (sl.n_chunks == 1 || sl.chunk_stride % line_cols == 0) &&
+          sl.sub_w % line_cols) {
+        // not an error in itself (the aligned width may not fit), but the cases this test passes all fit
+        printf("FAIL slices of %d columns do not end on lines of %d\n", sl.sub_w, line_cols);
+        return 1;
+      }
   std::vector<int> writers((size_t)N * F, 0);
   std::vector<char> is_split((size_t)N, 0);
   std::map<int32_t, std::pair<int64_t, int>> slot_owner;   // workspace slot -> (row, piece)

@@ -189,6 +189,15 @@ def test_geometry_with_degree_classes(checker, F, f_chunk, max_vec):
     run_checker(checker, F, f_chunk, max_vec, 0, N, cc)
 
 
+@pytest.mark.parametrize("F,f_chunk,max_vec,line_cols", [(602, 0, 4, 32), (1433, 0, 4, 32), (1000, 0, 8, 64), (2051, 0, 8, 64),
+                                                         (602, 256, 4, 32), (100, 0, 8, 64), (257, 0, 4, 32)])
+def test_geometry_with_line_aligned_slices(checker, F, f_chunk, max_vec, line_cols):
+    """When rows start on 128-byte lines the slices of a wide chunk end on line boundaries; coverage as before."""
+    N = 150
+    cc = counts(N, {0: 4, 2: 30, 4: 20, 6: 10, 9: 4, 13: 2})
+    run_checker(checker, F, f_chunk, max_vec, "0:%d" % line_cols, N, cc)
+
+
 @pytest.mark.parametrize("F,f_chunk,max_vec", [(602, 0, 4), (100, 0, 8), (16, 0, 8), (9, 4, 4), (1030, 64, 4)])
 def test_geometry_with_split_rows(checker, F, f_chunk, max_vec):
     """Rows of 2^15 edges or more are cut into pieces when a workspace is available: every piece covers all

@@ -368,7 +368,8 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
     a.sl = launches[k];
     a.mean = (op == GNNAGG_MEAN);
     a.ws = ws;
-    a.lds_per_workgroup = lds_claim(resident_workgroup_cap(class_off, N, a.sl.g_log2));
+    a.lds_per_workgroup =
+        lds_claim(resident_workgroup_cap(class_off, N, a.sl.g_log2, active_lanes_per_wave(a.sl), opk == OPK_WSUM));
     int rc = build_segments(class_off, N, a.sl.g_log2, ws != nullptr, &a.segs);
     if (rc != GNNAGG_OK) return rc;
     grids[k] = (uint64_t)a.segs.blocks_per_slice * (uint64_t)a.sl.n_chunks * (uint64_t)a.sl.n_sub;

@@ -275,12 +275,19 @@ inline int32_t auto_f_chunk(int64_t N, int32_t F, int elem_bytes) {
 // in flight alone (256 CUs x 16-20 waves x 8 x ~7 lines x 128 B = ~30 MB) are as large as the whole L2
 // (8 x 4 MB), so nothing that was fetched stays long enough to serve a second destination.  On dense
 // graphs, where a row of X is gathered hundreds of times, fewer resident waves mean more L2 hits and
-// a shorter run (measured on MI355X, 64-lane slices: 2 workgroups per CU are 30 % faster than 4-5 at
-// mean degree ~490, 3 are 5-17 % faster at mean degree 128-256); on sparse graphs and narrow slices
-// the parallelism is worth more.  The mean degree is estimated from the plan's degree classes.
-// Returns 0 for "no cap".
-inline int resident_workgroup_cap(const int64_t* class_off, int64_t N, int g_log2) {
-  if (!class_off || N <= 0 || g_log2 < 4) return 0;
+// a shorter run; on sparse graphs and narrow slices the parallelism is worth more.
+//
+// What the sweeps on MI355X show (dense graphs, mean degree 190-600, 128 to 602 fp32 / 200 to 512 bf16
+// columns, caps 2-5 and none) is an optimum in BYTES IN FLIGHT PER COMPUTE UNIT: a workgroup has
+// 4 waves x 8 loads x (active lanes per wave) x 16 B in flight, and the best cap is the one that
+// brings cap x that to about 56 KB for the weighted sum (whose loop also streams the edge weights)
+// and about 78 KB for sum / mean / max.  64 active lanes: 2 and 2; 56: 2 and 3; 48: 2 and 3; 39: 3 and 4
+// - each the measured best, by 5-25 % over its neighbours.  Slices of at most 16 lanes (wide mode with
+// four or more rows per wave) ran best uncapped.  The mean degree is estimated from the plan's degree
+// classes; active_lanes is the launch's average over its slices.  Returns 0 for "no cap".
+inline int resident_workgroup_cap(const int64_t* class_off, int64_t N, int g_log2, int active_lanes,
+                                  bool weighted) {
+  if (!class_off || N <= 0 || g_log2 < 5 || active_lanes <= 0) return 0;
   double edges = 0.0;
   for (int k = 0; k < GNNAGG_PLAN_CLASSES; ++k) {
     const int c = 32 - k;  // rows with 2^(c-1) <= degree < 2^c
@@ -289,10 +296,19 @@ inline int resident_workgroup_cap(const int64_t* class_off, int64_t N, int g_log
     edges += mid * (double)(class_off[k + 1] - class_off[k]);
   }
   const double mean_degree = edges / (double)N;
-  if (g_log2 < 6) return mean_degree >= 384.0 ? 3 : 0;  // 16/32-lane slices: smaller effect (~10 % at ~490)
-  if (mean_degree >= 384.0) return 2;
-  if (mean_degree >= 96.0) return 3;
-  return 0;
+  if (mean_degree < (g_log2 == 6 ? 96.0 : 384.0)) return 0;
+  const double target = (g_log2 == 6 && weighted) ? 56.0 * 1024.0 : 78.0 * 1024.0;
+  const double per_workgroup = (double)kWavesPerBlock * 8.0 * (double)active_lanes * 16.0;
+  int cap = (int)(target / per_workgroup + 0.5);
+  return cap < 2 ? 2 : (cap > 4 ? 4 : cap);
+}
+
+// Active lanes per wave of a launch, averaged over its slices: lanes that own columns, times the rows a
+// wave holds side by side when a slice is narrower than the wave.
+inline int active_lanes_per_wave(const SliceLaunch& sl) {
+  const int64_t lanes_per_chunk = ceil_div(sl.chunk_w, sl.vec);
+  const int per_slice = (int)ceil_div(lanes_per_chunk, sl.n_sub);  // <= 2^g_log2
+  return per_slice << (6 - sl.g_log2);
 }
 
 // LDS a workgroup has to occupy so that exactly `cap` workgroups fit in the 160 KB of a gfx950

@@ -229,26 +229,34 @@ def cap_checker(tmp_path_factory):
     return exe
 
 
-def run_cap(exe, g, N, spread):
-    out = subprocess.run([exe, str(g), str(N)] + [str(c) for c in counts(N, spread)], capture_output=True, text=True)
+def run_cap(exe, g, lanes, weighted, N, spread):
+    out = subprocess.run([exe, str(g), str(lanes), str(int(weighted)), str(N)] + [str(c) for c in counts(N, spread)],
+                         capture_output=True, text=True)
     assert out.returncode == 0, out.stderr
     return [int(t) for t in out.stdout.split()]
 
 
-def test_workgroup_cap_follows_mean_degree(cap_checker):
+def test_workgroup_cap_follows_degree_and_bytes_in_flight(cap_checker):
     N = 1000
     dense = {10: 600, 9: 300, 8: 100}        # degrees 128..1023: mean ~ 580
     medium = {8: 700, 7: 300}                # degrees 64..255: mean ~ 160
     sparse = {3: 500, 2: 300, 5: 100}        # single digits
-    cap, claim, noplan = run_cap(cap_checker, 6, N, dense)
+    cap, claim, noplan = run_cap(cap_checker, 6, 64, True, N, dense)
     assert cap == 2 and noplan == 0
     # exactly `cap` workgroups fit into 160 KB of LDS
     assert cap * claim <= 160 * 1024 < (cap + 1) * claim
-    cap, claim, _ = run_cap(cap_checker, 6, N, medium)
-    assert cap == 3 and cap * claim <= 160 * 1024 < (cap + 1) * claim
-    assert run_cap(cap_checker, 6, N, sparse)[:2] == [0, 0]
-    assert run_cap(cap_checker, 5, N, dense)[0] == 3 and run_cap(cap_checker, 5, N, medium)[0] == 0
-    assert run_cap(cap_checker, 2, N, dense)[0] == 0   # narrow slices are never capped
+    # the measured optima: (active lanes, weighted) -> cap
+    for lanes, weighted, want in [(64, False, 2), (56, True, 2), (56, False, 3), (48, True, 2), (48, False, 3),
+                                  (39, True, 3), (39, False, 4), (50, True, 2), (50, False, 3)]:
+        cap, claim, _ = run_cap(cap_checker, 6, lanes, weighted, N, dense)
+        assert cap == want, (lanes, weighted, cap)
+        assert cap * claim <= 160 * 1024 < (cap + 1) * claim
+    assert run_cap(cap_checker, 6, 64, True, N, medium)[0] == 2
+    assert run_cap(cap_checker, 6, 64, True, N, sparse)[:2] == [0, 0]
+    assert run_cap(cap_checker, 5, 64, True, N, dense)[0] == 2 and run_cap(cap_checker, 5, 50, True, N, dense)[0] == 3
+    assert run_cap(cap_checker, 5, 64, True, N, medium)[0] == 0
+    assert run_cap(cap_checker, 4, 64, True, N, dense)[0] == 0   # slices of 16 lanes or fewer are never capped
+    assert run_cap(cap_checker, 2, 64, False, N, dense)[0] == 0
 
 
 def test_auto_chunk_width(lib):

@@ -26,14 +26,15 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0
 MFMA_F64_PEAK_TFLOPS = 78.6
 
-# HBM-side bytes per aggregation launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, scaled on the copy
+# HBM-side bytes per aggregation call (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, summed over the call's
+# launches - a narrower last slice gets a launch of its own on dense graphs - and scaled on the copy
 # probe: see profiles/aggregate_kernel_*.txt), valid for the kernels as committed with those profiles and
 # for f_chunk = 0 only.  Set an entry to None when the kernel changes until the counters are taken again.
 MEASURED_TRAFFIC = {
-    "c4-gcn": 152.632e9,  # profiles/aggregate_kernel_c4_gcn.txt
-    "c5-sum": 13.321e9,   # profiles/aggregate_kernel_c5_sum_bf16.txt
+    "c4-gcn": 152.953e9,  # profiles/aggregate_kernel_c4_gcn.txt
+    "c5-sum": 13.316e9,   # profiles/aggregate_kernel_c5_sum_bf16.txt
     "c4-gat": 14.677e9,   # profiles/gat_aggregate_kernel_c4_gat.txt
-    "c4-hid32-gcn": 6.448e9,  # profiles/aggregate_kernel_c4_hidden32_gcn.txt
+    "c4-hid32-gcn": 6.483e9,  # profiles/aggregate_kernel_c4_hidden32_gcn.txt
 }
 
 WORKLOADS = {
@@ -281,6 +282,7 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic,
                      "kernel": "gat_aggregate_kernel (+ score pass)" if gat else "aggregate_kernel",
+                     "per": "library call (all its launches of that kernel; kernel_ms is their sum)",
                      "kernel_ms": kern_ms, "kernel_ms_median": float(np.median(ms)), "kernel_ms_min": float(ms.min()),
                      "algorithmic_bytes": b_alg,
                      "hbm_gbs": (traffic / (kern_ms * 1e-3) / 1e9) if traffic else None,

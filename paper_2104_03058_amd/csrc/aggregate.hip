@@ -346,7 +346,8 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
   if (f_chunk == GNNAGG_F_CHUNK_AUTO) f_chunk = auto_f_chunk(N, F, (int)xs);
   std::vector<SliceLaunch> launches;
   const bool rows_on_lines = ((uintptr_t)X % 128) == 0 && ((uint64_t)x_pitch * xs) % 128 == 0;
-  plan_columns(F, f_chunk, (int)(16 / xs), 0, rows_on_lines ? (int)(128 / xs) : 0, &launches);
+  const bool capped = resident_workgroup_cap(class_off, N, 6, kWave, true) > 0;  // dense graph: caps in play
+  plan_columns(F, f_chunk, (int)(16 / xs), 0, rows_on_lines ? (int)(128 / xs) : 0, capped, &launches);
   const int opk = (op == GNNAGG_WSUM) ? OPK_WSUM : (op == GNNAGG_MAX ? OPK_MAX : OPK_SUM);
 
   // build and validate every launch before the first one is enqueued

@@ -434,7 +434,7 @@ extern "C" int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
   if (out == H) return GNNAGG_EINVAL;
 
   std::vector<SliceLaunch> launches;
-  plan_columns(F, f_chunk, 4, C, 0, &launches);
+  plan_columns(F, f_chunk, 4, C, 0, false, &launches);
   std::vector<GatArgs> args(launches.size());
   std::vector<uint64_t> grids(launches.size());
   for (size_t k = 0; k < launches.size(); ++k) {

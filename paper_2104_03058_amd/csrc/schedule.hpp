@@ -137,9 +137,10 @@ inline int pow2_ceil_log2(int64_t x) {
 // per-lane vector (16 bytes of input); vec_multiple forces vec to divide it
 // (attention: a lane must stay inside one head) or is 0; line_cols is the number
 // of columns in a 128-byte line if every row of the input starts on a line
-// boundary, else 0.
+// boundary, else 0; tail_launch asks for a separate launch for a narrower last
+// slice (worth its launch only where the resident-workgroup cap is in play).
 inline void plan_columns(int32_t F, int32_t f_chunk, int max_vec, int vec_multiple, int line_cols,
-                         std::vector<SliceLaunch>* out) {
+                         bool tail_launch, std::vector<SliceLaunch>* out) {
   out->clear();
   const int32_t width = (f_chunk <= 0 || f_chunk >= F) ? F : f_chunk;
   struct Group { int32_t c_begin, n_chunks, chunk_w; };
@@ -182,6 +183,21 @@ inline void plan_columns(int32_t F, int32_t f_chunk, int max_vec, int vec_multip
     sl.n_sub = n_sub;
     sl.vec = vec;
     sl.g_log2 = pow2_ceil_log2(ceil_div(sub_w, vec));
+    if (tail_launch && sl.n_sub > 1 && sl.n_chunks == 1 && last < sub_w) {
+      // the narrower last slice gets a launch of its own, after the others: its waves have fewer active
+      // lanes, so its best number of resident workgroups differs (resident_workgroup_cap)
+      SliceLaunch tail = sl;
+      sl.chunk_w = (n_sub - 1) * sub_w;
+      sl.n_sub = n_sub - 1;
+      tail.c_begin = sl.c_begin + sl.chunk_w;
+      tail.chunk_w = last;
+      tail.sub_w = last;
+      tail.n_sub = 1;
+      tail.g_log2 = pow2_ceil_log2(ceil_div(last, vec));
+      out->push_back(sl);
+      out->push_back(tail);
+      continue;
+    }
     out->push_back(sl);
   }
 }

@@ -36,7 +36,7 @@ int main(int argc, char** argv) {
     if (class_off[GNNAGG_PLAN_CLASSES] != N) { printf("FAIL class counts do not add up\n"); return 1; }
   }
   std::vector<SliceLaunch> launches;
-  plan_columns(F, f_chunk, max_vec, vec_multiple, line_cols, &launches);
+  plan_columns(F, f_chunk, max_vec, vec_multiple, line_cols, use_plan != 0, &launches);
   if (line_cols)
     for (const SliceLaunch& sl : launches)
       if (sl.n_sub > 1 && sl.c_begin % line_cols == 0 && (sl.n_chunks == 1 || sl.chunk_stride % line_cols == 0) &&

@@ -189,7 +189,7 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
         ws = torch.empty(g.gnnagg_gat_workspace_bytes(N, heads, C, plan), dtype=torch.uint8, device="cuda")
 
         def step():
-            g.gnnagg_gat_attention(d_rp, d_ci, d_H, d_as, d_ad, 0.2, False, True, f_chunk, plan, out=out3,
+            g.gnnagg_gat_attention(d_rp, d_ci, d_H, d_as, d_ad, 0.2, False, True, max(f_chunk, 0), plan, out=out3,
                                    workspace=ws)
     else:
         op = {"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname]
@@ -218,7 +218,8 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
         per_edge_score = 0 if C in (4, 8, 16) else heads * 4
         b_alg = nnz * (F * 4 + per_edge_score + 4) + 2 * N * F * 4 + 2 * N * heads * 4 * 2 + (N + 1) * 8
     else:
-        f_eff = g.gnnagg_auto_f_chunk(N, F, g.BF16 if xdt == "bf16" else g.F32) if f_chunk == -1 else f_chunk
+        f_eff = (g.gnnagg_auto_f_chunk(N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)), plan)
+                 if f_chunk == -1 else f_chunk)
         b_alg = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", f_eff)
     kern_ms = float(ms.mean())
     achieved = b_alg / (kern_ms * 1e-3) / 1e9
@@ -226,7 +227,7 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
     compulsory = N * F * x_bytes + N * F * 4 + nnz * (8 if opname == "wsum" else 4) + (N + 1) * 8
     if gat:
         compulsory += 2 * N * heads * 4
-    traffic = MEASURED_TRAFFIC.get(workload) if (f_chunk == 0 and pitched) else None  # taken in that layout
+    traffic = MEASURED_TRAFFIC.get(workload) if (f_chunk == -1 and pitched) else None  # taken in the default set-up
     log("step %.3f ms wall, kernel mean %.3f ms (min %.3f), %.3e edge-features/s, %.0f GB/s algorithmic" %
         (ms_per_step, kern_ms, ms.min(), edge_features / (ms_per_step * 1e-3), achieved))
 
@@ -276,7 +277,7 @@ def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_sec
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": workload, "graph": W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "op": opname,
-                   "f_chunk": f_chunk, "x_dtype": xdt, "x_row_pitch": int(d_X.stride(0)),
+                   "f_chunk": f_chunk, "f_chunk_used": (F if gat else (f_eff if 0 < f_eff < F else F)), "x_dtype": xdt, "x_row_pitch": int(d_X.stride(0)),
                    "out_row_pitch": int(out.stride(0))},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
@@ -326,7 +327,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c4-gcn", choices=sorted(WORKLOADS) + ["copy"],
                     help="'copy' runs only the library's plain copy kernel on 1 GiB (profiler calibration)")
-    ap.add_argument("--f-chunk", type=int, default=0, help="chunk width; 0 = one chunk, -1 = let the library pick")
+    ap.add_argument("--f-chunk", type=int, default=-1,
+                    help="chunk width; -1 = let the library pick (GNNAGG_F_CHUNK_AUTO, the default), 0 = one chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--also", default="c5-sum",
@@ -374,7 +376,7 @@ def main():
                   args.cpu_seconds, copy_gbs, not args.contiguous)
     also = []
     for wl in [w for w in args.also.split(",") if w and w != args.workload]:
-        r = measure(g, W, torch, wl, 0, args.steps, args.warmup, False, 0.0, copy_gbs, not args.contiguous)
+        r = measure(g, W, torch, wl, args.f_chunk, args.steps, args.warmup, False, 0.0, copy_gbs, not args.contiguous)
         also.append({k: r[k] for k in ("value", "unit", "ms_per_step", "config", "roofline", "setup")})
     rec["also"] = also
     if args.cpu_chunk_sweep:

@@ -127,11 +127,13 @@ GNNAGG_API int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
  *            Chunks run one after another over all rows (the chunk-outer,
  *            vertex-inner order of Algorithm 1), each written in place into its
  *            columns of `out` (no separate concat).  0 or >= F: one chunk.
- *            GNNAGG_F_CHUNK_AUTO: the library picks - one chunk while X is at most a few
- *            times the 256 MB Infinity Cache, otherwise the width whose column slice of
- *            X is about that size (Section II-B ties the number of layers to the memory
- *            capacity of the device), never narrower than
- *            128 bytes per row.  gnnagg_auto_f_chunk returns that choice.
+ *            GNNAGG_F_CHUNK_AUTO: the library picks (Section II-B ties the number of layers to the
+ *            memory capacity of the device and the character of the dataset): chunks of one
+ *            128-byte line when the rows of X start on lines (see gnnagg_aggregate_ws), X is fp32 and
+ *            the plan shows a dense graph whose longest rows hold a large share of the edges; a
+ *            power-of-two width whose column slice of X is a few hundred MB once X is beyond 1 GiB
+ *            (never narrower than 128 bytes per row); otherwise one chunk.  gnnagg_auto_f_chunk
+ *            returns that choice.
  *   row_order, class_off   a plan from gnnagg_plan_rows for this rowptr, or both
  *            NULL (rows then run in natural order, one wavefront per row slice:
  *            correct for any graph, slow on hub rows).  class_off is a HOST
@@ -177,8 +179,10 @@ GNNAGG_API int gnnagg_aggregate_ws(int op, int64_t N, const int64_t* rowptr, con
  * 0 for invalid arguments). */
 GNNAGG_API int64_t gnnagg_row_pitch(int32_t F, int dtype);
 
-/* The chunk width gnnagg_aggregate uses for GNNAGG_F_CHUNK_AUTO (host-side arithmetic only). */
-GNNAGG_API int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype);
+/* The chunk width the aggregation calls use for GNNAGG_F_CHUNK_AUTO (host-side arithmetic only) for an
+ * X of row pitch x_pitch (0 = F) whose first row starts on a 128-byte line, and the plan's class_off
+ * (HOST pointer, or NULL for no plan).  0 for invalid arguments. */
+GNNAGG_API int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype, int64_t x_pitch, const int64_t* class_off);
 
 /*
  * Graph-attention aggregation (the GAT operator the paper evaluates in

@@ -65,7 +65,7 @@ def load_library():
         lib.gnnagg_gat_attention.argtypes = [i64, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp, i32, vp, vp, vp, szp,
                                              vp]
         lib.gnnagg_auto_f_chunk.restype = i32
-        lib.gnnagg_auto_f_chunk.argtypes = [i64, i32, ci]
+        lib.gnnagg_auto_f_chunk.argtypes = [i64, i32, ci, i64, vp]
         lib.gnnagg_combine.restype = ci
         lib.gnnagg_combine.argtypes = [i64, vp, ci, i32, vp, vp, i32, ci, vp, vp]
         lib.gnnagg_copy_probe.restype = ci
@@ -324,9 +324,11 @@ def gnnagg_copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None
     _check("gnnagg_copy_probe", load_library().gnnagg_copy_probe(_dev(dst), _dev(src), nbytes, _stream(stream)))
 
 
-def gnnagg_auto_f_chunk(N: int, F: int, x_dtype: int = F32) -> int:
-    """Chunk width the library uses for f_chunk = F_CHUNK_AUTO."""
-    return int(load_library().gnnagg_auto_f_chunk(N, F, x_dtype))
+def gnnagg_auto_f_chunk(N: int, F: int, x_dtype: int = F32, x_pitch: int = 0,
+                        plan: Optional[RowPlan] = None) -> int:
+    """Chunk width the library uses for f_chunk = F_CHUNK_AUTO on an X of that row pitch (0 = F) and plan."""
+    class_off = ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None
+    return int(load_library().gnnagg_auto_f_chunk(N, F, x_dtype, x_pitch, class_off))
 
 
 def gnnagg_combine(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor] = None, relu: bool = False,

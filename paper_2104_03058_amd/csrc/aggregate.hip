@@ -343,9 +343,9 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
                    int32_t F, int32_t f_chunk, const int32_t* row_order, const int64_t* class_off, double* ws,
                    hipStream_t stream) {
   const size_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
-  if (f_chunk == GNNAGG_F_CHUNK_AUTO) f_chunk = auto_f_chunk(N, F, (int)xs);
-  std::vector<SliceLaunch> launches;
   const bool rows_on_lines = ((uintptr_t)X % 128) == 0 && ((uint64_t)x_pitch * xs) % 128 == 0;
+  if (f_chunk == GNNAGG_F_CHUNK_AUTO) f_chunk = auto_f_chunk(N, F, (int)xs, rows_on_lines, class_off);
+  std::vector<SliceLaunch> launches;
   const bool capped = resident_workgroup_cap(class_off, N, 6, kWave, true) > 0;  // dense graph: caps in play
   plan_columns(F, f_chunk, (int)(16 / xs), 0, rows_on_lines ? (int)(128 / xs) : 0, capped, &launches);
   const int opk = (op == GNNAGG_WSUM) ? OPK_WSUM : (op == GNNAGG_MAX ? OPK_MAX : OPK_SUM);
@@ -467,7 +467,15 @@ extern "C" int64_t gnnagg_row_pitch(int32_t F, int dtype) {
   return padded / elem;
 }
 
-extern "C" int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype) {
+extern "C" int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype, int64_t x_pitch, const int64_t* class_off) {
   if (N < 0 || F <= 0 || (x_dtype != GNNAGG_F32 && x_dtype != GNNAGG_BF16)) return 0;
-  return auto_f_chunk(N, F, x_dtype == GNNAGG_F32 ? 4 : 2);
+  const int elem = x_dtype == GNNAGG_F32 ? 4 : 2;
+  if (x_pitch == 0) x_pitch = F;
+  if (x_pitch < F) return 0;
+  if (class_off) {
+    if (class_off[0] != 0 || class_off[GNNAGG_PLAN_CLASSES] != N) return 0;
+    for (int k = 0; k < GNNAGG_PLAN_CLASSES; ++k)
+      if (class_off[k] > class_off[k + 1]) return 0;
+  }
+  return auto_f_chunk(N, F, elem, ((uint64_t)x_pitch * (uint64_t)elem) % 128 == 0, class_off);
 }

@@ -271,19 +271,57 @@ inline int build_segments(const int64_t* class_off, int64_t N, int g_log2, bool 
   return GNNAGG_OK;
 }
 
-// Chunk width for GNNAGG_F_CHUNK_AUTO.  Measured on MI355X: while X is within a few times the 256 MB
-// Infinity Cache one chunk is fastest (config 4, X = 561 MB: 25 ms unchunked, 29 ms at 256 columns),
-// because every extra chunk pass re-reads the edge list; once X is several GB (2.4 M rows x 256-512
-// fp32 columns) chunks whose column slice of X is ~300-600 MB are 13-17 % faster than one chunk, and
-// row pieces under 128 bytes are twice slower than either.
-inline int32_t auto_f_chunk(int64_t N, int32_t F, int elem_bytes) {
+// Mean degree and the share of all edges that end in the `hot_rows` longest rows, both estimated from
+// the plan's degree classes (a row of class c counts as 1.5 * 2^(c-1) - 0.5 edges).
+inline void degree_profile(const int64_t* class_off, int64_t N, int64_t hot_rows, double* mean_degree,
+                           double* hot_share) {
+  double edges = 0.0, hot = 0.0;
+  int64_t left = hot_rows;
+  for (int k = 0; k < GNNAGG_PLAN_CLASSES; ++k) {  // classes 32 down to 0: longest rows first
+    const int c = 32 - k;
+    if (c == 0) continue;
+    const double mid = 1.5 * (double)(1ull << (c - 1)) - 0.5;
+    const int64_t rows = class_off[k + 1] - class_off[k];
+    edges += mid * (double)rows;
+    const int64_t take = rows < left ? rows : left;
+    hot += mid * (double)take;
+    left -= take;
+  }
+  *mean_degree = N > 0 ? edges / (double)N : 0.0;
+  *hot_share = edges > 0.0 ? hot / edges : 0.0;
+}
+
+// Chunk width for GNNAGG_F_CHUNK_AUTO: the paper leaves the number of layers to the memory capacity of
+// the device and the character of the dataset (Section II-B); on MI355X the measurements say
+//  (1) X beyond ~1 GiB (several times the 256 MB Infinity Cache; 2.4 M rows x 256-512 fp32 columns):
+//      chunks whose column slice of X is ~300-600 MB are 13-17 % faster than one chunk, row pieces under
+//      128 bytes twice slower than either -> power-of-two width with a ~384 MB slice, >= 128-byte pieces;
+//  (2) rows on 128-byte lines, fp32, at least four lines wide, a dense graph (mean degree >= 96) whose
+//      hubs matter - the 32,768 longest rows, as many as one 4 MB L2 holds lines of one chunk, take
+//      >= 40 % of the edges: chunks of exactly ONE LINE (32 columns) are 9-27 % faster than one chunk
+//      (power-law graphs of mean degree 490-600 and hot share 0.70-0.74, 128-602 columns), because a
+//      chunk pass then asks for one line per edge from a slice of N x 128 bytes in which the hubs' lines
+//      stay in L2.  Uniform graphs (hot share < 0.2) lose 3-9 % to the extra passes over the edge list,
+//      bf16 rows lose 20 % (a lane then accumulates 8 columns in fp64 per line: arithmetic-bound), and
+//      without line-aligned rows a 128-byte piece straddles two lines and the pass costs twice;
+//  (3) otherwise one chunk.
+inline int32_t auto_f_chunk(int64_t N, int32_t F, int elem_bytes, bool rows_on_lines, const int64_t* class_off) {
   const double x_bytes = (double)N * (double)F * (double)elem_bytes;
-  if (N <= 0 || x_bytes <= 1024.0 * 1024.0 * 1024.0) return F;
-  const int64_t min_w = 128 / elem_bytes;                                  // 128-byte row pieces
-  int64_t w = (int64_t)(384.0 * 1024.0 * 1024.0 / ((double)N * elem_bytes));  // ~384 MB column slice
-  int64_t p = min_w;
-  while (p * 2 <= w) p *= 2;  // a power of two keeps every chunk on full 16-byte lanes
-  return (int32_t)(p >= F ? F : p);
+  if (N <= 0) return F;
+  if (x_bytes > 1024.0 * 1024.0 * 1024.0) {
+    const int64_t min_w = 128 / elem_bytes;                                  // 128-byte row pieces
+    int64_t w = (int64_t)(384.0 * 1024.0 * 1024.0 / ((double)N * elem_bytes));  // ~384 MB column slice
+    int64_t p = min_w;
+    while (p * 2 <= w) p *= 2;  // a power of two keeps every chunk on full 16-byte lanes
+    return (int32_t)(p >= F ? F : p);
+  }
+  constexpr int64_t kLinesPerL2 = 4 * 1024 * 1024 / 128;
+  if (rows_on_lines && elem_bytes == 4 && F >= 128 && class_off && N > kLinesPerL2) {
+    double mean_degree, hot_share;
+    degree_profile(class_off, N, kLinesPerL2, &mean_degree, &hot_share);
+    if (mean_degree >= 96.0 && hot_share >= 0.4) return 32;
+  }
+  return F;
 }
 
 // How many workgroups of the aggregation kernel should share a compute unit.  Every resident wave

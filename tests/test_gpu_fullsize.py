@@ -46,6 +46,22 @@ def test_config4_full_size_gcn_and_mean():
         ref = oracle.aggregate_rows(oracle.WSUM, rows, rp, ci, w, X, threads=16)
         assert_close(got, ref, what="c4 wsum fc=%d" % fc)
         del out
+    # the benchmark's set-up: rows on 128-byte lines, the library picks the chunk width (one line here)
+    Xp = g.pitched_empty(N, 602, torch.float32)
+    Xp.copy_(d_X)
+    assert g.gnnagg_auto_f_chunk(N, 602, g.F32, int(Xp.stride(0)), plan) == 32
+    assert g.gnnagg_auto_f_chunk(N, 602, g.F32, 602, plan) == 602
+    for op, oop, ww, dw in ((g.WSUM, oracle.WSUM, w, d_w), (g.MEAN, oracle.MEAN, None, None), (g.MAX, oracle.MAX, None, None)):
+        say("c4 full: pitched rows, automatic chunk width, op", op)
+        out = g.gnnagg_aggregate(op, d_rp, d_ci, dw, Xp, g.pitched_empty(N, 602, torch.float32), g.F_CHUNK_AUTO, plan)
+        got = host(out[torch.from_numpy(rows).cuda()])
+        ref = oracle.aggregate_rows(oop, rows, rp, ci, ww, X, threads=16)
+        if op == g.MAX:
+            assert_bits(got, ref, "c4 max auto")
+        else:
+            assert_close(got, ref, what="c4 auto op %d" % op)
+        del out
+    del Xp
     say("c4 full: mean")
     out = g.gnnagg_aggregate(g.MEAN, d_rp, d_ci, None, d_X, None, 0, plan)
     got = host(out[torch.from_numpy(rows).cuda()])
@@ -137,7 +153,7 @@ def test_automatic_chunk_width_on_a_feature_matrix_beyond_the_cache():
     import paper_2104_03058_amd as g
     N, src, dst = W.graph("c5")
     F = 128
-    assert g.gnnagg_auto_f_chunk(N, F, g.F32) == 32
+    assert g.gnnagg_auto_f_chunk(N, F, g.F32) == 32  # 1.25 GB of X: the capacity rule
     rp, ci, _, _ = oracle.build_csr(N, src, dst, 0, threads=16)
     d_rp, d_ci = dev(rp), dev(ci)
     X = W.normal_f32((N, F), seed=60)

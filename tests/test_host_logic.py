@@ -261,12 +261,41 @@ def test_workgroup_cap_follows_degree_and_bytes_in_flight(cap_checker):
 
 def test_auto_chunk_width(lib):
     import paper_2104_03058_amd as g
-    assert g.gnnagg_auto_f_chunk(232965, 602, g.F32) == 602          # 561 MB: one chunk
+    assert g.gnnagg_auto_f_chunk(232965, 602, g.F32) == 602          # 561 MB, no plan: one chunk
     assert g.gnnagg_auto_f_chunk(2449029, 100, g.BF16) == 100        # 490 MB: one chunk
     assert g.gnnagg_auto_f_chunk(2449029, 512, g.F32) == 32          # 5 GB: ~300 MB column slices
     assert g.gnnagg_auto_f_chunk(2449029, 1024, g.BF16) == 64        # same bytes per row piece in bf16
     assert g.gnnagg_auto_f_chunk(50_000_000, 64, g.F32) == 32        # never under 128 bytes per row piece
     assert g.gnnagg_auto_f_chunk(10, 0, g.F32) == 0 and g.gnnagg_auto_f_chunk(10, 8, 7) == 0
+    assert g.gnnagg_auto_f_chunk(10, 8, g.F32, 4) == 0               # a pitch below F
+
+
+def plan_of(N, spread):
+    import paper_2104_03058_amd as g
+    off = (ctypes.c_int64 * 34)()
+    for k, rows in enumerate(counts(N, spread)):
+        off[k + 1] = off[k] + rows
+    return g.RowPlan(None, off)
+
+
+def test_auto_chunk_width_one_line_on_dense_skewed_graphs(lib):
+    """Line-aligned fp32 rows on a dense graph whose 32,768 longest rows hold much of the edges: chunks of one
+    128-byte line.  Any of the conditions missing: one chunk."""
+    import paper_2104_03058_amd as g
+    N = 232965
+    skewed = plan_of(N, {15: 60, 14: 700, 13: 4000, 12: 12000, 11: 25000, 10: 40000, 9: 50000, 8: 45000, 7: 30000,
+                         6: 15000, 5: 8000})                 # power-law shaped: mean ~ 500, long tail of hubs
+    flat = plan_of(N, {8: N})                                 # every row 128..255 edges
+    sparse = plan_of(N, {15: 5, 10: 1000, 5: 100000, 3: 100000})
+    assert g.gnnagg_auto_f_chunk(N, 602, g.F32, 608, skewed) == 32
+    assert g.gnnagg_auto_f_chunk(N, 256, g.F32, 256, skewed) == 32
+    assert g.gnnagg_auto_f_chunk(N, 602, g.F32, 602, skewed) == 602    # rows not on lines
+    assert g.gnnagg_auto_f_chunk(N, 602, g.F32, 608, None) == 602      # no plan
+    assert g.gnnagg_auto_f_chunk(N, 602, g.F32, 608, flat) == 602      # no hubs
+    assert g.gnnagg_auto_f_chunk(N, 602, g.F32, 608, sparse) == 602    # low mean degree
+    assert g.gnnagg_auto_f_chunk(N, 64, g.F32, 64, skewed) == 64       # narrower than four lines
+    assert g.gnnagg_auto_f_chunk(N, 512, g.BF16, 512, skewed) == 512   # bf16: arithmetic-bound at that width
+    assert g.gnnagg_auto_f_chunk(20000, 602, g.F32, 608, plan_of(20000, {12: 500, 9: 19500})) == 602  # fits one L2
 
 
 def test_bench_module_is_importable_and_its_workloads_name_known_graphs():

@@ -351,7 +351,7 @@ def main():
                          "on the whole graph of the workload at each width (0 = one chunk); minutes of CPU time")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+        sys.exit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
 
     import torch
     if not torch.cuda.is_available():

@@ -46,7 +46,7 @@ typedef enum {
   GNNAGG_OK = 0,
   GNNAGG_EINVAL = -1,       /* an argument is out of range or inconsistent */
   GNNAGG_ENULL = -2,        /* a required pointer is NULL */
-  GNNAGG_EUNSUPPORTED = -3, /* valid request this build does not implement */
+  GNNAGG_EUNSUPPORTED = -3, /* valid request the library does not implement */
   GNNAGG_EWORKSPACE = -4,   /* workspace missing, too small or misaligned */
   GNNAGG_EDEVICE = -5       /* a HIP call failed */
 } gnnagg_status;

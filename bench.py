@@ -61,6 +61,10 @@ WORKLOADS = {
     # Combination (dense layer F -> H on the matrix cores), alone and as one GCN layer with Combination first
     "c4-combine-32": ("c4", "combine", (602, 32), "f32", False),
     "c4-layer-32": ("c4", "layer", (602, 32), "f32", True),
+    # the sparse graph at hidden width 16 after Combination: rows of 64 bytes, two per line; "-ranked" stores
+    # the hidden rows in popularity order (gnnagg_rank_sources + out_rows of gnnagg_combine)
+    "c5-layer-16": ("c5", "layer", (100, 16), "f32", False),
+    "c5-layer-16-ranked": ("c5", "layer-ranked", (100, 16), "f32", False),
 }
 
 
@@ -96,16 +100,24 @@ def measure_layer(g, W, torch, workload, steps, warmup, copy_gbs):
     hid = torch.empty((N, H), dtype=torch.float32, device="cuda")
     out = torch.empty((N, H), dtype=torch.float32, device="cuda")
     nnz = 0
+    ranked = opname == "layer-ranked"
+    rank = None
+    if ranked:
+        opname = "layer"
     if opname == "layer":
+        flags = (g.SELF_LOOPS | g.NORM_SYM) if gcn else 0
         d_rp, d_ci, d_w, _ = g.gnnagg_build_csr(N, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda(),
-                                                g.SELF_LOOPS | g.NORM_SYM, want_w=True)
+                                                flags, want_w=gcn)
         plan = g.gnnagg_plan_rows(d_rp)
         nnz = int(d_ci.shape[0])
+        if ranked:  # per graph, like the CSR and the plan
+            rank, d_ci = g.gnnagg_rank_sources(N, d_ci)
+    aop = g.WSUM if gcn else g.SUM
 
     def step():
-        g.gnnagg_combine(X, Wt, None, False, hid)
+        g.gnnagg_combine(X, Wt, None, False, hid, out_rows=rank)
         if opname == "layer":
-            g.gnnagg_aggregate(g.WSUM, d_rp, d_ci, d_w, hid, out, 0, plan)
+            g.gnnagg_aggregate(aop, d_rp, d_ci, d_w, hid, out, 0, plan)
 
     for _ in range(warmup):
         step()
@@ -122,11 +134,11 @@ def measure_layer(g, W, torch, workload, steps, warmup, copy_gbs):
     flop = 2.0 * N * F * H
     b_alg = N * F * 4 + F * H * 4 + N * H * 4
     if opname == "layer":
-        b_alg += algorithmic_bytes(nnz, N, H, 4, True, 0)
+        b_alg += algorithmic_bytes(nnz, N, H, 4, gcn, 0)
     achieved = b_alg / (kern_ms * 1e-3) / 1e9
     log("%s: %.3f ms per step (combination %.1f GFLOP in fp64 MFMA), %.0f GB/s algorithmic" %
         (workload, kern_ms, flop / 1e9, achieved))
-    rec = {"metric": "one GCN layer, Combination first" if opname == "layer" else "Combination (dense layer)",
+    rec = {"metric": "one layer, Combination first" if opname == "layer" else "Combination (dense layer)",
            "value": (float(nnz) * H if opname == "layer" else flop) / (ms_per_step * 1e-3),
            "unit": "edge-features/s at the hidden width" if opname == "layer" else "flop/s",
            "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -150,7 +162,7 @@ def measure_layer(g, W, torch, workload, steps, warmup, copy_gbs):
 def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_seconds, copy_gbs, pitched=True):
     """One workload: setup (CSR build, row plan), timed aggregation steps, optional CPU-checker leg."""
     gkey, opname, F, xdt, gcn = WORKLOADS[workload]
-    if opname in ("combine", "layer"):
+    if opname in ("combine", "layer", "layer-ranked"):
         return measure_layer(g, W, torch, workload, steps, warmup, copy_gbs)
     gat = opname == "gat"
     heads, C = F if gat else (1, F)

@@ -220,12 +220,33 @@ GNNAGG_API int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
  *   W      [F,H] row-major fp32; bias [H] fp32 or NULL
  *   relu   1: act = max(0, .), 0: identity
  *   out    [N,H] row-major fp32; must not overlap X
+ *   out_rows  [N] int32 or NULL: row i of the result is stored as row out_rows[i] of out (a
+ *          permutation of 0..N-1, e.g. the rank array of gnnagg_rank_sources, so that the
+ *          aggregation that follows gathers from rows stored in popularity order)
  *
  * Products and sums are carried in fp64 on the matrix cores and rounded to fp32 once.
  * Asynchronous on `stream`.
  */
 GNNAGG_API int gnnagg_combine(int64_t N, const void* X, int x_dtype, int32_t F, const float* W, const float* bias,
-                              int32_t H, int relu, float* out, void* stream);
+                              int32_t H, int relu, float* out, const int32_t* out_rows, void* stream);
+
+/*
+ * Popularity order of the source vertices, for feature rows narrower than a 128-byte line
+ * (Aggregation at the hidden widths of Section III).  A gather fetches whole lines; when the rows that
+ * are gathered most often sit next to each other, the hot part of X occupies a fraction of the lines
+ * it would otherwise and stays in L2.
+ *
+ *   rank           [N] int32 out: position of vertex j when the vertices are ordered by how often they
+ *                  occur in colidx, most frequent first, ties by vertex id
+ *   colidx_ranked  [nnz] int32 out: rank[colidx[e]]
+ *
+ * Aggregating with (colidx_ranked, Xr), where Xr[rank[j]] = X[j] - e.g. the output of gnnagg_combine
+ * with out_rows = rank - gives bit for bit the result of (colidx, X): the order of the edges inside a
+ * row does not change.  (Not for gnnagg_gat_attention, which also reads H at the destination.)
+ * Asynchronous on `stream`; the usual workspace protocol.
+ */
+GNNAGG_API int gnnagg_rank_sources(int64_t N, int64_t nnz, const int32_t* colidx, int32_t* rank,
+                        int32_t* colidx_ranked, void* workspace, size_t* workspace_bytes, void* stream);
 
 /*
  * Measurement aid, not part of the method: copies `bytes` bytes (a multiple of

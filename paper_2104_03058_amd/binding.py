@@ -67,7 +67,9 @@ def load_library():
         lib.gnnagg_auto_f_chunk.restype = i32
         lib.gnnagg_auto_f_chunk.argtypes = [i64, i32, ci, i64, vp]
         lib.gnnagg_combine.restype = ci
-        lib.gnnagg_combine.argtypes = [i64, vp, ci, i32, vp, vp, i32, ci, vp, vp]
+        lib.gnnagg_combine.argtypes = [i64, vp, ci, i32, vp, vp, i32, ci, vp, vp, vp]
+        lib.gnnagg_rank_sources.restype = ci
+        lib.gnnagg_rank_sources.argtypes = [i64, i64, vp, vp, vp, vp, szp, vp]
         lib.gnnagg_copy_probe.restype = ci
         lib.gnnagg_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         _lib = lib
@@ -332,19 +334,42 @@ def gnnagg_auto_f_chunk(N: int, F: int, x_dtype: int = F32, x_pitch: int = 0,
 
 
 def gnnagg_combine(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor] = None, relu: bool = False,
-                   out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """out[N,H] fp32 = act(X[N,F] @ W[F,H] + bias); X fp32 or bf16, W and bias fp32."""
+                   out: Optional[torch.Tensor] = None, stream=None,
+                   out_rows: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """out[N,H] fp32 = act(X[N,F] @ W[F,H] + bias); X fp32 or bf16, W and bias fp32.  With out_rows (int32 [N], a
+    permutation) row i of the result is stored as row out_rows[i]."""
     if X.dim() != 2 or W.dim() != 2 or W.shape[0] != X.shape[1]:
         raise ValueError("X must be [N,F] and W [F,H]")
     N, F, H = int(X.shape[0]), int(X.shape[1]), int(W.shape[1])
     if bias is not None and tuple(bias.shape) != (H,):
         raise ValueError("bias must be [H]")
+    if out_rows is not None and tuple(out_rows.shape) != (N,):
+        raise ValueError("out_rows must be [N]")
     if out is None:
         out = torch.empty((N, H), dtype=torch.float32, device=X.device)
     elif tuple(out.shape) != (N, H):
         raise ValueError("out must be [N, H]")
     rc = load_library().gnnagg_combine(N, _dev(X, None, "X"), _x_dtype(X), F, _dev(W, torch.float32, "W"),
                                        _dev(bias, torch.float32, "bias"), H, int(bool(relu)),
-                                       _dev(out, torch.float32, "out"), _stream(stream))
+                                       _dev(out, torch.float32, "out"), _dev(out_rows, torch.int32, "out_rows"),
+                                       _stream(stream))
     _check("gnnagg_combine", rc)
     return out
+
+
+def gnnagg_rank_sources(N: int, colidx: torch.Tensor, stream=None):
+    """(rank int32 [N], colidx_ranked int32 [nnz]): vertices ordered by how often they occur in colidx."""
+    lib = load_library()
+    nnz = int(colidx.shape[0])
+    dev = colidx.device
+    need = ctypes.c_size_t(0)
+    _check("gnnagg_rank_sources", lib.gnnagg_rank_sources(N, nnz, None, None, None, None, ctypes.byref(need), None))
+    ws = _workspace(need.value, dev)
+    rank = torch.empty(max(N, 1), dtype=torch.int32, device=dev)
+    ranked = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
+    have = ctypes.c_size_t(ws.numel())
+    _check("gnnagg_rank_sources",
+           lib.gnnagg_rank_sources(N, nnz, _dev(colidx, torch.int32, "colidx"), _dev(rank), _dev(ranked), _dev(ws),
+                                   ctypes.byref(have), _stream(stream)))
+    ws.record_stream(torch.cuda.current_stream() if stream is None else stream)
+    return rank[:N], ranked[:nnz]

@@ -38,6 +38,7 @@ struct CombineArgs {
   const float* W;
   const float* bias;
   float* out;
+  const int32_t* out_rows;  // row i of the result goes to row out_rows[i] of out (null: i)
   int64_t N;
   int32_t F, H;
   int32_t col0;       // first output column of this pass
@@ -167,7 +168,8 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(const CombineArgs a) {
         if (row >= a.N) continue;
         float y = (float)(acc[r][c][v] + b);
         if (a.relu) y = y > 0.0f ? y : 0.0f;
-        a.out[row * a.H + col] = y;
+        const int64_t orow = a.out_rows ? (int64_t)a.out_rows[row] : row;
+        a.out[orow * a.H + col] = y;
       }
     }
   }
@@ -191,13 +193,14 @@ int launch_combine(const CombineArgs& a, hipStream_t stream) {
 using namespace gnnagg;
 
 extern "C" int gnnagg_combine(int64_t N, const void* X, int x_dtype, int32_t F, const float* W, const float* bias,
-                              int32_t H, int relu, float* out, void* stream_) {
+                              int32_t H, int relu, float* out, const int32_t* out_rows, void* stream_) {
   if (N < 0 || F <= 0 || H <= 0 || (relu != 0 && relu != 1)) return GNNAGG_EINVAL;
   if (x_dtype != GNNAGG_F32 && x_dtype != GNNAGG_BF16) return GNNAGG_EINVAL;
   if (N == 0) return GNNAGG_OK;
   if (!X || !W || !out) return GNNAGG_ENULL;
   const size_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
-  if (((uintptr_t)X % xs) || ((uintptr_t)W % 4) || ((uintptr_t)out % 4) || (bias && ((uintptr_t)bias % 4)))
+  if (((uintptr_t)X % xs) || ((uintptr_t)W % 4) || ((uintptr_t)out % 4) || (bias && ((uintptr_t)bias % 4)) ||
+      (out_rows && ((uintptr_t)out_rows % 4)))
     return GNNAGG_EINVAL;
   if (X == (const void*)out) return GNNAGG_EINVAL;
   if (ceil_div(N, kRowsPerBlock) > 0x7fffffffll) return GNNAGG_EUNSUPPORTED;
@@ -209,6 +212,7 @@ extern "C" int gnnagg_combine(int64_t N, const void* X, int x_dtype, int32_t F, 
     a.W = W;
     a.bias = bias;
     a.out = out;
+    a.out_rows = out_rows;
     a.N = N;
     a.F = F;
     a.H = H;

@@ -117,6 +117,44 @@ __global__ __launch_bounds__(kBlock) void plan_finish_kernel(const uint64_t* __r
   else class_off[GNNAGG_PLAN_CLASSES] = N;
 }
 
+// ---- popularity order of the sources -------------------------------------------
+__global__ __launch_bounds__(kBlock) void fill_u32_kernel(uint32_t* __restrict__ p, int64_t n, uint32_t v) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+__global__ __launch_bounds__(kBlock) void count_sources_kernel(const int32_t* __restrict__ colidx, int64_t nnz,
+                                                               int64_t N, uint32_t* __restrict__ count) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (e >= nnz) return;
+  const int64_t j = colidx[e];
+  if (j >= 0 && j < N) atomicAdd(&count[j], 1u);  // integer counts: the result does not depend on the order
+}
+
+__global__ __launch_bounds__(kBlock) void make_count_keys_kernel(const uint32_t* __restrict__ count, int64_t N,
+                                                                 uint64_t* __restrict__ keys,
+                                                                 uint32_t* __restrict__ vals) {
+  const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (j >= N) return;
+  keys[j] = 0xffffffffull - (uint64_t)count[j];  // ascending key = descending count; the sort is stable in j
+  vals[j] = (uint32_t)j;
+}
+
+__global__ __launch_bounds__(kBlock) void rank_from_order_kernel(const uint32_t* __restrict__ order, int64_t N,
+                                                                 int32_t* __restrict__ rank) {
+  const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (p < N) rank[order[p]] = (int32_t)p;
+}
+
+__global__ __launch_bounds__(kBlock) void rename_sources_kernel(const int32_t* __restrict__ colidx, int64_t nnz,
+                                                                int64_t N, const int32_t* __restrict__ rank,
+                                                                int32_t* __restrict__ out) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (e >= nnz) return;
+  const int64_t j = colidx[e];
+  out[e] = (j >= 0 && j < N) ? rank[j] : (int32_t)j;
+}
+
 struct CsrWorkspace {
   uint64_t *keys_a, *keys_b;
   uint32_t *vals_a, *vals_b, *hist, *scan, *bad;
@@ -229,5 +267,46 @@ extern "C" int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
   GNNAGG_HIP_TRY(hipMemcpyAsync(class_off, d_off, sizeof(int64_t) * (GNNAGG_PLAN_CLASSES + 1),
                                 hipMemcpyDeviceToHost, stream));
   GNNAGG_HIP_TRY(hipStreamSynchronize(stream));
+  return GNNAGG_OK;
+}
+
+extern "C" int gnnagg_rank_sources(int64_t N, int64_t nnz, const int32_t* colidx, int32_t* rank,
+                                   int32_t* colidx_ranked, void* workspace, size_t* workspace_bytes, void* stream_) {
+  if (N < 0 || nnz < 0) return GNNAGG_EINVAL;
+  if (!workspace_bytes) return GNNAGG_ENULL;
+  if (N >= (1ll << 31) || nnz >= (1ll << 32)) return GNNAGG_EUNSUPPORTED;
+  CsrWorkspace w = carve_sort_workspace(workspace, N);
+  Carver extra(workspace ? (char*)workspace + w.bytes : nullptr);
+  uint32_t* count = extra.take<uint32_t>((size_t)(N > 0 ? N : 1));
+  const size_t need = w.bytes + extra.used;
+  if (!workspace) {
+    *workspace_bytes = need;
+    return GNNAGG_OK;
+  }
+  if (*workspace_bytes < need || ((uintptr_t)workspace & 255u)) return GNNAGG_EWORKSPACE;
+  if (N == 0) return nnz == 0 ? GNNAGG_OK : GNNAGG_EINVAL;
+  if (!rank || (nnz > 0 && (!colidx || !colidx_ranked))) return GNNAGG_ENULL;
+  if (((uintptr_t)rank % 4) || ((uintptr_t)colidx % 4) || ((uintptr_t)colidx_ranked % 4)) return GNNAGG_EINVAL;
+  hipStream_t stream = (hipStream_t)stream_;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(N)), dim3(kBlock), 0, stream, count, N, 0u);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  if (nnz > 0) {
+    hipLaunchKernelGGL(count_sources_kernel, dim3(grid_for(nnz)), dim3(kBlock), 0, stream, colidx, nnz, N, count);
+    GNNAGG_HIP_TRY(hipGetLastError());
+  }
+  hipLaunchKernelGGL(make_count_keys_kernel, dim3(grid_for(N)), dim3(kBlock), 0, stream, (const uint32_t*)count, N,
+                     w.keys_a, w.vals_a);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  bool in_a = true;
+  int rc = radix_sort_pairs(w.keys_a, w.vals_a, w.keys_b, w.vals_b, N, 0, 32, w.hist, w.scan, stream, &in_a);
+  if (rc != GNNAGG_OK) return rc;
+  hipLaunchKernelGGL(rank_from_order_kernel, dim3(grid_for(N)), dim3(kBlock), 0, stream,
+                     (const uint32_t*)(in_a ? w.vals_a : w.vals_b), N, rank);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  if (nnz > 0) {
+    hipLaunchKernelGGL(rename_sources_kernel, dim3(grid_for(nnz)), dim3(kBlock), 0, stream, colidx, nnz, N,
+                       (const int32_t*)rank, colidx_ranked);
+    GNNAGG_HIP_TRY(hipGetLastError());
+  }
   return GNNAGG_OK;
 }

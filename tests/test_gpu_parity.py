@@ -624,3 +624,36 @@ def test_row_pitched_input_and_output(F, bf16, fc):
         out2 = torch.full((N, out.stride(0)), -7.0, dtype=torch.float32, device="cuda")[:, :F]
         g.gnnagg_aggregate(gop, d_rp, d_ci, d_w if name == "wsum" else None, dev(X), out2, fc, plan)
         assert np.array_equal(host(out2).view(np.uint32), got.view(np.uint32))
+
+
+# ------------------------------------------------------------------ feature rows stored in popularity order
+def test_rank_sources_and_gather_from_ranked_rows():
+    """rank orders the vertices by how often they are gathered (ties by id); aggregating (colidx_ranked, X stored
+    by rank) gives bit for bit what (colidx, X) gives; Combination can write its rows by rank."""
+    N, src, dst = W.graph("c5", 0.01)
+    rp, ci, _, _ = oracle.build_csr(N, src, dst)
+    d_rp, d_ci = dev(rp), dev(ci)
+    rank, ranked = g.gnnagg_rank_sources(N, d_ci)
+    rank_h, ranked_h = host(rank), host(ranked)
+    count = np.bincount(ci, minlength=N)
+    want_order = np.lexsort((np.arange(N), -count))          # most frequent first, ties by id
+    want_rank = np.empty(N, np.int32)
+    want_rank[want_order] = np.arange(N, dtype=np.int32)
+    assert np.array_equal(rank_h, want_rank)
+    assert np.array_equal(ranked_h, want_rank[ci])
+    plan = g.gnnagg_plan_rows(d_rp)
+    X = W.normal_f32((N, 24), seed=950)
+    Wt = W.normal_f32((24, 16), seed=951, std=0.3)
+    hid = g.gnnagg_combine(dev(X), dev(Wt))
+    hid_r = g.gnnagg_combine(dev(X), dev(Wt), out_rows=rank)
+    assert_close(host(hid), oracle.combine(X, Wt), what="combine")
+    assert np.array_equal(host(hid_r)[rank_h].view(np.uint32), host(hid).view(np.uint32))
+    for gop in (0, 2, 3):
+        a = g.gnnagg_aggregate(gop, d_rp, d_ci, None, hid, None, 0, plan)
+        b = g.gnnagg_aggregate(gop, d_rp, ranked, None, hid_r, None, 0, plan)
+        assert np.array_equal(host(a).view(np.uint32), host(b).view(np.uint32)), gop
+    ref = oracle.aggregate(oracle.SUM, rp, ci, None, host(hid))
+    assert_close(host(g.gnnagg_aggregate(0, d_rp, ranked, None, hid_r, None, 0, plan)), ref, what="ranked sum")
+    # a graph without edges and a single vertex
+    r1, c1 = g.gnnagg_rank_sources(3, torch.empty(0, dtype=torch.int32, device="cuda"))
+    assert host(r1).tolist() == [0, 1, 2] and c1.numel() == 0

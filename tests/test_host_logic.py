@@ -124,19 +124,29 @@ def test_argument_validation_returns_before_any_launch(lib):
             pitch(64, 1), pitch(1, 1)] == [128, 608, 32, 16, 64, 4, 64, 64, 1]
     assert pitch(0, 0) == 0 and pitch(8, 7) == 0
 
+    ranks = lib.gnnagg_rank_sources
+    assert ranks(-1, 0, None, None, None, None, ctypes.byref(need), None) == EINVAL
+    assert ranks(5, 1 << 32, None, None, None, None, ctypes.byref(need), None) == EUNSUP
+    assert ranks(5, 9, None, None, None, None, None, None) == ENULL
+    assert ranks(5, 9, None, None, None, None, ctypes.byref(need), None) == 0 and need.value > 0
+    tiny = ctypes.c_size_t(8)
+    assert ranks(5, 9, one, one, one, one, ctypes.byref(tiny), None) == EWS
+    roomy = ctypes.c_size_t(need.value)
+    assert ranks(5, 9, None, one, one, one, ctypes.byref(roomy), None) == ENULL
+
     comb = lib.gnnagg_combine
     other = ctypes.c_void_p(8192)
-    assert comb(-1, one, 0, 8, one, None, 4, 0, other, None) == EINVAL   # N
-    assert comb(4, one, 0, 0, one, None, 4, 0, other, None) == EINVAL    # F
-    assert comb(4, one, 0, 8, one, None, 0, 0, other, None) == EINVAL    # H
-    assert comb(4, one, 3, 8, one, None, 4, 0, other, None) == EINVAL    # x_dtype
-    assert comb(4, one, 0, 8, one, None, 4, 2, other, None) == EINVAL    # relu flag
-    assert comb(4, None, 0, 8, one, None, 4, 0, other, None) == ENULL    # X
-    assert comb(4, one, 0, 8, None, None, 4, 0, other, None) == ENULL    # W
-    assert comb(4, one, 0, 8, one, None, 4, 0, None, None) == ENULL      # out
-    assert comb(4, one, 0, 8, one, None, 4, 0, one, None) == EINVAL      # out aliases X
-    assert comb(4, ctypes.c_void_p(4098), 0, 8, one, None, 4, 0, other, None) == EINVAL  # fp32 X on a 2-byte boundary
-    assert comb(0, None, 0, 8, None, None, 4, 0, None, None) == 0        # no rows: nothing to do
+    assert comb(-1, one, 0, 8, one, None, 4, 0, other, None, None) == EINVAL   # N
+    assert comb(4, one, 0, 0, one, None, 4, 0, other, None, None) == EINVAL    # F
+    assert comb(4, one, 0, 8, one, None, 0, 0, other, None, None) == EINVAL    # H
+    assert comb(4, one, 3, 8, one, None, 4, 0, other, None, None) == EINVAL    # x_dtype
+    assert comb(4, one, 0, 8, one, None, 4, 2, other, None, None) == EINVAL    # relu flag
+    assert comb(4, None, 0, 8, one, None, 4, 0, other, None, None) == ENULL    # X
+    assert comb(4, one, 0, 8, None, None, 4, 0, other, None, None) == ENULL    # W
+    assert comb(4, one, 0, 8, one, None, 4, 0, None, None, None) == ENULL      # out
+    assert comb(4, one, 0, 8, one, None, 4, 0, one, None, None) == EINVAL      # out aliases X
+    assert comb(4, ctypes.c_void_p(4098), 0, 8, one, None, 4, 0, other, None, None) == EINVAL  # fp32 X on a 2-byte boundary
+    assert comb(0, None, 0, 8, None, None, 4, 0, None, None, None) == 0        # no rows: nothing to do
 
 
 # ------------------------------------------------------------------ launch geometry
@@ -305,6 +315,6 @@ def test_bench_module_is_importable_and_its_workloads_name_known_graphs():
     bench = importlib.import_module("bench")
     for name, (gkey, opname, F, xdt, gcn) in bench.WORKLOADS.items():
         assert gkey in W.GRAPHS, name
-        assert opname in ("sum", "wsum", "mean", "max", "gat", "combine", "layer"), name
+        assert opname in ("sum", "wsum", "mean", "max", "gat", "combine", "layer", "layer-ranked"), name
         assert xdt in ("f32", "bf16"), name
     assert set(bench.MEASURED_TRAFFIC) <= set(bench.WORKLOADS)

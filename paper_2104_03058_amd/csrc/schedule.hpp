@@ -296,10 +296,11 @@ inline void degree_profile(const int64_t* class_off, int64_t N, int64_t hot_rows
 //  (1) X beyond ~1 GiB (several times the 256 MB Infinity Cache; 2.4 M rows x 256-512 fp32 columns):
 //      chunks whose column slice of X is ~300-600 MB are 13-17 % faster than one chunk, row pieces under
 //      128 bytes twice slower than either -> power-of-two width with a ~384 MB slice, >= 128-byte pieces;
-//  (2) rows on 128-byte lines, fp32, at least four lines wide, a dense graph (mean degree >= 96) whose
-//      hubs matter - the 32,768 longest rows, as many as one 4 MB L2 holds lines of one chunk, take
+//  (2) rows on 128-byte lines, fp32, at least four lines wide, a graph that is not very sparse (mean
+//      degree >= 16) and whose hubs matter - the 32,768 longest rows, as many as one 4 MB L2 holds lines of one chunk, take
 //      >= 40 % of the edges: chunks of exactly ONE LINE (32 columns) are 9-27 % faster than one chunk
-//      (power-law graphs of mean degree 490-600 and hot share 0.70-0.74, 128-602 columns), because a
+//      (power-law graphs of mean degree 490-600 and hot share 0.70-0.74, 128-602 columns; 11-20 % at
+//      mean degree 25-200, nothing to gain below ~12), because a
 //      chunk pass then asks for one line per edge from a slice of N x 128 bytes in which the hubs' lines
 //      stay in L2.  Uniform graphs (hot share < 0.2) lose 3-9 % to the extra passes over the edge list,
 //      bf16 rows lose 20 % (a lane then accumulates 8 columns in fp64 per line: arithmetic-bound), and
@@ -319,7 +320,7 @@ inline int32_t auto_f_chunk(int64_t N, int32_t F, int elem_bytes, bool rows_on_l
   if (rows_on_lines && elem_bytes == 4 && F >= 128 && class_off && N > kLinesPerL2) {
     double mean_degree, hot_share;
     degree_profile(class_off, N, kLinesPerL2, &mean_degree, &hot_share);
-    if (mean_degree >= 96.0 && hot_share >= 0.4) return 32;
+    if (mean_degree >= 16.0 && hot_share >= 0.4) return 32;
   }
   return F;
 }

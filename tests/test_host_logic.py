@@ -296,7 +296,7 @@ def test_auto_chunk_width_one_line_on_dense_skewed_graphs(lib):
     skewed = plan_of(N, {15: 60, 14: 700, 13: 4000, 12: 12000, 11: 25000, 10: 40000, 9: 50000, 8: 45000, 7: 30000,
                          6: 15000, 5: 8000})                 # power-law shaped: mean ~ 500, long tail of hubs
     flat = plan_of(N, {8: N})                                 # every row 128..255 edges
-    sparse = plan_of(N, {15: 5, 10: 1000, 5: 100000, 3: 100000})
+    sparse = plan_of(N, {12: 5, 8: 100, 3: 100000, 2: 100000})   # mean degree ~ 5
     assert g.gnnagg_auto_f_chunk(N, 602, g.F32, 608, skewed) == 32
     assert g.gnnagg_auto_f_chunk(N, 256, g.F32, 256, skewed) == 32
     assert g.gnnagg_auto_f_chunk(N, 602, g.F32, 602, skewed) == 602    # rows not on lines

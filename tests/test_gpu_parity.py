@@ -657,3 +657,44 @@ def test_rank_sources_and_gather_from_ranked_rows():
     # a graph without edges and a single vertex
     r1, c1 = g.gnnagg_rank_sources(3, torch.empty(0, dtype=torch.int32, device="cuda"))
     assert host(r1).tolist() == [0, 1, 2] and c1.numel() == 0
+
+
+# ------------------------------------------------------------------ HIP graph capture of the enqueue-only calls
+def test_calls_can_be_captured_in_a_graph_and_replayed():
+    """Combination, aggregation and attention only enqueue kernels (no allocation, no synchronisation, no
+    memset), so a layer can be captured once and replayed: every replay, with fresh inputs copied in place
+    and ordinary eager work in between, must give the bits of the eager call."""
+    N, src, dst = W.graph("c2")
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, oracle.SELF_LOOPS | oracle.NORM_SYM, want_w=True)
+    d_rp, d_ci, d_w = dev(rp), dev(ci), dev(w)
+    plan = g.gnnagg_plan_rows(d_rp)
+    Wt = dev(W.normal_f32((48, 64), seed=971, std=0.2))
+    a_s, a_d = dev(W.normal_f32((8, 8), seed=972, std=0.1)), dev(W.normal_f32((8, 8), seed=973, std=0.1))
+    X = torch.zeros((N, 48), dtype=torch.float32, device="cuda")
+    hid = torch.empty((N, 64), dtype=torch.float32, device="cuda")
+    agg = torch.empty((N, 64), dtype=torch.float32, device="cuda")
+    att = torch.empty((N, 8, 8), dtype=torch.float32, device="cuda")
+    ws = torch.empty(g.gnnagg_gat_workspace_bytes(N, 8, 8, plan), dtype=torch.uint8, device="cuda")
+
+    def layer():
+        g.gnnagg_combine(X, Wt, None, True, hid)
+        g.gnnagg_aggregate(g.WSUM, d_rp, d_ci, d_w, hid, agg, 0, plan)
+        g.gnnagg_gat_attention(d_rp, d_ci, hid.view(N, 8, 8), a_s, a_d, 0.2, False, True, 0, plan, out=att, workspace=ws)
+
+    layer()  # eager once: code objects loaded, nothing left to allocate
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        layer()
+    for k in range(4):
+        X.copy_(dev(W.normal_f32((N, 48), seed=980 + k)))
+        graph.replay()
+        torch.cuda.synchronize()
+        got_agg, got_att = agg.clone(), att.clone()
+        agg.zero_()
+        att.zero_()
+        layer()  # eager, same inputs
+        torch.cuda.synchronize()
+        assert torch.equal(got_agg, agg) and torch.equal(got_att, att), "replay %d differs from the eager call" % k
+        ref = oracle.aggregate(oracle.WSUM, rp, ci, w, oracle.combine(host(X), host(Wt), None, True))
+        assert_close(host(agg), ref, what="captured layer, replay %d" % k)

@@ -3,8 +3,9 @@
 // One sort pass = three launches: per-workgroup digit histograms, a scan of the
 // digit-major histogram table, and a scatter in which every key finds its
 // stable rank inside its workgroup tile with wave ballots (64-lane match on the
-// digit) and a small LDS table across the four waves.  No global atomics, so
-// the output order is unique.
+// digit) and a small LDS table across the four waves; the tile is sorted by digit
+// in LDS and leaves it in whole runs.  No global atomics, so the output order is
+// unique.
 #include "radix_sort.hpp"
 
 namespace gnnagg {
@@ -87,54 +88,96 @@ __global__ __launch_bounds__(kBlock) void radix_hist_kernel(const uint64_t* __re
   hist[(int64_t)threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
 }
 
+// One workgroup scatters one tile of kSortTile keys.  The tile is cut into four contiguous quarters, one
+// per wave; a wave keeps its 16 x 64 keys in registers.  Phase 1: every wave counts its quarter per digit
+// (wave ballots find the lanes that hold the same digit; one lane per group adds the group size to an LDS
+// counter).  Thread d then turns the counts of digit d into the place of each wave's keys with that
+// digit inside the tile sorted by digit (an exclusive scan over the digits gives where digit d starts).
+// Phase 2: every wave walks its rounds again, alone - position = running start of (wave, digit) + rank
+// inside the group - and stores key and value at that place IN LDS.  Phase 3: the sorted tile leaves LDS
+// in order, so the keys of one digit go to consecutive global addresses (whole lines, not one 8-byte
+// store per lane and digit).  Equal digits keep their input order: the sort is stable, and no global
+// atomic is involved.
 __global__ __launch_bounds__(kBlock) void radix_scatter_kernel(
     const uint64_t* __restrict__ kin, const uint32_t* __restrict__ vin, uint64_t* __restrict__ kout,
     uint32_t* __restrict__ vout, int64_t n, int shift, const uint32_t* __restrict__ hist_scanned,
     int64_t nblk) {
-  __shared__ uint32_t base[kRadixBins];
-  __shared__ uint32_t cnt[kWavesPerBlock][kRadixBins];
+  __shared__ uint64_t lkey[kSortTile];
+  __shared__ uint32_t lval[kSortTile];
+  __shared__ uint32_t start[kWavesPerBlock][kRadixBins];  // counts in phase 1, running local positions after
+  __shared__ uint32_t shift_out[kRadixBins];              // global position minus local position, per digit
+  __shared__ uint32_t lds4[kWavesPerBlock];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
-  base[tid] = hist_scanned[(int64_t)tid * nblk + blockIdx.x];
 #pragma unroll
-  for (int k = 0; k < kWavesPerBlock; ++k) cnt[k][tid] = 0;
+  for (int k = 0; k < kWavesPerBlock; ++k) start[k][tid] = 0;
   __syncthreads();
+  constexpr int kQuarter = kSortTile / kWavesPerBlock;  // keys per wave
   const int64_t tile = (int64_t)blockIdx.x * kSortTile;
+  const int64_t first = tile + (int64_t)w * kQuarter + lane;
   const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
+  uint64_t key[kSortItemsPerThread];
+  uint32_t val[kSortItemsPerThread];
+  uint32_t rank_size[kSortItemsPerThread];  // rank inside the group (low 8 bits), group size - 1 (next 8), valid (bit 16)
+#pragma unroll
   for (int r = 0; r < kSortItemsPerThread; ++r) {
-    if (tile + (int64_t)r * kBlock >= n) break;  // uniform over the workgroup
-    const int64_t i = tile + (int64_t)r * kBlock + tid;
+    const int64_t i = first + (int64_t)r * kWave;
     const bool valid = i < n;
-    const uint64_t key = valid ? kin[i] : 0ull;
-    const uint32_t val = valid ? vin[i] : 0u;
-    const uint32_t d = (uint32_t)(key >> shift) & (kRadixBins - 1);
-    // lanes of this wave that hold the same digit
-    uint64_t same = __ballot(valid);
+    key[r] = valid ? kin[i] : 0ull;
+    val[r] = valid ? vin[i] : 0u;
+    const uint32_t d = (uint32_t)(key[r] >> shift) & (kRadixBins - 1);
+    uint64_t same = __ballot(valid);  // lanes of this wave that hold the same digit
 #pragma unroll
     for (int b = 0; b < kRadixBits; ++b) {
       const bool bit = (d >> b) & 1u;
       const uint64_t bal = __ballot(valid && bit);
       same &= bit ? bal : ~bal;
     }
-    const uint32_t rank = (uint32_t)__popcll(same & below);
-    if (valid && rank == 0) cnt[w][d] = (uint32_t)__popcll(same);
-    __syncthreads();
-    if (valid) {
-      uint32_t pos = base[d] + rank;
-#pragma unroll
-      for (int k = 0; k < kWavesPerBlock; ++k)
-        if (k < w) pos += cnt[k][d];
-      kout[pos] = key;
-      vout[pos] = val;
-    }
-    __syncthreads();
-    uint32_t t = 0;
+    const uint32_t rank = (uint32_t)__popcll(same & below), size = (uint32_t)__popcll(same);
+    rank_size[r] = rank | ((size - (valid ? 1u : 0u)) << 8) | (valid ? 1u << 16 : 0u);
+    if (valid && rank == 0) start[w][d] += size;  // one lane per digit group; groups of a round differ in d
+  }
+  __syncthreads();
+  {
+    uint32_t c[kWavesPerBlock], tot = 0;
 #pragma unroll
     for (int k = 0; k < kWavesPerBlock; ++k) {
-      t += cnt[k][tid];
-      cnt[k][tid] = 0;
+      c[k] = start[k][tid];
+      tot += c[k];
     }
-    base[tid] += t;
-    __syncthreads();
+    uint32_t all;
+    uint32_t b = block_exclusive_scan(tot, lds4, &all);  // where digit `tid` starts in the sorted tile
+    shift_out[tid] = hist_scanned[(int64_t)tid * nblk + blockIdx.x] - b;  // modulo 2^32, undone below
+#pragma unroll
+    for (int k = 0; k < kWavesPerBlock; ++k) {
+      start[k][tid] = b;
+      b += c[k];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < kSortItemsPerThread; ++r) {
+    const bool valid = (rank_size[r] >> 16) & 1u;
+    const uint32_t d = (uint32_t)(key[r] >> shift) & (kRadixBins - 1);
+    const uint32_t rank = rank_size[r] & 0xffu, size = ((rank_size[r] >> 8) & 0xffu) + 1u;
+    uint32_t pos = 0;
+    if (valid) pos = start[w][d] + rank;
+    // every lane of a group has read the start before its first lane moves it on: LDS operations of one
+    // wave complete in program order
+    if (valid && rank == 0) start[w][d] += size;
+    if (valid) {
+      lkey[pos] = key[r];
+      lval[pos] = val[r];
+    }
+  }
+  __syncthreads();
+  const int64_t left = n - tile;
+  const int count = left < kSortTile ? (int)left : kSortTile;  // keys in this tile
+  for (int p = tid; p < count; p += kBlock) {
+    const uint64_t k = lkey[p];
+    const uint32_t d = (uint32_t)(k >> shift) & (kRadixBins - 1);
+    const uint32_t pos = (uint32_t)p + shift_out[d];
+    kout[pos] = k;
+    vout[pos] = lval[p];
   }
 }
 

@@ -9,7 +9,7 @@ namespace gnnagg {
 
 constexpr int kRadixBits = 8;
 constexpr int kRadixBins = 1 << kRadixBits;
-constexpr int kSortItemsPerThread = 16;
+constexpr int kSortItemsPerThread = 10;  // 2,560-key tiles: 36 KB of LDS, four workgroups per compute unit (measured best of 4..16)
 constexpr int kSortTile = kBlock * kSortItemsPerThread;  // keys per workgroup per pass
 
 constexpr int kScanItemsPerThread = 16;

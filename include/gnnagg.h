@@ -99,6 +99,14 @@ GNNAGG_API int gnnagg_build_csr(int64_t N, int64_t E, const int32_t* src, const 
                      size_t* workspace_bytes, void* stream);
 
 /*
+ * Checks a CSR that did not come from gnnagg_build_csr before it is handed to the aggregation calls,
+ * which trust it: rowptr[0] == 0, rowptr non-decreasing, rowptr[N] == nnz, every colidx value in [0, N).
+ * Returns GNNAGG_EINVAL if any of that fails.  Waits for `stream`; the usual workspace protocol.
+ */
+GNNAGG_API int gnnagg_check_csr(int64_t N, int64_t nnz, const int64_t* rowptr, const int32_t* colidx, void* workspace,
+                     size_t* workspace_bytes, void* stream);
+
+/*
  * Degree-sorted row schedule for the aggregation kernels (per graph, reusable
  * by every later aggregation call on the same CSR).  Power-law degree
  * distributions (Section III, Table II: average degree 4.5 to 597) need rows of

@@ -68,6 +68,8 @@ def load_library():
         lib.gnnagg_auto_f_chunk.argtypes = [i64, i32, ci, i64, vp]
         lib.gnnagg_combine.restype = ci
         lib.gnnagg_combine.argtypes = [i64, vp, ci, i32, vp, vp, i32, ci, vp, vp, vp]
+        lib.gnnagg_check_csr.restype = ci
+        lib.gnnagg_check_csr.argtypes = [i64, i64, vp, vp, vp, szp, vp]
         lib.gnnagg_rank_sources.restype = ci
         lib.gnnagg_rank_sources.argtypes = [i64, i64, vp, vp, vp, vp, szp, vp]
         lib.gnnagg_copy_probe.restype = ci
@@ -166,6 +168,23 @@ def gnnagg_build_csr(N: int, src: torch.Tensor, dst: torch.Tensor, flags: int = 
                               _stream(stream))
     _check("gnnagg_build_csr", rc)
     return rowptr, colidx, w, perm
+
+
+def gnnagg_check_csr(rowptr: torch.Tensor, colidx: torch.Tensor, stream=None) -> bool:
+    """True if (rowptr, colidx) is a well-formed CSR of N = len(rowptr) - 1 vertices (the aggregation calls trust
+    their CSR; check one that did not come from gnnagg_build_csr)."""
+    lib = load_library()
+    N, nnz = int(rowptr.shape[0]) - 1, int(colidx.shape[0])
+    need = ctypes.c_size_t(0)
+    _check("gnnagg_check_csr", lib.gnnagg_check_csr(N, nnz, None, None, None, ctypes.byref(need), None))
+    ws = _workspace(need.value, rowptr.device)
+    have = ctypes.c_size_t(ws.numel())
+    rc = lib.gnnagg_check_csr(N, nnz, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"), _dev(ws),
+                              ctypes.byref(have), _stream(stream))
+    if rc == -1:
+        return False
+    _check("gnnagg_check_csr", rc)
+    return True
 
 
 @dataclass

@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kBlock) void plan_finish_kernel(const uint64_t* __r
 }
 
 // ---- popularity order of the sources -------------------------------------------
-__global__ __launch_bounds__(kBlock) void fill_u32_kernel(uint32_t* __restrict__ p, int64_t n, uint32_t v) {
+__global__ __launch_bounds__(kBlock) void fill_range_u32_kernel(uint32_t* __restrict__ p, int64_t n, uint32_t v) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i < n) p[i] = v;
 }
@@ -153,6 +153,25 @@ __global__ __launch_bounds__(kBlock) void rename_sources_kernel(const int32_t* _
   if (e >= nnz) return;
   const int64_t j = colidx[e];
   out[e] = (j >= 0 && j < N) ? rank[j] : (int32_t)j;
+}
+
+// ---- validity check of a caller's CSR ----------------------------------------------
+__global__ __launch_bounds__(kBlock) void check_rowptr_kernel(const int64_t* __restrict__ rowptr, int64_t N,
+                                                              int64_t nnz, uint32_t* __restrict__ bad) {
+  const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (r > N) return;
+  bool wrong = false;
+  if (r == 0) wrong = rowptr[0] != 0 || rowptr[N] != nnz;
+  if (r < N) wrong = wrong || rowptr[r] > rowptr[r + 1] || rowptr[r] < 0 || rowptr[r + 1] > nnz;
+  if (wrong) atomicOr(bad, 1u);
+}
+
+__global__ __launch_bounds__(kBlock) void check_colidx_kernel(const int32_t* __restrict__ colidx, int64_t nnz,
+                                                              int64_t N, uint32_t* __restrict__ bad) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (e >= nnz) return;
+  const int64_t j = colidx[e];
+  if (j < 0 || j >= N) atomicOr(bad, 2u);
 }
 
 struct CsrWorkspace {
@@ -288,7 +307,7 @@ extern "C" int gnnagg_rank_sources(int64_t N, int64_t nnz, const int32_t* colidx
   if (!rank || (nnz > 0 && (!colidx || !colidx_ranked))) return GNNAGG_ENULL;
   if (((uintptr_t)rank % 4) || ((uintptr_t)colidx % 4) || ((uintptr_t)colidx_ranked % 4)) return GNNAGG_EINVAL;
   hipStream_t stream = (hipStream_t)stream_;
-  hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(N)), dim3(kBlock), 0, stream, count, N, 0u);
+  hipLaunchKernelGGL(fill_range_u32_kernel, dim3(grid_for(N)), dim3(kBlock), 0, stream, count, N, 0u);
   GNNAGG_HIP_TRY(hipGetLastError());
   if (nnz > 0) {
     hipLaunchKernelGGL(count_sources_kernel, dim3(grid_for(nnz)), dim3(kBlock), 0, stream, colidx, nnz, N, count);
@@ -309,4 +328,30 @@ extern "C" int gnnagg_rank_sources(int64_t N, int64_t nnz, const int32_t* colidx
     GNNAGG_HIP_TRY(hipGetLastError());
   }
   return GNNAGG_OK;
+}
+
+extern "C" int gnnagg_check_csr(int64_t N, int64_t nnz, const int64_t* rowptr, const int32_t* colidx, void* workspace,
+                                size_t* workspace_bytes, void* stream_) {
+  if (N < 0 || nnz < 0) return GNNAGG_EINVAL;
+  if (!workspace_bytes) return GNNAGG_ENULL;
+  if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
+  Carver carve(workspace);
+  uint32_t* bad = carve.take<uint32_t>(64);
+  if (!workspace) {
+    *workspace_bytes = carve.used;
+    return GNNAGG_OK;
+  }
+  if (*workspace_bytes < carve.used || ((uintptr_t)workspace & 255u)) return GNNAGG_EWORKSPACE;
+  if (!rowptr || (nnz > 0 && !colidx)) return GNNAGG_ENULL;
+  if (((uintptr_t)rowptr % 8) || ((uintptr_t)colidx % 4)) return GNNAGG_EINVAL;
+  hipStream_t stream = (hipStream_t)stream_;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(1), 0, stream, bad, 0u);
+  hipLaunchKernelGGL(check_rowptr_kernel, dim3(grid_for(N + 1)), dim3(kBlock), 0, stream, rowptr, N, nnz, bad);
+  if (nnz > 0)
+    hipLaunchKernelGGL(check_colidx_kernel, dim3(grid_for(nnz)), dim3(kBlock), 0, stream, colidx, nnz, N, bad);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  uint32_t flag = 0;
+  GNNAGG_HIP_TRY(hipMemcpyAsync(&flag, bad, sizeof(flag), hipMemcpyDeviceToHost, stream));
+  GNNAGG_HIP_TRY(hipStreamSynchronize(stream));
+  return flag ? GNNAGG_EINVAL : GNNAGG_OK;
 }

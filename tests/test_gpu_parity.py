@@ -698,3 +698,22 @@ def test_calls_can_be_captured_in_a_graph_and_replayed():
         assert torch.equal(got_agg, agg) and torch.equal(got_att, att), "replay %d differs from the eager call" % k
         ref = oracle.aggregate(oracle.WSUM, rp, ci, w, oracle.combine(host(X), host(Wt), None, True))
         assert_close(host(agg), ref, what="captured layer, replay %d" % k)
+
+
+def test_check_csr_accepts_built_graphs_and_rejects_broken_ones():
+    N, src, dst = W.graph("c2")
+    rp, ci, _, _ = gpu_csr(N, src, dst, oracle.SELF_LOOPS)
+    assert g.gnnagg_check_csr(rp, ci)
+    bad = ci.clone()
+    bad[1234] = N            # a source that does not exist
+    assert not g.gnnagg_check_csr(rp, bad)
+    bad[1234] = -1
+    assert not g.gnnagg_check_csr(rp, bad)
+    rp2 = rp.clone()
+    rp2[100], rp2[101] = rp[101].item() + 1, rp[100].item()   # a row that ends before it starts
+    assert not g.gnnagg_check_csr(rp2, ci)
+    rp3 = rp.clone()
+    rp3[N] = rp[N] + 5       # claims more entries than colidx holds
+    assert not g.gnnagg_check_csr(rp3, ci)
+    empty = torch.zeros(4, dtype=torch.int64, device="cuda")
+    assert g.gnnagg_check_csr(empty, torch.empty(0, dtype=torch.int32, device="cuda"))

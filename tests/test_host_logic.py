@@ -124,6 +124,13 @@ def test_argument_validation_returns_before_any_launch(lib):
             pitch(64, 1), pitch(1, 1)] == [128, 608, 32, 16, 64, 4, 64, 64, 1]
     assert pitch(0, 0) == 0 and pitch(8, 7) == 0
 
+    chk = lib.gnnagg_check_csr
+    assert chk(-1, 0, one, one, one, ctypes.byref(need), None) == EINVAL
+    assert chk(4, 3, one, one, None, None, None) == ENULL
+    assert chk(4, 3, None, None, None, ctypes.byref(need), None) == 0 and need.value >= 256
+    assert chk(4, 3, one, one, one, ctypes.byref(ctypes.c_size_t(8)), None) == EWS
+    assert chk(4, 3, None, one, one, ctypes.byref(ctypes.c_size_t(4096)), None) == ENULL
+
     ranks = lib.gnnagg_rank_sources
     assert ranks(-1, 0, None, None, None, None, ctypes.byref(need), None) == EINVAL
     assert ranks(5, 1 << 32, None, None, None, None, ctypes.byref(need), None) == EUNSUP

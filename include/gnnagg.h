@@ -18,9 +18,11 @@
  *    the caller.  The library allocates no device memory; scratch is passed in
  *    as `workspace`.  Inputs and outputs must not overlap.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    gnnagg_aggregate and gnnagg_gat_attention only enqueue work on it and
- *    return; gnnagg_build_csr and gnnagg_plan_rows also wait for it, because
- *    they hand results back to the host.
+ *    gnnagg_aggregate, gnnagg_aggregate_ws, gnnagg_gat_attention, gnnagg_combine
+ *    and gnnagg_rank_sources only enqueue kernels on it and return (no
+ *    allocation, synchronisation or memset: they can be captured in a HIP
+ *    graph); gnnagg_build_csr, gnnagg_check_csr and gnnagg_plan_rows also wait
+ *    for it, because they hand results back to the host.
  *  - Every call returns a gnnagg_status.  Invalid arguments are detected on the
  *    host before anything is launched and leave all outputs untouched.  Index
  *    values outside [0, N) inside colidx are a contract violation that the

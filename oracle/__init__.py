@@ -50,6 +50,8 @@ def _load():
         lib.gnnagg_ref_gat_attention_rows.argtypes = [i64, vp, vp, vp, vp, vp, vp, i32, i32, f32, vp, ci]
         lib.gnnagg_ref_combine.restype = ci
         lib.gnnagg_ref_combine.argtypes = [i64, vp, ci, i32, vp, vp, i32, ci, vp, ci]
+        lib.gnnagg_ref_update.restype = ci
+        lib.gnnagg_ref_update.argtypes = [i64, i32, vp, vp, ci, vp]
         _lib = lib
     return _lib
 
@@ -157,4 +159,16 @@ def combine(X, W, bias=None, relu=False, threads=1):
     rc = _load().gnnagg_ref_combine(N, _p(X), _xinfo(X), F, _p(W), _p(bias), H, int(bool(relu)), _p(out), threads)
     if rc != 0:
         raise ValueError("gnnagg_ref_combine failed: %d" % rc)
+    return out
+
+
+def update(A, bias=None, relu=False):
+    """out [N,F] float32 = act(A + bias): the Update step without a weight matrix on an aggregated matrix."""
+    A = _c(A, np.float32)
+    N, F = A.shape
+    bias = None if bias is None else _c(bias, np.float32)
+    out = np.empty((N, F), dtype=np.float32)
+    rc = _load().gnnagg_ref_update(N, F, _p(A), _p(bias), int(bool(relu)), _p(out))
+    if rc != 0:
+        raise ValueError("gnnagg_ref_update failed: %d" % rc)
     return out

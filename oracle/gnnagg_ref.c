@@ -340,3 +340,17 @@ int gnnagg_ref_combine(int64_t N, const void* X, int x_dtype, int32_t F, const f
     }
   return 0;
 }
+
+/* The Update step of Algorithm 1 without a weight matrix, applied to an aggregated matrix A [N,F]:
+ *   out[n,f] = act( A[n,f] + bias[f] ),  the sum formed in fp64 and rounded once to fp32;
+ * bias may be NULL. */
+int gnnagg_ref_update(int64_t N, int32_t F, const float* A, const float* bias, int relu, float* out) {
+  if (N < 0 || F <= 0 || !A || !out) return -1;
+  for (int64_t n = 0; n < N; ++n)
+    for (int32_t f = 0; f < F; ++f) {
+      float y = (float)((double)A[n * F + f] + (bias ? (double)bias[f] : 0.0));
+      if (relu && !(y > 0.0f)) y = 0.0f;
+      out[n * F + f] = y;
+    }
+  return 0;
+}

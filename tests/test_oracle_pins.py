@@ -495,3 +495,21 @@ def test_combination_commutes_with_linear_aggregation():
         a = oracle.combine(oracle.aggregate(op, rp, ci, w, X), Wt).astype(np.float64)
         b = oracle.aggregate(op, rp, ci, w, oracle.combine(X, Wt)).astype(np.float64)
         assert np.allclose(a, b, rtol=1e-4, atol=1e-4)
+
+
+def test_update_without_weights_is_a_rounded_addition_then_the_activation():
+    # pinned by the closed form on exactly representable values and by numpy on random ones
+    A = np.array([[1.0, -2.0, 0.5, -0.0], [3.0, 0.25, -8.0, 16.0]], np.float32)
+    b = np.array([0.5, 1.0, -0.5, 0.0], np.float32)
+    assert np.array_equal(oracle.update(A, b), np.array([[1.5, -1.0, 0.0, 0.0], [3.5, 1.25, -8.5, 16.0]], np.float32))
+    got = oracle.update(A, b, relu=True)
+    assert np.array_equal(got, np.array([[1.5, 0.0, 0.0, 0.0], [3.5, 1.25, 0.0, 16.0]], np.float32))
+    assert not np.signbit(got).any()  # max(0, .) never returns -0
+    assert np.array_equal(oracle.update(A), A) and np.array_equal(oracle.update(A, relu=True), np.maximum(A, 0))
+    R = W.normal_f32((50, 7), seed=320)
+    rb = W.normal_f32((7,), seed=321)
+    want = (R.astype(np.float64) + rb.astype(np.float64)).astype(np.float32)
+    assert np.array_equal(oracle.update(R, rb), want)  # a sum of two floats is exact in fp64: one rounding
+    assert np.array_equal(oracle.update(R, rb, relu=True), np.maximum(want, np.float32(0)))
+    # the bias belongs to the column, not the row
+    assert not np.array_equal(oracle.update(R[:7], rb), (R[:7].T.astype(np.float64) + rb).T.astype(np.float32))

@@ -18,11 +18,13 @@
  *    the caller.  The library allocates no device memory; scratch is passed in
  *    as `workspace`.  Inputs and outputs must not overlap.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    gnnagg_aggregate, gnnagg_aggregate_ws, gnnagg_gat_attention, gnnagg_combine
- *    and gnnagg_rank_sources only enqueue kernels on it and return (no
- *    allocation, synchronisation or memset: they can be captured in a HIP
- *    graph); gnnagg_build_csr, gnnagg_check_csr and gnnagg_plan_rows also wait
- *    for it, because they hand results back to the host.
+ *    gnnagg_aggregate, gnnagg_aggregate_ws, gnnagg_aggregate_update,
+ *    gnnagg_gat_attention, gnnagg_combine and
+ *    gnnagg_rank_sources only enqueue kernels on it and return (no allocation
+ *    on the host or the device, no synchronisation, no memset: they can be
+ *    captured in a HIP graph); gnnagg_build_csr, gnnagg_check_csr and
+ *    gnnagg_plan_rows also wait for it, because they hand results back to the
+ *    host.
  *  - Every call returns a gnnagg_status.  Invalid arguments are detected on the
  *    host before anything is launched and leave all outputs untouched.  Index
  *    values outside [0, N) inside colidx are a contract violation that the
@@ -184,6 +186,37 @@ GNNAGG_API int gnnagg_aggregate_ws(int op, int64_t N, const int64_t* rowptr, con
                         int out_dtype, int64_t out_pitch, int32_t F, int32_t f_chunk, const int32_t* row_order,
                         const int64_t* class_off, void* workspace, size_t* workspace_bytes, void* stream);
 
+/*
+ * Aggregation followed by the Update step of Algorithm 1 in the same kernels (Section I: Combination is
+ * the per-vertex dense update; Section III orders it before or after Aggregation):
+ *
+ *   W2 == NULL:  out[N,F]  = act( aggregate(X) + bias[F] )          any F, any f_chunk
+ *   W2 != NULL:  out[N,H2] = act( aggregate(X) W2[F,H2] + bias[H2] )  F <= GNNAGG_FUSED_MAX_ROW
+ *
+ * so that a layer act(A (X W) + b) is gnnagg_combine followed by this call with no further pass over the
+ * result, and a layer act((A X) W2 + b) at a hidden width is this call alone: the aggregated row is
+ * multiplied while it is still in the workgroup's LDS.  aggregate(X) is the value gnnagg_aggregate_ws
+ * returns (rounded to fp32 once).  With W2 the F products and the bias are summed in fp64 and rounded
+ * once, as in gnnagg_combine; without W2 the bias is added in fp32.  act is max(0, .) for relu == 1 and
+ * the identity for relu == 0.
+ *
+ *   W2     [F,H2] row-major fp32, or NULL (then H2 must be 0); H2 <= GNNAGG_FUSED_MAX_COLS
+ *   bias   fp32, as long as a row of out, or NULL
+ *   out    [N,F] or [N,H2], out_dtype GNNAGG_F32 or GNNAGG_BF16 (rounded to nearest even after act)
+ *   f_chunk  as in gnnagg_aggregate; with W2 the row is contracted whole, so 0, >= F or
+ *          GNNAGG_F_CHUNK_AUTO only (anything else is GNNAGG_EINVAL)
+ *
+ * Everything else (pitches, plan, workspace protocol, splitting of very long rows) as in
+ * gnnagg_aggregate_ws.  GNNAGG_EUNSUPPORTED for W2 with F > GNNAGG_FUSED_MAX_ROW.
+ */
+#define GNNAGG_FUSED_MAX_ROW 64
+#define GNNAGG_FUSED_MAX_COLS 4096
+GNNAGG_API int gnnagg_aggregate_update(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                            const float* edge_w, const void* X, int x_dtype, int64_t x_pitch, int32_t F,
+                            int32_t f_chunk, const float* W2, int32_t H2, const float* bias, int relu, void* out,
+                            int out_dtype, int64_t out_pitch, const int32_t* row_order, const int64_t* class_off,
+                            void* workspace, size_t* workspace_bytes, void* stream);
+
 /* Row pitch (in elements) that starts every row of an [N,F] matrix of the given type on a 128-byte line
  * boundary, or on a power-of-two fraction of a line for rows shorter than one (host arithmetic only;
  * 0 for invalid arguments). */
@@ -213,6 +246,16 @@ GNNAGG_API int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype, int64_
  *              or more, the partial softmax states of their pieces (such rows are split over
  *              workgroups as in gnnagg_aggregate_ws and finished by two small kernels).  Its size
  *              therefore depends on class_off: query it with the plan the call will use.
+ *              With alpha == NULL and 4, 8 or 16 channels per head both scores of an edge are recomputed
+ *              in registers from the feature rows: the call is then a single kernel launch and leaves
+ *              the score arrays untouched.
+ *
+ * Precision.  Scores are summed in fp64 and rounded to fp32, the logit s_src + s_dst and the LeakyReLU are
+ * fp32 operations, and exp(logit - reference) uses the hardware exponential (relative error about
+ * 1e-7 * |argument| + 2e-7), while denominators and weighted sums are carried in fp64.  The result is
+ * within 1e-6 + 1e-5 |r| of the fp64 definition as long as the logits of a row stay within about +-16
+ * (scores of a few units, as attention vectors of standard deviation 0.1 give); the error grows in
+ * proportion to the largest |logit| (ulp of the fp32 logit), about 1e-5 relative at |logit| = 100.
  */
 GNNAGG_API int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* H,
                          const float* a_src, const float* a_dst, int32_t heads, int32_t C,

@@ -59,6 +59,9 @@ def load_library():
         lib.gnnagg_aggregate_ws.restype = ci
         lib.gnnagg_aggregate_ws.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, vp, ci, i64, i32, i32, vp, vp, vp, szp,
                                             vp]
+        lib.gnnagg_aggregate_update.restype = ci
+        lib.gnnagg_aggregate_update.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, i32, i32, vp, i32, vp, ci, vp, ci,
+                                                i64, vp, vp, vp, szp, vp]
         lib.gnnagg_row_pitch.restype = i64
         lib.gnnagg_row_pitch.argtypes = [i32, ci]
         lib.gnnagg_gat_attention.restype = ci
@@ -279,6 +282,50 @@ def gnnagg_aggregate(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w
                                   _dev(out, None, "out"), F32 if out.dtype == torch.float32 else BF16, F, f_chunk,
                                   order, class_off, _stream(stream))
         _check("gnnagg_aggregate", rc)
+    return out
+
+
+def gnnagg_aggregate_update(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w: Optional[torch.Tensor],
+                            X: torch.Tensor, W2: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None,
+                            relu: bool = False, out: Optional[torch.Tensor] = None, f_chunk: int = 0,
+                            plan: Optional[RowPlan] = None, stream=None,
+                            workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """out = act(aggregate(X) + bias) ([N,F]) or, with W2 [F,H2], act(aggregate(X) @ W2 + bias) ([N,H2]) in the
+    aggregation kernels themselves; X and out may be row-pitched views."""
+    lib = load_library()
+    if X.dim() != 2:
+        raise ValueError("X must be [N, F]")
+    N, F = int(X.shape[0]), int(X.shape[1])
+    if rowptr.shape[0] != N + 1:
+        raise ValueError("rowptr must have N+1 entries")
+    H2 = 0
+    if W2 is not None:
+        if W2.dim() != 2 or W2.shape[0] != F:
+            raise ValueError("W2 must be [F, H2]")
+        H2 = int(W2.shape[1])
+    cols = H2 if W2 is not None else F
+    if bias is not None and tuple(bias.shape) != (cols,):
+        raise ValueError("bias must have one entry per output column")
+    if out is None:
+        out = torch.empty((N, cols), dtype=torch.float32, device=X.device)
+    elif tuple(out.shape) != (N, cols):
+        raise ValueError("out must be [N, %d]" % cols)
+    order, class_off = _plan_args(plan, N)
+    x_pitch, out_pitch = int(X.stride(0)) if N > 1 else F, int(out.stride(0)) if N > 1 else cols
+    need = gnnagg_aggregate_workspace_bytes(N, F, plan)
+    own = workspace is None and need > 0
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device) if need > 0 else _token(X.device)
+    have = ctypes.c_size_t(workspace.numel() * workspace.element_size())
+    rc = lib.gnnagg_aggregate_update(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
+                                     _dev(edge_w, torch.float32, "edge_w"), _rows(X, "X"), _x_dtype(X), x_pitch, F,
+                                     f_chunk, _dev(W2, torch.float32, "W2"), H2, _dev(bias, torch.float32, "bias"),
+                                     int(bool(relu)), _rows(out, "out"),
+                                     F32 if out.dtype == torch.float32 else BF16, out_pitch, order, class_off,
+                                     _dev(workspace), ctypes.byref(have), _stream(stream))
+    _check("gnnagg_aggregate_update", rc)
+    if own:
+        workspace.record_stream(torch.cuda.current_stream() if stream is None else stream)
     return out
 
 

@@ -41,8 +41,20 @@ struct AggArgs {
   int32_t mean;
   uint32_t lds_per_workgroup;  // host only: LDS each workgroup should occupy (0 = no cap)
   double* ws;                  // partial results of split rows: [slot][F] (null: no row is split)
+  // Update step at the store (Algorithm 1: Update follows Aggregate): y = act(a + bias), or with W2
+  // (kernels built with FUSE only) y = act(a W2 + bias) on the aggregated row a while it is still on chip
+  const float* bias;  // [F], or [H2] with W2; null: none
+  const float* W2;    // [F, H2] row-major; null: no fused dense layer
+  int32_t H2;
+  int32_t relu;
   SegTable segs;
 };
+
+// act(a + b) for the store: one fp32 addition (correctly rounded), then the activation
+__device__ inline float update_bias_act(float a, const float* __restrict__ bias, int64_t col, int relu) {
+  float y = bias ? a + bias[col] : a;
+  return (relu && !(y > 0.0f)) ? 0.0f : y;
+}
 
 // float bits <-> integer key whose signed order is the float order with
 // -0 below +0 (the map is its own inverse)
@@ -164,9 +176,12 @@ struct AggAcc {
   }
 };
 
-template <typename T, int OPK, int VEC, int MODE>
+template <typename T, int OPK, int VEC, int MODE, bool FUSE>
 __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
   __shared__ double lds[(kWavesPerBlock - 1) * kWave * VEC];
+  // FUSE: the aggregated rows of this workgroup (fp32, at most 256 lanes x VEC columns) and their row ids
+  __shared__ float tile[FUSE ? kBlock * VEC : 1];
+  __shared__ int32_t tile_row[FUSE ? kBlock : 1];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
 
   const LaneRole role = lane_role(a.sl, a.segs, blockIdx.x, tid);
@@ -216,8 +231,42 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
     float res[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) res[k] = st.result(k, deg, a.mean != 0);
-    if (a.out_bf16) store_row_bf16<VEC>(static_cast<uint16_t*>(a.out) + r * a.out_pitch + col, res);
-    else store_row<VEC>(static_cast<float*>(a.out) + r * a.out_pitch + col, res);
+    if constexpr (FUSE) {
+      // one slice, one chunk, columns [0, F): park the row for the dense layer below
+      const int lrow = hub ? 0 : (wv << (6 - role.L)) + (lane >> role.L);
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) tile[lrow * (int)a.F + col + k] = res[k];
+    } else {
+      if (a.bias || a.relu) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) res[k] = update_bias_act(res[k], a.bias, col + k, a.relu);
+      }
+      if (a.out_bf16) store_row_bf16<VEC>(static_cast<uint16_t*>(a.out) + r * a.out_pitch + col, res);
+      else store_row<VEC>(static_cast<float*>(a.out) + r * a.out_pitch + col, res);
+    }
+  }
+  if constexpr (FUSE) {
+    // y[h] = act(sum_f a[f] W2[f, h] + bias[h]) for the rows parked above: fp64 FMAs in column order,
+    // one rounding; thread t takes (row t / H2, column t % H2), so W2 and out are read and written in runs
+    if (role.split_log2 > 0) return;  // pieces of a split row: the merge kernel finishes the row
+    const int rows_here = hub ? 1 : (kWavesPerBlock << (6 - role.L));
+    if (role.ng == 0 && col == 0 && col_ok) {
+      const int lrow = hub ? 0 : (wv << (6 - role.L)) + (lane >> role.L);
+      tile_row[lrow] = row_ok ? (int32_t)r : -1;
+    }
+    __syncthreads();
+    const int F = (int)a.F, H2 = a.H2;
+    for (int t = tid; t < rows_here * H2; t += kBlock) {
+      const int lrow = t / H2, h = t - lrow * H2;
+      const int64_t rr = tile_row[lrow];
+      if (rr < 0) continue;
+      double y = 0.0;
+      for (int f = 0; f < F; ++f) y = __builtin_fma((double)tile[lrow * F + f], (double)a.W2[f * H2 + h], y);
+      if (a.bias) y += (double)a.bias[h];  // like gnnagg_combine: bias joins the fp64 sum, one rounding
+      const float res = update_bias_act((float)y, nullptr, h, a.relu);
+      if (a.out_bf16) static_cast<uint16_t*>(a.out)[rr * a.out_pitch + h] = (uint16_t)bf16_bits(res);
+      else static_cast<float*>(a.out)[rr * a.out_pitch + h] = res;
+    }
   }
 }
 
@@ -230,6 +279,9 @@ struct MergeArgs {
   int64_t F, out_pitch;
   int64_t rows;  // split rows in all runs together
   int32_t out_bf16, mean, nrun;
+  const float* bias;  // the Update step, as in AggArgs
+  const float* W2;
+  int32_t H2, relu;
   Seg run[kMaxSplitSeg];
 };
 
@@ -257,19 +309,68 @@ __global__ __launch_bounds__(kBlock) void split_merge_kernel(const MergeArgs a) 
     else o.acc[0] = p[q * a.F];
     st.merge(o);
   }
-  const float res = st.result(0, deg, a.mean != 0);
+  const float res = update_bias_act(st.result(0, deg, a.mean != 0), a.bias, col, a.relu);
   if (a.out_bf16) static_cast<uint16_t*>(a.out)[r * a.out_pitch + col] = (uint16_t)bf16_bits(res);
   else static_cast<float*>(a.out)[r * a.out_pitch + col] = res;
 }
 
-template <typename T, int OPK, int VEC, int MODE>
-int launch_one(const AggArgs& a, uint64_t grid, hipStream_t stream) {
+// The same for a call with a fused dense layer: one thread per (split row, output column h) folds the
+// pieces of every input column in piece order, rounds the aggregate to fp32 and contracts it with W2.
+template <int OPK>
+__global__ __launch_bounds__(kBlock) void split_merge_fused_kernel(const MergeArgs a) {
+  const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (t >= a.rows * a.H2) return;
+  int64_t i = t / a.H2;
+  const int64_t h = t - i * a.H2;
+  int k = 0;
+  while (k + 1 < a.nrun && i >= (int64_t)a.run[k].row_end - a.run[k].row_begin) {
+    i -= (int64_t)a.run[k].row_end - a.run[k].row_begin;
+    ++k;
+  }
+  const Seg run = a.run[k];
+  const int64_t r = a.order[run.row_begin + i];
+  const int64_t deg = a.rowptr[r + 1] - a.rowptr[r];
+  const int64_t pieces = (int64_t)1 << run.split_log2;
+  const double* p = a.ws + ((int64_t)run.ws_begin + i * pieces) * a.F;
+  double y = 0.0;
+  for (int64_t f = 0; f < a.F; ++f) {
+    State<OPK, 1> st;
+    st.init();
+    for (int64_t q = 0; q < pieces; ++q) {
+      State<OPK, 1> o;
+      if constexpr (OPK == OPK_MAX) o.key[0] = (int32_t)p[q * a.F + f];
+      else o.acc[0] = p[q * a.F + f];
+      st.merge(o);
+    }
+    y = __builtin_fma((double)st.result(0, deg, a.mean != 0), (double)a.W2[f * a.H2 + h], y);
+  }
+  if (a.bias) y += (double)a.bias[h];
+  const float res = update_bias_act((float)y, nullptr, h, a.relu);
+  if (a.out_bf16) static_cast<uint16_t*>(a.out)[r * a.out_pitch + h] = (uint16_t)bf16_bits(res);
+  else static_cast<float*>(a.out)[r * a.out_pitch + h] = res;
+}
+
+template <typename T, int OPK, int VEC, int MODE, bool FUSE>
+int launch_fused_or_not(const AggArgs& a, uint64_t grid, hipStream_t stream) {
   // Unused dynamic LDS is how the number of resident workgroups per compute unit is capped (see
   // resident_workgroup_cap): a workgroup that claims 1/k of the LDS leaves room for k of them.
   const size_t static_lds = sizeof(double) * (kWavesPerBlock - 1) * kWave * VEC;
   const size_t dyn_lds = a.lds_per_workgroup > static_lds ? a.lds_per_workgroup - static_lds : 0;
-  hipLaunchKernelGGL((aggregate_kernel<T, OPK, VEC, MODE>), dim3((unsigned)grid), dim3(kBlock), dyn_lds, stream, a);
+  hipLaunchKernelGGL((aggregate_kernel<T, OPK, VEC, MODE, FUSE>), dim3((unsigned)grid), dim3(kBlock), dyn_lds, stream,
+                     a);
   return hipGetLastError() == hipSuccess ? GNNAGG_OK : GNNAGG_EDEVICE;
+}
+
+// A fused dense layer needs the whole aggregated row in one workgroup: rows of at most 64 columns, i.e.
+// slices of at most 16 lanes - never the wave-wide kernel.
+template <typename T, int OPK, int VEC, int MODE>
+int launch_one(const AggArgs& a, uint64_t grid, hipStream_t stream) {
+  if constexpr (MODE != MODE_WAVE) {
+    if (a.W2) return launch_fused_or_not<T, OPK, VEC, MODE, true>(a, grid, stream);
+  } else {
+    if (a.W2) return GNNAGG_EUNSUPPORTED;
+  }
+  return launch_fused_or_not<T, OPK, VEC, MODE, false>(a, grid, stream);
 }
 
 // Slices wider than four lanes only occur with the widest per-lane vector (16 bytes of input), so the
@@ -309,7 +410,15 @@ using namespace gnnagg;
 
 namespace {
 
-// Argument checks shared by the two aggregation entry points; GNNAGG_OK with *nothing = true means
+// The Update step of a call (all null / zero: none).
+struct Update {
+  const float* bias = nullptr;
+  const float* W2 = nullptr;
+  int32_t H2 = 0;
+  int32_t relu = 0;
+};
+
+// Argument checks shared by the aggregation entry points; GNNAGG_OK with *nothing = true means
 // there is nothing to do.
 int check_aggregate_args(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* edge_w,
                          const void* X, int x_dtype, void* out, int out_dtype, int32_t F, int32_t f_chunk,
@@ -337,22 +446,45 @@ int check_aggregate_args(int op, int64_t N, const int64_t* rowptr, const int32_t
   return GNNAGG_OK;
 }
 
-// ws == nullptr: no row is split.  Otherwise ws holds segs.ws_slots * F doubles.
+// Pitches and plan of the calls that take them; the workspace size a plan asks for (0: no row is split).
+int check_pitches_and_plan(int64_t N, int32_t F, int32_t out_cols, int64_t* x_pitch, int64_t* out_pitch,
+                           const int32_t* row_order, const int64_t* class_off, size_t* need) {
+  if (N < 0 || F <= 0 || out_cols <= 0) return GNNAGG_EINVAL;
+  if (*x_pitch == 0) *x_pitch = F;
+  if (*out_pitch == 0) *out_pitch = out_cols;
+  if (*x_pitch < F || *out_pitch < out_cols || *x_pitch > (1ll << 40) || *out_pitch > (1ll << 40))
+    return GNNAGG_EINVAL;
+  if ((row_order == nullptr) != (class_off == nullptr)) return GNNAGG_EINVAL;
+  if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
+  SegTable probe;
+  int rc = build_segments(class_off, N, 6, true, &probe);  // the split runs do not depend on the slice width
+  if (rc != GNNAGG_OK) return rc;
+  *need = (size_t)probe.ws_slots * (size_t)F * sizeof(double);
+  return GNNAGG_OK;
+}
+
+// ws == nullptr: no row is split.  Otherwise ws holds segs.ws_slots * F doubles.  Everything a call
+// needs on the host lives on the stack: nothing is allocated, on the host or on the device.
 int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* edge_w,
                    const void* X, int x_dtype, int64_t x_pitch, void* out, int out_dtype, int64_t out_pitch,
                    int32_t F, int32_t f_chunk, const int32_t* row_order, const int64_t* class_off, double* ws,
-                   hipStream_t stream) {
+                   const Update& up, hipStream_t stream) {
   const size_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
   const bool rows_on_lines = ((uintptr_t)X % 128) == 0 && ((uint64_t)x_pitch * xs) % 128 == 0;
+  if (up.W2) f_chunk = 0;  // the dense layer contracts whole rows
   if (f_chunk == GNNAGG_F_CHUNK_AUTO) f_chunk = auto_f_chunk(N, F, (int)xs, rows_on_lines, class_off);
-  std::vector<SliceLaunch> launches;
+  LaunchList launches;
   const bool capped = resident_workgroup_cap(class_off, N, 6, kWave, true) > 0;  // dense graph: caps in play
   plan_columns(F, f_chunk, (int)(16 / xs), 0, rows_on_lines ? (int)(128 / xs) : 0, capped, &launches);
+  if (launches.overflow || launches.empty()) return GNNAGG_EUNSUPPORTED;
+  if (up.W2 && (launches.size() != 1 || launches[0].n_sub != 1 || launches[0].n_chunks != 1 ||
+                launches[0].g_log2 > 4))
+    return GNNAGG_EUNSUPPORTED;  // cannot happen for F <= 64
   const int opk = (op == GNNAGG_WSUM) ? OPK_WSUM : (op == GNNAGG_MAX ? OPK_MAX : OPK_SUM);
 
   // build and validate every launch before the first one is enqueued
-  std::vector<AggArgs> args(launches.size());
-  std::vector<uint64_t> grids(launches.size());
+  AggArgs args[kMaxLaunches];
+  uint64_t grids[kMaxLaunches];
   for (size_t k = 0; k < launches.size(); ++k) {
     AggArgs& a = args[k];
     a.rowptr = rowptr;
@@ -369,6 +501,10 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
     a.sl = launches[k];
     a.mean = (op == GNNAGG_MEAN);
     a.ws = ws;
+    a.bias = up.bias;
+    a.W2 = up.W2;
+    a.H2 = up.H2;
+    a.relu = up.relu;
     a.lds_per_workgroup =
         lds_claim(resident_workgroup_cap(class_off, N, a.sl.g_log2, active_lanes_per_wave(a.sl), opk == OPK_WSUM));
     int rc = build_segments(class_off, N, a.sl.g_log2, ws != nullptr, &a.segs);
@@ -381,7 +517,7 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
                                      : launch_op<bf16_t>(opk, args[k], grids[k], stream);
     if (rc != GNNAGG_OK) return rc;
   }
-  if (ws && !args.empty() && args[0].segs.ws_slots > 0) {
+  if (ws && args[0].segs.ws_slots > 0) {
     // the split runs are the same in every launch: they depend on the degree classes only
     MergeArgs m;
     m.rowptr = rowptr;
@@ -392,6 +528,10 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
     m.out_pitch = out_pitch;
     m.out_bf16 = (out_dtype == GNNAGG_BF16);
     m.mean = (op == GNNAGG_MEAN);
+    m.bias = up.bias;
+    m.W2 = up.W2;
+    m.H2 = up.H2;
+    m.relu = up.relu;
     m.nrun = 0;
     m.rows = 0;
     const SegTable& st = args[0].segs;
@@ -401,10 +541,16 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
       m.run[m.nrun++] = st.seg[k];
       m.rows += (int64_t)st.seg[k].row_end - st.seg[k].row_begin;
     }
-    const int64_t blocks = ceil_div(m.rows * (int64_t)F, kBlock);
+    const int64_t blocks = ceil_div(m.rows * (int64_t)(up.W2 ? up.H2 : F), kBlock);
     if (blocks > 0x7fffffffll) return GNNAGG_EUNSUPPORTED;
-    if (opk == OPK_MAX) hipLaunchKernelGGL(split_merge_kernel<OPK_MAX>, dim3((unsigned)blocks), dim3(kBlock), 0, stream, m);
-    else hipLaunchKernelGGL(split_merge_kernel<OPK_SUM>, dim3((unsigned)blocks), dim3(kBlock), 0, stream, m);
+    const dim3 grid((unsigned)blocks), block(kBlock);
+    if (up.W2) {
+      if (opk == OPK_MAX) hipLaunchKernelGGL(split_merge_fused_kernel<OPK_MAX>, grid, block, 0, stream, m);
+      else hipLaunchKernelGGL(split_merge_fused_kernel<OPK_SUM>, grid, block, 0, stream, m);
+    } else {
+      if (opk == OPK_MAX) hipLaunchKernelGGL(split_merge_kernel<OPK_MAX>, grid, block, 0, stream, m);
+      else hipLaunchKernelGGL(split_merge_kernel<OPK_SUM>, grid, block, 0, stream, m);
+    }
     if (hipGetLastError() != hipSuccess) return GNNAGG_EDEVICE;
   }
   return GNNAGG_OK;
@@ -421,7 +567,7 @@ extern "C" int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const 
                                 class_off, &nothing);
   if (rc != GNNAGG_OK || nothing) return rc;
   return aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, F, out, out_dtype, F, F, f_chunk, row_order,
-                        class_off, nullptr, (hipStream_t)stream_);
+                        class_off, nullptr, Update(), (hipStream_t)stream_);
 }
 
 extern "C" int gnnagg_aggregate_ws(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
@@ -430,16 +576,9 @@ extern "C" int gnnagg_aggregate_ws(int op, int64_t N, const int64_t* rowptr, con
                                    const int32_t* row_order, const int64_t* class_off, void* workspace,
                                    size_t* workspace_bytes, void* stream_) {
   if (!workspace_bytes) return GNNAGG_ENULL;
-  if (N < 0 || F <= 0) return GNNAGG_EINVAL;
-  if (x_pitch == 0) x_pitch = F;
-  if (out_pitch == 0) out_pitch = F;
-  if (x_pitch < F || out_pitch < F || x_pitch > (1ll << 40) || out_pitch > (1ll << 40)) return GNNAGG_EINVAL;
-  if ((row_order == nullptr) != (class_off == nullptr)) return GNNAGG_EINVAL;
-  if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
-  SegTable probe;
-  int rc = build_segments(class_off, N, 6, true, &probe);  // the split runs do not depend on the slice width
+  size_t need = 0;
+  int rc = check_pitches_and_plan(N, F, F, &x_pitch, &out_pitch, row_order, class_off, &need);
   if (rc != GNNAGG_OK) return rc;
-  const size_t need = (size_t)probe.ws_slots * (size_t)F * sizeof(double);
   if (!workspace) {
     *workspace_bytes = need;
     return GNNAGG_OK;
@@ -450,7 +589,41 @@ extern "C" int gnnagg_aggregate_ws(int op, int64_t N, const int64_t* rowptr, con
                             class_off, &nothing);
   if (rc != GNNAGG_OK || nothing) return rc;
   return aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, x_pitch, out, out_dtype, out_pitch, F, f_chunk,
-                        row_order, class_off, need > 0 ? static_cast<double*>(workspace) : nullptr,
+                        row_order, class_off, need > 0 ? static_cast<double*>(workspace) : nullptr, Update(),
+                        (hipStream_t)stream_);
+}
+
+extern "C" int gnnagg_aggregate_update(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                                       const float* edge_w, const void* X, int x_dtype, int64_t x_pitch,
+                                       int32_t F, int32_t f_chunk, const float* W2, int32_t H2, const float* bias,
+                                       int relu, void* out, int out_dtype, int64_t out_pitch,
+                                       const int32_t* row_order, const int64_t* class_off, void* workspace,
+                                       size_t* workspace_bytes, void* stream_) {
+  if (!workspace_bytes) return GNNAGG_ENULL;
+  if (relu != 0 && relu != 1) return GNNAGG_EINVAL;
+  if (W2 ? (H2 <= 0 || H2 > GNNAGG_FUSED_MAX_COLS) : (H2 != 0)) return GNNAGG_EINVAL;
+  if (W2 && F > 0 && F > GNNAGG_FUSED_MAX_ROW) return GNNAGG_EUNSUPPORTED;
+  if (W2 && f_chunk > 0 && f_chunk < F) return GNNAGG_EINVAL;  // the dense layer contracts whole rows
+  size_t need = 0;
+  int rc = check_pitches_and_plan(N, F, W2 ? H2 : F, &x_pitch, &out_pitch, row_order, class_off, &need);
+  if (rc != GNNAGG_OK) return rc;
+  if (!workspace) {
+    *workspace_bytes = need;
+    return GNNAGG_OK;
+  }
+  if (*workspace_bytes < need || ((uintptr_t)workspace & 255u)) return GNNAGG_EWORKSPACE;
+  bool nothing;
+  rc = check_aggregate_args(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, f_chunk, row_order,
+                            class_off, &nothing);
+  if (rc != GNNAGG_OK || nothing) return rc;
+  if ((W2 && ((uintptr_t)W2 % 4)) || (bias && ((uintptr_t)bias % 4))) return GNNAGG_EINVAL;
+  Update up;
+  up.bias = bias;
+  up.W2 = W2;
+  up.H2 = W2 ? H2 : 0;
+  up.relu = relu;
+  return aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, x_pitch, out, out_dtype, out_pitch, F, f_chunk,
+                        row_order, class_off, need > 0 ? static_cast<double*>(workspace) : nullptr, up,
                         (hipStream_t)stream_);
 }
 

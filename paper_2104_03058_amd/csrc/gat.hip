@@ -28,7 +28,8 @@ struct GatArgs {
   const int32_t* colidx;
   const float* H;
   const float* a_src;
-  const float* s_src;
+  const float* a_dst;
+  const float* s_src;  // score arrays; both null when every score is recomputed in registers (LH > 0, no alpha)
   const float* s_dst;
   float* alpha;
   float* out;
@@ -219,7 +220,20 @@ __global__ __launch_bounds__(kBlock) void gat_aggregate_kernel(const GatArgs a) 
   acc.s_src_h = a.s_src + head;
   acc.heads = a.heads;
   acc.slope = a.slope;
-  acc.sd = row_ok ? a.s_dst[r * a.heads + head] : 0.0f;
+  if (LH > 0 && !a.s_dst) {
+    // the destination's score from its own feature row, summed in the order of gat_scores_kernel (the lanes
+    // of a head hold the same row and run together; a lane without a row computes on row 0 and drops it)
+    float hv[VEC];
+    unpack(load_raw<float, VEC>(a.H + r * HC + col), hv);
+    double p = 0.0;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) p = __builtin_fma((double)a.a_dst[col + k], (double)hv[k], p);
+    if constexpr (LH >= 2) p += quad_exchange<kQuadXor1>(p);
+    if constexpr (LH >= 4) p += quad_exchange<kQuadXor2>(p);
+    acc.sd = (float)p;
+  } else {
+    acc.sd = row_ok ? a.s_dst[r * a.heads + head] : 0.0f;
+  }
   const float sd = acc.sd;
   const int64_t nnz = (MODE == MODE_NARROW) ? a.rowptr[a.N] : 0;
   gather_row<MODE>(acc, a.colidx, nullptr, e0, e1, ng, g, role.L, col_ok, lane, nnz);
@@ -433,18 +447,26 @@ extern "C" int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
     return GNNAGG_EINVAL;
   if (out == H) return GNNAGG_EINVAL;
 
-  std::vector<SliceLaunch> launches;
+  LaunchList launches;
   plan_columns(F, f_chunk, 4, C, 0, false, &launches);
-  std::vector<GatArgs> args(launches.size());
-  std::vector<uint64_t> grids(launches.size());
+  if (launches.overflow || launches.empty()) return GNNAGG_EUNSUPPORTED;
+  // Heads of 4, 8 or 16 channels: both scores of an edge are recomputed from the row pieces the lanes hold,
+  // so without alpha (whose second pass reads the score arrays) the score kernel and its arrays drop out
+  // and the call is a single launch.
+  bool need_scores = alpha != nullptr;
+  for (size_t k = 0; k < launches.size(); ++k)
+    if (!lanes_per_head_fused(launches[k], C)) need_scores = true;
+  GatArgs args[kMaxLaunches];
+  uint64_t grids[kMaxLaunches];
   for (size_t k = 0; k < launches.size(); ++k) {
     GatArgs& a = args[k];
     a.rowptr = rowptr;
     a.colidx = colidx;
     a.H = H;
     a.a_src = a_src;
-    a.s_src = s_src;
-    a.s_dst = s_dst;
+    a.a_dst = a_dst;
+    a.s_src = need_scores ? s_src : nullptr;
+    a.s_dst = need_scores ? s_dst : nullptr;
     a.alpha = alpha;
     a.out = out;
     a.order = row_order;
@@ -466,9 +488,11 @@ extern "C" int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
   int32_t grp = C;
   for (size_t k = 0; k < launches.size(); ++k)
     if (lanes_per_head_fused(launches[k], C)) grp = 4;
-  hipLaunchKernelGGL(gat_scores_kernel, dim3((unsigned)ceil_div(n_vh, kBlock)), dim3(kBlock), 0, stream, H, a_src,
-                     a_dst, n_vh, heads, C, grp, s_src, s_dst);
-  GNNAGG_HIP_TRY(hipGetLastError());
+  if (need_scores) {
+    hipLaunchKernelGGL(gat_scores_kernel, dim3((unsigned)ceil_div(n_vh, kBlock)), dim3(kBlock), 0, stream, H, a_src,
+                       a_dst, n_vh, heads, C, grp, s_src, s_dst);
+    GNNAGG_HIP_TRY(hipGetLastError());
+  }
   for (size_t k = 0; k < launches.size(); ++k) {
     int rc;
     switch (args[k].sl.vec) {

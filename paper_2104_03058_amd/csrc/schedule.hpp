@@ -8,8 +8,6 @@
 // the paper's chunk-outer / vertex-inner order and the rows of X touched at
 // any time are restricted to the current chunk's columns.
 #pragma once
-#include <vector>
-
 #include "common.hpp"
 
 namespace gnnagg {
@@ -48,6 +46,25 @@ struct SegTable {
 // A lane owns vec consecutive columns; 2^g_log2 lanes span one slice.
 struct SliceLaunch {
   int32_t c_begin, chunk_stride, chunk_w, n_chunks, sub_w, n_sub, vec, g_log2;
+};
+
+// The launches of one call: a fixed-capacity list, so that planning a call touches no heap (a chunk
+// yields at most two groups of columns, a group at most one sliver group, a group at most two launches).
+constexpr int kMaxLaunches = 16;
+struct LaunchList {
+  SliceLaunch v[kMaxLaunches];
+  int n = 0;
+  bool overflow = false;
+  void clear() { n = 0; overflow = false; }
+  void push_back(const SliceLaunch& s) {
+    if (n < kMaxLaunches) v[n++] = s;
+    else overflow = true;
+  }
+  size_t size() const { return (size_t)n; }
+  bool empty() const { return n == 0; }
+  const SliceLaunch& operator[](size_t k) const { return v[k]; }
+  const SliceLaunch* begin() const { return v; }
+  const SliceLaunch* end() const { return v + n; }
 };
 
 // What one thread of a launch does: which row (position in the plan), which
@@ -140,16 +157,16 @@ inline int pow2_ceil_log2(int64_t x) {
 // boundary, else 0; tail_launch asks for a separate launch for a narrower last
 // slice (worth its launch only where the resident-workgroup cap is in play).
 inline void plan_columns(int32_t F, int32_t f_chunk, int max_vec, int vec_multiple, int line_cols,
-                         bool tail_launch, std::vector<SliceLaunch>* out) {
+                         bool tail_launch, LaunchList* out) {
   out->clear();
   const int32_t width = (f_chunk <= 0 || f_chunk >= F) ? F : f_chunk;
   struct Group { int32_t c_begin, n_chunks, chunk_w; };
-  std::vector<Group> groups;
-  if (F / width > 0) groups.push_back({0, F / width, width});
-  if (F % width) groups.push_back({(F / width) * width, 1, F % width});
-  while (!groups.empty()) {
-    Group gr = groups.back();
-    groups.pop_back();
+  Group groups[4];  // the full-width chunks, the narrower last chunk, and at most one sliver of the group in work
+  int n_groups = 0;
+  if (F / width > 0) groups[n_groups++] = {0, F / width, width};
+  if (F % width) groups[n_groups++] = {(F / width) * width, 1, F % width};
+  while (n_groups > 0) {
+    Group gr = groups[--n_groups];
     int vec = max_vec;
     while (vec > 1 && (vec > gr.chunk_w || (vec_multiple && vec_multiple % vec))) vec >>= 1;
     const int32_t cap = kWave * vec;
@@ -167,9 +184,8 @@ inline void plan_columns(int32_t F, int32_t f_chunk, int max_vec, int vec_multip
       n_sub = (int32_t)ceil_div(gr.chunk_w, cap);
       last = gr.chunk_w - (n_sub - 1) * sub_w;
       if (last < vec) {  // give the sliver a launch of its own with a narrower vector
-        groups.push_back({gr.c_begin + (n_sub - 1) * sub_w, gr.n_chunks, last});
-        // the sliver repeats once per chunk, chunk_stride apart: keep the stride of the parent
-        groups.back().c_begin = gr.c_begin + (n_sub - 1) * sub_w;
+        // the sliver repeats once per chunk, chunk_stride apart: it keeps the stride of the parent
+        groups[n_groups++] = {gr.c_begin + (n_sub - 1) * sub_w, gr.n_chunks, last};
         gr.chunk_w = (n_sub - 1) * sub_w;
         n_sub -= 1;
       }

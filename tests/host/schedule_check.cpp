@@ -35,8 +35,9 @@ int main(int argc, char** argv) {
     for (int k = 0; k < GNNAGG_PLAN_CLASSES; ++k) class_off[k + 1] = class_off[k] + atoll(argv[7 + k]);
     if (class_off[GNNAGG_PLAN_CLASSES] != N) { printf("FAIL class counts do not add up\n"); return 1; }
   }
-  std::vector<SliceLaunch> launches;
+  LaunchList launches;
   plan_columns(F, f_chunk, max_vec, vec_multiple, line_cols, use_plan != 0, &launches);
+  if (launches.overflow || launches.empty()) { printf("FAIL launch list overflow or empty\n"); return 1; }
   if (line_cols)
     for (const SliceLaunch& sl : launches)
       if (sl.n_sub > 1 && sl.c_begin % line_cols == 0 && (sl.n_chunks == 1 || sl.chunk_stride % line_cols == 0) &&

@@ -351,6 +351,12 @@ def check_gat(N, rp, ci, H, a_s, a_d, f_chunks=(0,), plans=(True, False), what="
                                                 plan if use_plan else None)
             assert_close(host(out), rout, what="%s out fc=%d plan=%s" % (what, fc, use_plan))
             assert_close(host(alpha), ralpha, what="%s alpha fc=%d plan=%s" % (what, fc, use_plan))
+            # without alpha, heads of 4 / 8 / 16 channels run as one launch that recomputes both scores in
+            # registers, in the summation order of the score kernel: the same bits
+            _, out2 = g.gnnagg_gat_attention(d_rp, d_ci, d_H, d_as, d_ad, 0.2, False, True, fc,
+                                             plan if use_plan else None)
+            assert_close(host(out2), rout, what="%s out (no alpha) fc=%d plan=%s" % (what, fc, use_plan))
+            assert_bits(host(out2), host(out), "%s out with and without alpha fc=%d plan=%s" % (what, fc, use_plan))
 
 
 def test_config3_gat_mid_graph():
@@ -407,6 +413,116 @@ def test_gat_special_cases():
     # error of the weights: this case checks robustness, not the parity bar
     assert np.allclose(host(out2), rout, rtol=2e-3, atol=1e-5)
     assert np.allclose(host(alpha2), ralpha, rtol=2e-3, atol=1e-6)
+
+
+# ------------------------------------------------------------------ Update step inside the aggregation kernels
+def check_update(N, rp, ci, w, X, ops, f_chunks=(0,), bf16=False, what="", seed=0):
+    """act(aggregate(X) + bias) against the checker's aggregate followed by its Update step."""
+    F = X.shape[1]
+    d_rp, d_ci, d_X = dev(rp), dev(ci), dev(X)
+    d_w = dev(w) if w is not None else None
+    plan = g.gnnagg_plan_rows(d_rp)
+    bias = W.normal_f32((F,), seed=900 + seed)
+    d_b = dev(bias)
+    for name in ops:
+        gop, rop = OPS[name]
+        agg = oracle.aggregate(rop, rp, ci, w, X, threads=8)
+        for relu in (False, True):
+            for use_bias in (True, False):
+                ref = oracle.update(agg, bias if use_bias else None, relu)
+                for fc in f_chunks:
+                    for use_plan in (True, False):
+                        say("  update", what, name, "relu", relu, "bias", use_bias, "fc", fc, "plan", use_plan)
+                        out = torch.full((N, F), float("nan"), dtype=torch.float32, device="cuda")
+                        g.gnnagg_aggregate_update(gop, d_rp, d_ci, d_w if name == "wsum" else None, d_X, None,
+                                                  d_b if use_bias else None, relu, out, fc,
+                                                  plan if use_plan else None)
+                        tag = "%s %s relu=%s bias=%s fc=%d plan=%s" % (what, name, relu, use_bias, fc, use_plan)
+                        if name == "max" and not use_bias:
+                            assert_bits(host(out), ref, tag)
+                        else:
+                            assert_close(host(out), ref, bf16, tag)
+
+
+def test_update_bias_and_activation_at_the_store():
+    N, src, dst = W.graph("c1")
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, oracle.SELF_LOOPS | oracle.NORM_SYM, want_w=True)
+    check_update(N, rp, ci, w, W.normal_f32((N, 96), seed=901), ("wsum", "mean", "max"), f_chunks=(0, 32, 40),
+                 what="c1 F=96", seed=1)
+    check_update(N, rp, ci, w, W.normal_f32((N, 602), seed=902), ("sum",), f_chunks=(0, 64), what="c1 F=602", seed=2)
+    check_update(N, rp, ci, w, W.normal_bf16((N, 100), seed=903), ("sum", "max"), bf16=True, what="c1 bf16", seed=3)
+    # a hub row (whole workgroup) and rows split over workgroups keep the epilogue
+    N2 = 300
+    src2, dst2 = long_rows_graph(N2, [40000, 9000, 300], seed=5)
+    rp2, ci2, _, _ = oracle.build_csr(N2, src2, dst2)
+    w2 = W.normal_f32((len(ci2),), seed=12)
+    check_update(N2, rp2, ci2, w2, W.normal_f32((N2, 33), seed=904), ("wsum", "max"), f_chunks=(0, 8),
+                 what="long rows", seed=4)
+    # bf16 output: rounded after the activation
+    X = W.normal_f32((N, 40), seed=905)
+    bias = W.normal_f32((40,), seed=906)
+    ref = oracle.update(oracle.aggregate(oracle.WSUM, rp, ci, w, X), bias, True)
+    out = torch.empty((N, 40), dtype=torch.bfloat16, device="cuda")
+    g.gnnagg_aggregate_update(g.WSUM, dev(rp), dev(ci), dev(w), dev(X), None, dev(bias), True, out, 0,
+                              g.gnnagg_plan_rows(dev(rp)))
+    got = W.bf16_to_f32(host(out.view(torch.int16)).view(np.uint16))
+    assert_close(got, W.bf16_to_f32(W.f32_to_bf16(ref)), bf16=True, what="bf16 out after relu")
+
+
+@pytest.mark.parametrize("F,H2,bf16", [(32, 32, False), (16, 41, False), (64, 7, False), (8, 1, False), (1, 3, False),
+                                       (33, 64, False), (5, 300, False), (32, 16, True), (24, 40, True)])
+def test_update_fused_dense_layer_on_the_aggregated_row(F, H2, bf16):
+    """act(aggregate(X) W2 + b) in the aggregation kernel against the checker's aggregate then its dense layer:
+    every operator, short rows sharing a wavefront, a hub row, rows split over workgroups, pitched rows."""
+    N = 700
+    src, dst = long_rows_graph(N, [33000, 9000, 700, 70], seed=F * 7 + H2)
+    rp, ci, _, _ = oracle.build_csr(N, src, dst)
+    w = W.normal_f32((len(ci),), seed=13, std=0.05)
+    X = W.normal_bf16((N, F), seed=910 + F) if bf16 else W.normal_f32((N, F), seed=910 + F)
+    W2 = W.normal_f32((F, H2), seed=920 + H2, std=0.3)
+    bias = W.normal_f32((H2,), seed=930 + H2)
+    d_rp, d_ci, d_w, d_W2, d_b = dev(rp), dev(ci), dev(w), dev(W2), dev(bias)
+    plan = g.gnnagg_plan_rows(d_rp)
+    d_X = g.pitched_empty(N, F, torch.bfloat16 if bf16 else torch.float32)
+    d_X.copy_(dev(X))
+    for name in ("sum", "wsum", "mean", "max"):
+        gop, rop = OPS[name]
+        agg = oracle.aggregate(rop, rp, ci, w, X, threads=8)
+        for relu, use_bias, use_plan in ((True, True, True), (False, False, True), (False, True, False)):
+            say("  fused layer", name, "F", F, "H2", H2, "relu", relu, "bias", use_bias, "plan", use_plan)
+            ref = oracle.combine(agg, W2, bias if use_bias else None, relu, threads=8)
+            out = g.pitched_empty(N, H2, torch.float32)
+            out.fill_(float("nan"))
+            g.gnnagg_aggregate_update(gop, d_rp, d_ci, d_w if name == "wsum" else None, d_X, d_W2,
+                                      d_b if use_bias else None, relu, out, 0, plan if use_plan else None)
+            assert_close(host(out), ref, what="fused %s relu=%s bias=%s plan=%s" % (name, relu, use_bias, use_plan))
+            # the same layer as two calls: identical up to the order of the fp64 additions
+            two = g.gnnagg_combine(g.gnnagg_aggregate(gop, d_rp, d_ci, d_w if name == "wsum" else None, d_X, None, 0,
+                                                      plan if use_plan else None).contiguous(),
+                                   d_W2, d_b if use_bias else None, relu)
+            assert_close(host(out), host(two), what="fused vs two calls " + name)
+
+
+def test_update_layer_on_the_tiny_benchmark_graph_both_orders():
+    """One GCN layer act(A X W + b) on the config 1 graph: Combination first then the aggregation with the
+    epilogue, and aggregation at a hidden width with the fused dense layer; both against the checker."""
+    N, src, dst = W.graph("c1")
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, oracle.SELF_LOOPS | oracle.NORM_SYM, want_w=True)
+    d_rp, d_ci, d_w = dev(rp), dev(ci), dev(w)
+    plan = g.gnnagg_plan_rows(d_rp)
+    X = W.bernoulli_f32((N, 1433), 0.013, seed=940)
+    W1 = W.normal_f32((1433, 16), seed=941, std=0.1)
+    b1 = W.normal_f32((16,), seed=942, std=0.1)
+    hid = g.gnnagg_combine(dev(X), dev(W1))
+    out = g.gnnagg_aggregate_update(g.WSUM, d_rp, d_ci, d_w, hid, None, dev(b1), True, None, 0, plan)
+    ref_hid = oracle.combine(X, W1)
+    ref = oracle.update(oracle.aggregate(oracle.WSUM, rp, ci, w, ref_hid), b1, True)
+    assert_close(host(out), ref, what="combination first, epilogue")
+    W2 = W.normal_f32((16, 7), seed=943, std=0.3)
+    b2 = W.normal_f32((7,), seed=944)
+    out2 = g.gnnagg_aggregate_update(g.WSUM, d_rp, d_ci, d_w, out, dev(W2), dev(b2), False, None, 0, plan)
+    ref2 = oracle.combine(oracle.aggregate(oracle.WSUM, rp, ci, w, ref), W2, b2, False)
+    assert_close(host(out2), ref2, what="second layer, fused dense layer")
 
 
 # ------------------------------------------------------------------ combination (dense layer on the matrix cores)

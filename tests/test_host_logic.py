@@ -156,11 +156,41 @@ def test_argument_validation_returns_before_any_launch(lib):
     assert comb(0, None, 0, 8, None, None, 4, 0, None, None, None) == 0        # no rows: nothing to do
 
 
+def test_update_entry_point_validates_on_the_host(lib):
+    EINVAL, ENULL, EUNSUP, EWS = -1, -2, -3, -4
+    one, other = ctypes.c_void_p(4096), ctypes.c_void_p(8192)
+    need = ctypes.c_size_t(0)
+    big = ctypes.c_size_t(1 << 20)
+    upd = lib.gnnagg_aggregate_update
+
+    def call(op=0, N=100, X=one, F=8, fc=0, W2=None, H2=0, bias=None, relu=0, out=other, x_pitch=0, out_pitch=0,
+             ws=one, wsb=big):
+        return upd(op, N, one, one, one, X, 0, x_pitch, F, fc, W2, H2, bias, relu, out, 0, out_pitch, None, None, ws,
+                   ctypes.byref(wsb) if wsb is not None else None, None)
+
+    assert call(wsb=None) == ENULL
+    assert call(relu=2) == EINVAL
+    assert call(H2=5) == EINVAL                       # a width without a matrix
+    assert call(W2=one, H2=0) == EINVAL               # a matrix without a width
+    assert call(W2=one, H2=4097) == EINVAL
+    assert call(W2=one, H2=8, F=65) == EUNSUP         # the fused layer holds rows of at most 64 columns
+    assert call(W2=one, H2=8, F=64, fc=16) == EINVAL  # ... and contracts them whole
+    assert call(W2=one, H2=8, F=64, out_pitch=7) == EINVAL   # out has H2 columns
+    assert call(W2=ctypes.c_void_p(4098), H2=8) == EINVAL    # alignment
+    assert call(bias=ctypes.c_void_p(4098)) == EINVAL
+    assert call(op=9) == EINVAL
+    assert call(out=one) == EINVAL                    # out aliases X
+    assert call(ws=None, wsb=need) == 0 and need.value == 0  # size query, no plan
+    assert call(N=0, X=None, out=None) == 0
+
+
 # ------------------------------------------------------------------ launch geometry
 @pytest.fixture(scope="module")
 def checker(tmp_path_factory):
     exe = str(tmp_path_factory.mktemp("host") / "schedule_check")
-    subprocess.check_call(["g++", "-O1", "-std=c++17", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
+    # AddressSanitizer and UBSan on the host side of the scheduling code (a CPU build: no GPU code runs)
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=undefined", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
                            "-I" + os.path.join(ROOT, "include"),
                            "-I" + os.path.join(ROOT, "paper_2104_03058_amd", "csrc"),
                            os.path.join(ROOT, "tests", "host", "schedule_check.cpp"), "-o", exe])
@@ -239,7 +269,8 @@ def test_geometry_attention_lanes_stay_inside_heads(checker, heads, C, f_chunk):
 @pytest.fixture(scope="module")
 def cap_checker(tmp_path_factory):
     exe = str(tmp_path_factory.mktemp("host") / "cap_check")
-    subprocess.check_call(["g++", "-O1", "-std=c++17", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=undefined", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
                            "-I" + os.path.join(ROOT, "include"),
                            "-I" + os.path.join(ROOT, "paper_2104_03058_amd", "csrc"),
                            os.path.join(ROOT, "tests", "host", "cap_check.cpp"), "-o", exe])

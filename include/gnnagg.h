@@ -19,7 +19,7 @@
  *    as `workspace`.  Inputs and outputs must not overlap.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    gnnagg_aggregate, gnnagg_aggregate_ws, gnnagg_aggregate_update,
- *    gnnagg_gat_attention, gnnagg_combine and
+ *    gnnagg_aggregate_noalloc, gnnagg_gat_attention, gnnagg_combine and
  *    gnnagg_rank_sources only enqueue kernels on it and return (no allocation
  *    on the host or the device, no synchronisation, no memset: they can be
  *    captured in a HIP graph); gnnagg_build_csr, gnnagg_check_csr and
@@ -216,6 +216,28 @@ GNNAGG_API int gnnagg_aggregate_update(int op, int64_t N, const int64_t* rowptr,
                             int32_t f_chunk, const float* W2, int32_t H2, const float* bias, int relu, void* out,
                             int out_dtype, int64_t out_pitch, const int32_t* row_order, const int64_t* class_off,
                             void* workspace, size_t* workspace_bytes, void* stream);
+
+/*
+ * gnnagg_aggregate_ws for callers that cannot allocate device memory and have no workspace to hand over
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments
+ * without the workspace pair, same kernels, same result bit for bit.  The partial results of split rows
+ * (rows of 2^15 edges or more in the plan) go to a fixed array of GNNAGG_NOALLOC_SCRATCH_BYTES that is
+ * part of the library's code object: every GPU the library runs on holds one copy until the process
+ * ends.  The call allocates nothing, on the host or on the device.
+ *
+ *   - GNNAGG_EWORKSPACE if the plan needs more than GNNAGG_NOALLOC_SCRATCH_BYTES (the size
+ *     gnnagg_aggregate_ws reports for the same (N, F, class_off)): use gnnagg_aggregate_ws then.
+ *   - All calls on one GPU share that GPU's array: two calls whose kernels may overlap in time (different
+ *     streams, or graphs replayed concurrently) race on it.  Calls on one stream are ordered and safe.
+ *     Nothing in the array has to start at zero: every slot is written in full before it is read.
+ *   - The device of `stream` must be current.  The first call on a device that splits a row looks the
+ *     array's address up (hipGetSymbolAddress); make that call outside stream capture.
+ */
+#define GNNAGG_NOALLOC_SCRATCH_BYTES (8u << 20)
+GNNAGG_API int gnnagg_aggregate_noalloc(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                             const float* edge_w, const void* X, int x_dtype, int64_t x_pitch, void* out,
+                             int out_dtype, int64_t out_pitch, int32_t F, int32_t f_chunk,
+                             const int32_t* row_order, const int64_t* class_off, void* stream);
 
 /* Row pitch (in elements) that starts every row of an [N,F] matrix of the given type on a 128-byte line
  * boundary, or on a power-of-two fraction of a line for rows shorter than one (host arithmetic only;

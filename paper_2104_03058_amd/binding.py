@@ -62,6 +62,8 @@ def load_library():
         lib.gnnagg_aggregate_update.restype = ci
         lib.gnnagg_aggregate_update.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, i32, i32, vp, i32, vp, ci, vp, ci,
                                                 i64, vp, vp, vp, szp, vp]
+        lib.gnnagg_aggregate_noalloc.restype = ci
+        lib.gnnagg_aggregate_noalloc.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, vp, ci, i64, i32, i32, vp, vp, vp]
         lib.gnnagg_row_pitch.restype = i64
         lib.gnnagg_row_pitch.argtypes = [i32, ci]
         lib.gnnagg_gat_attention.restype = ci
@@ -326,6 +328,30 @@ def gnnagg_aggregate_update(op: int, rowptr: torch.Tensor, colidx: torch.Tensor,
     _check("gnnagg_aggregate_update", rc)
     if own:
         workspace.record_stream(torch.cuda.current_stream() if stream is None else stream)
+    return out
+
+
+def gnnagg_aggregate_noalloc(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w: Optional[torch.Tensor],
+                             X: torch.Tensor, out: torch.Tensor, f_chunk: int = 0, plan: Optional[RowPlan] = None,
+                             stream=None) -> torch.Tensor:
+    """gnnagg_aggregate into a caller's `out` with no allocation anywhere: split rows use the library's fixed
+    scratch array (raises GnnaggError with status -4 when the plan needs more than that array holds)."""
+    lib = load_library()
+    if X.dim() != 2:
+        raise ValueError("X must be [N, F]")
+    N, F = int(X.shape[0]), int(X.shape[1])
+    if rowptr.shape[0] != N + 1:
+        raise ValueError("rowptr must have N+1 entries")
+    if tuple(out.shape) != (N, F):
+        raise ValueError("out must be [N, F]")
+    order, class_off = _plan_args(plan, N)
+    x_pitch, out_pitch = int(X.stride(0)) if N > 1 else F, int(out.stride(0)) if N > 1 else F
+    rc = lib.gnnagg_aggregate_noalloc(op, N, _dev(rowptr, torch.int64, "rowptr"),
+                                      _dev(colidx, torch.int32, "colidx"), _dev(edge_w, torch.float32, "edge_w"),
+                                      _rows(X, "X"), _x_dtype(X), x_pitch, _rows(out, "out"),
+                                      F32 if out.dtype == torch.float32 else BF16, out_pitch, F, f_chunk, order,
+                                      class_off, _stream(stream))
+    _check("gnnagg_aggregate_noalloc", rc)
     return out
 
 

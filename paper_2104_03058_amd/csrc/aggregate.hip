@@ -16,6 +16,8 @@
 //   - Sums accumulate in fp64 (full rate on this chip) and are rounded to fp32
 //     once, so the result does not depend on the degree or on how the row was
 //     split; max works on order-preserving integer keys and is exact.
+#include <mutex>
+
 #include "common.hpp"
 #include "schedule.hpp"
 #include "device_utils.hpp"
@@ -408,7 +410,29 @@ int launch_op(int opk, const AggArgs& a, uint64_t grid, hipStream_t stream) {
 
 using namespace gnnagg;
 
+// Scratch of gnnagg_aggregate_noalloc: the partial results of split rows, for callers that cannot hand
+// over a workspace of their own.  One copy per GPU, at an address of its own on each; host code reaches
+// it only through the pointer hipGetSymbolAddress returns for the current device.
+static __device__ __align__(256) unsigned char scratch[GNNAGG_NOALLOC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_of_device[kMaxDevices];  // device address of `scratch` per GPU, looked up on first use
+
+int scratch_for_current_device(void** p) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GNNAGG_EDEVICE;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_of_device[dev]) {
+    void* q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return GNNAGG_EDEVICE;
+    scratch_of_device[dev] = q;
+  }
+  *p = scratch_of_device[dev];
+  return GNNAGG_OK;
+}
 
 // The Update step of a call (all null / zero: none).
 struct Update {
@@ -625,6 +649,28 @@ extern "C" int gnnagg_aggregate_update(int op, int64_t N, const int64_t* rowptr,
   return aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, x_pitch, out, out_dtype, out_pitch, F, f_chunk,
                         row_order, class_off, need > 0 ? static_cast<double*>(workspace) : nullptr, up,
                         (hipStream_t)stream_);
+}
+
+extern "C" int gnnagg_aggregate_noalloc(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                                        const float* edge_w, const void* X, int x_dtype, int64_t x_pitch,
+                                        void* out, int out_dtype, int64_t out_pitch, int32_t F, int32_t f_chunk,
+                                        const int32_t* row_order, const int64_t* class_off, void* stream_) {
+  size_t need = 0;
+  int rc = check_pitches_and_plan(N, F, F, &x_pitch, &out_pitch, row_order, class_off, &need);
+  if (rc != GNNAGG_OK) return rc;
+  if (need > (size_t)GNNAGG_NOALLOC_SCRATCH_BYTES) return GNNAGG_EWORKSPACE;  // the plan's split rows do not fit
+  bool nothing;
+  rc = check_aggregate_args(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, f_chunk, row_order,
+                            class_off, &nothing);
+  if (rc != GNNAGG_OK || nothing) return rc;
+  void* ws = nullptr;
+  if (need > 0) {
+    rc = scratch_for_current_device(&ws);
+    if (rc != GNNAGG_OK) return rc;
+  }
+  // every slot a piece owns is written in full before the merge kernel reads it: nothing to clear
+  return aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, x_pitch, out, out_dtype, out_pitch, F, f_chunk,
+                        row_order, class_off, static_cast<double*>(ws), Update(), (hipStream_t)stream_);
 }
 
 extern "C" int64_t gnnagg_row_pitch(int32_t F, int dtype) {

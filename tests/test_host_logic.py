@@ -156,7 +156,7 @@ def test_argument_validation_returns_before_any_launch(lib):
     assert comb(0, None, 0, 8, None, None, 4, 0, None, None, None) == 0        # no rows: nothing to do
 
 
-def test_update_entry_point_validates_on_the_host(lib):
+def test_update_and_no_alloc_entry_points_validate_on_the_host(lib):
     EINVAL, ENULL, EUNSUP, EWS = -1, -2, -3, -4
     one, other = ctypes.c_void_p(4096), ctypes.c_void_p(8192)
     need = ctypes.c_size_t(0)
@@ -182,6 +182,22 @@ def test_update_entry_point_validates_on_the_host(lib):
     assert call(out=one) == EINVAL                    # out aliases X
     assert call(ws=None, wsb=need) == 0 and need.value == 0  # size query, no plan
     assert call(N=0, X=None, out=None) == 0
+
+    na = lib.gnnagg_aggregate_noalloc
+    assert na(0, -1, one, one, one, one, 0, 0, other, 0, 0, 8, 0, None, None, None) == EINVAL
+    assert na(9, 10, one, one, one, one, 0, 0, other, 0, 0, 8, 0, None, None, None) == EINVAL
+    assert na(0, 10, one, one, one, one, 0, 4, other, 0, 0, 8, 0, None, None, None) == EINVAL  # pitch below F
+    assert na(0, 10, None, one, one, one, 0, 0, other, 0, 0, 8, 0, None, None, None) == ENULL
+    assert na(0, 10, one, one, one, one, 0, 0, other, 0, 0, 8, 0, one, None, None) == EINVAL   # half a plan
+    assert na(0, 0, None, None, None, None, 0, 0, None, 0, 0, 8, 0, None, None, None) == 0
+    # a plan whose split rows need more than the fixed array: 600 rows of class 16, 1024 columns
+    off = (ctypes.c_int64 * 34)()
+    for k in range(34):
+        off[k] = 0 if k <= 16 else (600 if k < 33 else 1000)
+    assert na(0, 1000, one, one, one, one, 0, 0, other, 0, 0, 1024, 0, one, ctypes.cast(off, ctypes.c_void_p),
+              None) == EWS
+    text = open(HEADER).read()
+    assert re.search(r"#define\s+GNNAGG_NOALLOC_SCRATCH_BYTES\s+\(8u << 20\)", text)
 
 
 # ------------------------------------------------------------------ launch geometry

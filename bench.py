@@ -1,21 +1,33 @@
 #!/usr/bin/env python3
 """Benchmark of the aggregation hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4-gcn] [--f-chunk C]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4-gcn] [--f-chunk C] [--also LIST]
 
-A step is one gnnagg_aggregate call (chunk addressing, gather, reduce, in-place
-concat) over the whole synthetic graph, with the CSR, the row plan and the
-features already resident in HBM.  The default workload is the dense
-232,965-vertex / 114.6 M-edge graph with 602 fp32 features and GCN weights; the
-sparse 2.4 M-vertex bf16 workload is measured after it and reported under "also".  The CSR build and the row plan are per-graph
-steps; they are timed separately and reported under "setup".  Prints one JSON
-line: edge-features/s, the HBM roofline of the aggregation kernel (algorithmic
-bytes / HIP-event time, peak 8 TB/s) and the CPU checker timed on the host
-cores on a bounded sample of destination rows of the same workload.
+A step is one library call (chunk addressing, gather, reduce, in-place concat) over the whole synthetic
+graph, with the CSR, the row plan and the features already resident in HBM.  The main workload is the dense
+232,965-vertex / 114.6 M-edge graph with 602 fp32 features and GCN weights.  The default run also measures,
+and reports under "also": the chunk-width sweeps of the two benchmark configurations that name one, the
+sparse 2.4 M-vertex bf16 workloads, attention, the hidden-width regime, Combination and whole layers, and
+first of all four gathers on uniform random graphs that pin the source rows to one level of the memory
+system (L2, Infinity Cache, HBM): their rates are the measured ceilings the other figures are set against.
+Every entry is checked against the CPU checker on sampled destination rows.  The CSR build and the row plan
+are per-graph steps, timed separately ("setup").  Prints one JSON line.
+
+Rates per entry:
+  roofline        algorithmic bytes per call / HIP-event time against the 8 TB/s HBM peak.  A gather whose
+                  rows are served by L2 exceeds that peak; "frac" above 1 says the caches work, not that HBM
+                  delivered it.
+  roofline_l2     128-byte line requests of the gather per second against the rate of the L2-resident probe.
+  roofline_fabric bytes that crossed the L2 boundary (rocprofv3 counters, taken from profiles/ when the
+                  summary there was made with these kernel sources and this configuration, else null) per
+                  second against the fastest of the beyond-L2 probes.  Infinity Cache hits and HBM reads
+                  are not separable in the counters of this chip.
 """
 from __future__ import annotations
 
 import argparse
+import glob
+import hashlib
 import json
 import os
 import sys
@@ -23,19 +35,9 @@ import time
 
 import numpy as np
 
+ROOT = os.path.dirname(os.path.abspath(__file__))
 HBM_PEAK_GBS = 8000.0
 MFMA_F64_PEAK_TFLOPS = 78.6
-
-# HBM-side bytes per aggregation call (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, summed over the call's
-# launches - a narrower last slice gets a launch of its own on dense graphs - and scaled on the copy
-# probe: see profiles/aggregate_kernel_*.txt), valid for the kernels as committed with those profiles and
-# for f_chunk = 0 only.  Set an entry to None when the kernel changes until the counters are taken again.
-MEASURED_TRAFFIC = {
-    "c4-gcn": 119.643e9,  # profiles/aggregate_kernel_c4_gcn.txt
-    "c5-sum": 13.317e9,   # profiles/aggregate_kernel_c5_sum_bf16.txt
-    "c4-gat": 14.677e9,   # profiles/gat_aggregate_kernel_c4_gat.txt
-    "c4-hid32-gcn": 6.483e9,  # profiles/aggregate_kernel_c4_hidden32_gcn.txt
-}
 
 WORKLOADS = {
     # name: (graph key, op, F, feature dtype, self loops + GCN norm)
@@ -45,6 +47,9 @@ WORKLOADS = {
     "c5-max": ("c5", "max", 100, "bf16", False),
     "c5-sum-f32": ("c5", "sum", 32, "bf16", False),
     "c5-sum-f16": ("c5", "sum", 16, "bf16", False),
+    # the same with the feature rows stored in popularity order (gnnagg_rank_sources, once per graph)
+    "c5-sum-f32-ranked": ("c5", "sum-ranked", 32, "bf16", False),
+    "c5-sum-f16-ranked": ("c5", "sum-ranked", 16, "bf16", False),
     "c2-mean": ("c2", "mean", 500, "f32", False),
     "c1-gcn": ("c1", "wsum", 1433, "f32", True),
     # attention: F = (heads, channels per head); self-loops, no GCN weights
@@ -58,313 +63,565 @@ WORKLOADS = {
     "c6-hid8-gcn": ("c6", "wsum", 8, "f32", True),
     "c6-hid32-mean": ("c6", "mean", 32, "f32", False),
     "c6-gat": ("c6", "gat", (8, 4), "f32", False),
-    # Combination (dense layer F -> H on the matrix cores), alone and as one GCN layer with Combination first
+    # Combination (dense layer F -> H on the matrix cores), alone and as one GCN layer with Combination first;
+    # "-fused": the layer's bias and ReLU applied at the store of the aggregation (gnnagg_aggregate_update)
     "c4-combine-32": ("c4", "combine", (602, 32), "f32", False),
     "c4-layer-32": ("c4", "layer", (602, 32), "f32", True),
+    "c4-layer-32-fused": ("c4", "layer-fused", (602, 32), "f32", True),
+    # second layer at the hidden width: aggregate 32 columns, then x W2 [32, 41] + bias in the same kernel
+    "c4-layer2-32-41-fused": ("c4", "agg-dense", (32, 41), "f32", True),
     # the sparse graph at hidden width 16 after Combination: rows of 64 bytes, two per line; "-ranked" stores
     # the hidden rows in popularity order (gnnagg_rank_sources + out_rows of gnnagg_combine)
     "c5-layer-16": ("c5", "layer", (100, 16), "f32", False),
     "c5-layer-16-ranked": ("c5", "layer-ranked", (100, 16), "f32", False),
+    # measurement aids: gathers on uniform random graphs whose source rows live in one level of the memory system
+    "probe-l2-line": ("u-l2", "sum", 32, "f32", False),
+    "probe-mall-line": ("u-mall", "sum", 32, "f32", False),
+    "probe-hbm-line": ("u-hbm", "sum", 32, "f32", False),
+    "probe-hbm-row": ("u-hbmw", "sum", 602, "f32", False),
 }
+PROBES = ["probe-l2-line", "probe-mall-line", "probe-hbm-line", "probe-hbm-row"]
 
-
-_GRAPHS = {}
-
-
-def graph_of(W, gkey):
-    """The synthetic graph of a workload, generated once per run."""
-    if gkey not in _GRAPHS:
-        _GRAPHS.clear()  # one graph at a time: the largest holds ~1 GB of host memory
-        _GRAPHS[gkey] = W.graph(gkey)
-    return _GRAPHS[gkey]
+# "name@W" runs workload `name` at chunk width W ("all" = one chunk): the sweeps of the benchmark configurations
+DEFAULT_ALSO = (
+    PROBES
+    + ["c4-gcn@8", "c4-gcn@16", "c4-gcn@32", "c4-gcn@64", "c4-gcn@all",
+       "c4-mean", "c4-mean@8", "c4-mean@16", "c4-mean@32", "c4-mean@64", "c4-mean@all",
+       "c4-hid32-gcn", "c4-hid8-gcn", "c4-gat", "c4-combine-32", "c4-layer-32", "c4-layer-32-fused",
+       "c4-layer2-32-41-fused",
+       "c5-sum", "c5-max", "c5-sum-f32", "c5-sum-f16", "c5-sum-f32-ranked", "c5-sum-f16-ranked",
+       "c5-layer-16", "c5-layer-16-ranked",
+       "c6-hid32-gcn", "c6-hid16-gcn", "c6-hid8-gcn", "c6-hid32-mean", "c6-gat",
+       "c2-mean", "c3-gat", "c1-gcn", "c1-gcn@16", "c1-gcn@64", "c1-gcn@all"])
+CPU_BASELINE_ALSO = {"c5-sum": 5.0, "c5-max": 5.0}     # multi-threaded checker on a bounded sample (seconds)
+SINGLE_THREAD_ALSO = {"c1-gcn", "c2-mean", "c3-gat"}    # whole graph on one thread
+CPU_CHUNK_SWEEPS = {"c1-gcn": [16, 64, 0], "c4-gcn": [8, 16, 32, 64, 0]}
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+AGGREGATE_SOURCES = ["aggregate.hip", "gather.hpp", "schedule.hpp", "device_utils.hpp", "common.hpp"]
+GAT_SOURCES = ["gat.hip", "gather.hpp", "schedule.hpp", "device_utils.hpp", "common.hpp"]
+
+
+def kernel_source_hash(files):
+    """Fingerprint of the HIP sources a kernel is built from: a traffic figure in profiles/ counts for a run
+    only if it was taken with the same kernel."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2104_03058_amd", "csrc")
+    for fn in sorted(files):
+        h.update(fn.encode())
+        h.update(open(os.path.join(d, fn), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic():
+    """Records of HBM-side traffic per library call kept in profiles/*.txt, one JSON object per line that
+    starts with 'traffic_record:' (workload, f_chunk_used, x_row_pitch, kernel_sources, kernel_source_hash,
+    fetch_bytes, write_bytes), written when the rocprofv3 counters were summarised."""
+    recs = {}
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(path, errors="replace"):
+            if line.startswith("traffic_record:"):
+                try:
+                    r = json.loads(line[len("traffic_record:"):])
+                    r["source"] = os.path.relpath(path, ROOT)
+                    recs[r["workload"]] = r
+                except (ValueError, KeyError):
+                    pass
+    return recs
+
+
 def algorithmic_bytes(nnz, N, F, x_bytes, weighted, f_chunk):
-    """Bytes the method itself has to move per call: every neighbour-row slice once per edge, the
-    index (and weight) of every edge once per chunk pass, every output element once, the row
-    pointers once per chunk pass."""
+    """Bytes the method itself has to move per call: every neighbour-row slice once per edge, the index (and
+    weight) of every edge once per chunk pass, every output element once, the row pointers once per pass."""
     P = 1 if (f_chunk <= 0 or f_chunk >= F) else -(-F // f_chunk)
     return nnz * F * x_bytes + P * nnz * (4 + (4 if weighted else 0)) + N * F * 4 + P * (N + 1) * 8
 
 
-def measure_layer(g, W, torch, workload, steps, warmup, copy_gbs):
-    """Combination (X W on the matrix cores) alone, or followed by the GCN aggregation at the hidden width."""
-    gkey, opname, (F, H), xdt, gcn = WORKLOADS[workload]
-    N, src, dst = graph_of(W, gkey)
-    X = torch.from_numpy(W.normal_f32((N, F), seed=13)).cuda()
-    Wt = torch.from_numpy(W.normal_f32((F, H), seed=16, std=0.05)).cuda()
-    hid = torch.empty((N, H), dtype=torch.float32, device="cuda")
-    out = torch.empty((N, H), dtype=torch.float32, device="cuda")
-    nnz = 0
-    ranked = opname == "layer-ranked"
-    rank = None
-    if ranked:
-        opname = "layer"
-    if opname == "layer":
-        flags = (g.SELF_LOOPS | g.NORM_SYM) if gcn else 0
-        d_rp, d_ci, d_w, _ = g.gnnagg_build_csr(N, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda(),
-                                                flags, want_w=gcn)
-        plan = g.gnnagg_plan_rows(d_rp)
-        nnz = int(d_ci.shape[0])
-        if ranked:  # per graph, like the CSR and the plan
-            rank, d_ci = g.gnnagg_rank_sources(N, d_ci)
-    aop = g.WSUM if gcn else g.SUM
-
-    def step():
-        g.gnnagg_combine(X, Wt, None, False, hid, out_rows=rank)
-        if opname == "layer":
-            g.gnnagg_aggregate(aop, d_rp, d_ci, d_w, hid, out, 0, plan)
-
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
-    kern_ms = e0.elapsed_time(e1) / steps
-    flop = 2.0 * N * F * H
-    b_alg = N * F * 4 + F * H * 4 + N * H * 4
-    if opname == "layer":
-        b_alg += algorithmic_bytes(nnz, N, H, 4, gcn, 0)
-    achieved = b_alg / (kern_ms * 1e-3) / 1e9
-    log("%s: %.3f ms per step (combination %.1f GFLOP in fp64 MFMA), %.0f GB/s algorithmic" %
-        (workload, kern_ms, flop / 1e9, achieved))
-    rec = {"metric": "one layer, Combination first" if opname == "layer" else "Combination (dense layer)",
-           "value": (float(nnz) * H if opname == "layer" else flop) / (ms_per_step * 1e-3),
-           "unit": "edge-features/s at the hidden width" if opname == "layer" else "flop/s",
-           "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-           "config": {"workload": workload, "graph": W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "H": H},
-           "cpu_baseline": None, "setup": {}}
-    if opname == "combine":  # the dense contraction: priced against the fp64 matrix-core peak
-        tf = flop / (kern_ms * 1e-3) / 1e12
-        rec["roofline"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_F64_PEAK_TFLOPS, "unit": "TFLOP/s",
-                           "frac": tf / MFMA_F64_PEAK_TFLOPS, "traffic": None, "kernel": "combine_kernel",
-                           "kernel_ms": kern_ms, "flop": flop, "algorithmic_bytes": b_alg,
-                           "algorithmic_gbs": achieved, "measured_copy_gbs": copy_gbs}
-    else:
-        rec["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                           "kernel": "combine_kernel + aggregate_kernel", "kernel_ms": kern_ms,
-                           "algorithmic_bytes": b_alg, "measured_copy_gbs": copy_gbs}
-    return rec
+def gather_lines_per_edge(F, x_bytes, pitch_elems, f_used):
+    """128-byte lines of a source row the gather asks for per edge, summed over the chunk passes, when rows
+    start on lines (or are a power-of-two fraction of one); None for other layouts."""
+    pitch_bytes = pitch_elems * x_bytes
+    if pitch_bytes % 128 and not (pitch_bytes < 128 and 128 % pitch_bytes == 0):
+        return None
+    width = F if (f_used <= 0 or f_used >= F) else f_used
+    lines, c0 = 0, 0
+    while c0 < F:
+        c1 = min(F, c0 + width)
+        lines += ((c1 * x_bytes - 1) // 128) - (c0 * x_bytes // 128) + 1
+        c0 = c1
+    return lines
 
 
-def measure(g, W, torch, workload, f_chunk, steps, warmup, cpu_baseline, cpu_seconds, copy_gbs, pitched=True):
-    """One workload: setup (CSR build, row plan), timed aggregation steps, optional CPU-checker leg."""
-    gkey, opname, F, xdt, gcn = WORKLOADS[workload]
-    if opname in ("combine", "layer", "layer-ranked"):
-        return measure_layer(g, W, torch, workload, steps, warmup, copy_gbs)
-    gat = opname == "gat"
-    heads, C = F if gat else (1, F)
-    F = heads * C
-    t0 = time.time()
-    N, src, dst = graph_of(W, gkey)
-    log("graph %s: N=%d directed edges=%d (%.1fs)" % (gkey, N, len(src), time.time() - t0))
-    t0 = time.time()
-    X = W.normal_bf16((N, F), seed=13) if xdt == "bf16" else (
-        W.bernoulli_f32((N, F), 0.013, seed=13) if gkey == "c1" else W.normal_f32((N, F), seed=13))
-    log("features [%d,%d] %s (%.1fs)" % (N, F, xdt, time.time() - t0))
+class Bench:
+    def __init__(self, g, W, torch, steps, warmup, pitched=True):
+        self.g, self.W, self.torch = g, W, torch
+        self.steps, self.warmup, self.pitched = steps, warmup, pitched
+        self.gkey = None
+        self.host = None       # (N, src, dst) of the current graph
+        self.dev_csr = {}      # flags -> dict
+        self.ref_csr = {}      # flags -> (rp, ci, w)
+        self.feat = {}         # (F, xdt, seed) -> host array
+        self.ceil = {}         # probe name -> dict(rate figures)
+        self.copy_gbs = None
+        self.traffic = measured_traffic()
+        self.threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
 
-    def dev(a):
+    # ---- inputs, generated once per graph
+    def graph(self, gkey):
+        if gkey != self.gkey:
+            self.dev_csr.clear()
+            self.ref_csr.clear()
+            self.feat.clear()
+            self.host = None
+            self.torch.cuda.empty_cache()
+            t0 = time.time()
+            self.host = self.W.graph(gkey)
+            self.gkey = gkey
+            log("graph %s: N=%d directed edges=%d (%.1fs)" % (gkey, self.host[0], len(self.host[1]), time.time() - t0))
+        return self.host
+
+    def features(self, gkey, shape, xdt, seed=13):
+        key = (shape, xdt, seed)
+        if key not in self.feat:
+            W = self.W
+            if len(self.feat) > 2:
+                self.feat.clear()
+            self.feat[key] = (W.normal_bf16(shape, seed=seed) if xdt == "bf16" else
+                              W.bernoulli_f32(shape, 0.013, seed=seed) if gkey == "c1" else
+                              W.normal_f32(shape, seed=seed))
+        return self.feat[key]
+
+    def dev(self, a):
         if a.dtype == np.uint16:
-            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
-        return torch.from_numpy(a).cuda()
+            return self.torch.from_numpy(a.view(np.int16)).cuda().view(self.torch.bfloat16)
+        return self.torch.from_numpy(a).cuda()
 
-    d_src, d_dst, d_X = dev(src), dev(dst), dev(X)
-    flags = (g.SELF_LOOPS | g.NORM_SYM) if gcn else (g.SELF_LOOPS if gat else 0)
-    # ---- per-graph setup: CSR build and row plan (timed, not part of a step)
-    g.gnnagg_build_csr(N, d_src, d_dst, flags, want_w=gcn)  # warm-up (allocator, code objects)
-    torch.cuda.synchronize()
-    t0 = time.time()
-    d_rp, d_ci, d_w, _ = g.gnnagg_build_csr(N, d_src, d_dst, flags, want_w=gcn)
-    torch.cuda.synchronize()
-    t_csr = time.time() - t0
-    t0 = time.time()
-    plan = g.gnnagg_plan_rows(d_rp)
-    torch.cuda.synchronize()
-    t_plan = time.time() - t0
-    del d_src, d_dst
-    nnz = int(d_ci.shape[0])
-    log("device CSR build %.1f ms, row plan %.1f ms, nnz=%d" % (t_csr * 1e3, t_plan * 1e3, nnz))
+    def device_csr(self, gkey, flags):
+        """CSR build and row plan on the device, timed (the second build: the first warms allocator and code)."""
+        if flags not in self.dev_csr:
+            g, torch = self.g, self.torch
+            N, src, dst = self.graph(gkey)
+            d_src, d_dst = self.dev(src), self.dev(dst)
+            want_w = bool(flags & g.NORM_SYM)
+            g.gnnagg_build_csr(N, d_src, d_dst, flags, want_w=want_w)
+            torch.cuda.synchronize()
+            t0 = time.time()
+            rp, ci, w, _ = g.gnnagg_build_csr(N, d_src, d_dst, flags, want_w=want_w)
+            torch.cuda.synchronize()
+            t_csr = time.time() - t0
+            t0 = time.time()
+            plan = g.gnnagg_plan_rows(rp)
+            torch.cuda.synchronize()
+            t_plan = time.time() - t0
+            self.dev_csr[flags] = dict(rp=rp, ci=ci, w=w, plan=plan, nnz=int(ci.shape[0]),
+                                       setup={"csr_build_ms": t_csr * 1e3, "row_plan_ms": t_plan * 1e3})
+            log("device CSR build %.1f ms, row plan %.1f ms, nnz=%d" % (t_csr * 1e3, t_plan * 1e3, int(ci.shape[0])))
+        return self.dev_csr[flags]
 
-    out = torch.empty((N, F), dtype=torch.float32, device="cuda")
-    if pitched and not gat:
-        # rows of X and out start on 128-byte lines (the layout the library recommends: gnnagg_row_pitch);
-        # the padding columns are never read or written and are not counted in any byte figure
-        Xp = g.pitched_empty(N, F, d_X.dtype)
-        Xp.copy_(d_X)
-        d_X = Xp
-        out = g.pitched_empty(N, F, torch.float32)
-    if gat:
-        a_s, a_d = W.normal_f32((heads, C), seed=14, std=0.1), W.normal_f32((heads, C), seed=15, std=0.1)
-        d_as, d_ad = dev(a_s), dev(a_d)
-        d_H, out3 = d_X.view(N, heads, C), out.view(N, heads, C)
-        ws = torch.empty(g.gnnagg_gat_workspace_bytes(N, heads, C, plan), dtype=torch.uint8, device="cuda")
+    def checker_csr(self, gkey, flags):
+        if flags not in self.ref_csr:
+            import oracle
+            N, src, dst = self.graph(gkey)
+            t0 = time.time()
+            rp, ci, w, _ = oracle.build_csr(N, src, dst, flags, want_w=bool(flags & oracle.NORM_SYM),
+                                            threads=self.threads)
+            log("checker CSR build %.1fs on %d threads" % (time.time() - t0, self.threads))
+            self.ref_csr[flags] = (rp, ci, w)
+        return self.ref_csr[flags]
 
-        def step():
-            g.gnnagg_gat_attention(d_rp, d_ci, d_H, d_as, d_ad, 0.2, False, True, max(f_chunk, 0), plan, out=out3,
-                                   workspace=ws)
-    else:
-        op = {"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname]
+    # ---- timing: wall clock around K steps, HIP events on the launch stream around each
+    def time_steps(self, step):
+        torch = self.torch
+        for _ in range(self.warmup):
+            step()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(self.steps)]
+        t0 = time.perf_counter()
+        for a, b in ev:
+            a.record()
+            step()
+            b.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return np.array([a.elapsed_time(b) for a, b in ev]), wall * 1e3 / self.steps
 
-        def step():
-            g.gnnagg_aggregate(op, d_rp, d_ci, d_w, d_X, out, f_chunk, plan)
-
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    # whole timed region: wall clock around K steps; per-step kernel time: HIP events on the launch stream
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-    t0 = time.perf_counter()
-    for a, b in ev:
-        a.record()
-        step()
-        b.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms = np.array([a.elapsed_time(b) for a, b in ev])
-    ms_per_step = wall * 1e3 / steps
-    edge_features = float(nnz) * F
-    x_bytes = 2 if xdt == "bf16" else 4
-    if gat:  # per edge: the row piece, the index, and one score per head unless the kernel recomputes it from the
-        # row piece (heads of 4, 8 or 16 channels); per vertex: H once for the scores, out, scores
-        per_edge_score = 0 if C in (4, 8, 16) else heads * 4
-        b_alg = nnz * (F * 4 + per_edge_score + 4) + 2 * N * F * 4 + 2 * N * heads * 4 * 2 + (N + 1) * 8
-    else:
-        f_eff = (g.gnnagg_auto_f_chunk(N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)), plan)
-                 if f_chunk == -1 else f_chunk)
-        # priced at ONE pass over the edge list (the smaller figure), whatever chunk width runs: the index and
-        # weight re-reads of a chunked run are the method's overhead, not work to take credit for
-        b_alg = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", 0)
-        b_alg_chunked = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", f_eff)
-    kern_ms = float(ms.mean())
-    achieved = b_alg / (kern_ms * 1e-3) / 1e9
-    # every array once: the floor no gather kernel reaches, reported as distance from the ideal
-    compulsory = N * F * x_bytes + N * F * 4 + nnz * (8 if opname == "wsum" else 4) + (N + 1) * 8
-    if gat:
-        compulsory += 2 * N * heads * 4
-    traffic = MEASURED_TRAFFIC.get(workload) if (f_chunk == -1 and pitched) else None  # taken in the default set-up
-    log("step %.3f ms wall, kernel mean %.3f ms (min %.3f), %.3e edge-features/s, %.0f GB/s algorithmic" %
-        (ms_per_step, kern_ms, ms.min(), edge_features / (ms_per_step * 1e-3), achieved))
-
-    # ---- launch-bound workloads: the same step captured in a HIP graph and replayed (the calls only enqueue
-    # kernels, so they can be captured); reported beside the eager figure
-    graph_ms = None
-    if edge_features < 1e9:
+    def replay_ms(self, step):
+        """The same step captured in a HIP graph and replayed (the calls only enqueue kernels)."""
+        torch = self.torch
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             step()
-        for _ in range(warmup):
+        for _ in range(self.warmup):
             graph.replay()
         torch.cuda.synchronize()
         g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         g0.record()
-        for _ in range(steps):
+        for _ in range(self.steps):
             graph.replay()
         g1.record()
         torch.cuda.synchronize()
-        graph_ms = g0.elapsed_time(g1) / steps
-        log("captured in a graph and replayed: %.4f ms per step" % graph_ms)
+        return g0.elapsed_time(g1) / self.steps
 
-    # ---- CPU checker on the host cores: bounded sample of destination rows, also the parity check
-    cpu = None
-    parity = None
-    if not (not cpu_baseline):
-        import oracle
-        threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
-        t0 = time.time()
-        rp, ci, w, _ = oracle.build_csr(N, src, dst, flags, want_w=gcn, threads=threads)
-        log("checker CSR build %.1fs on %d threads" % (time.time() - t0, threads))
-        rop = {"sum": oracle.SUM, "wsum": oracle.WSUM, "mean": oracle.MEAN, "max": oracle.MAX}.get(opname)
-
-        def checker_rows(rr):
-            if gat:
-                return oracle.gat_attention_rows(rr, rp, ci, X.reshape(N, heads, C), a_s, a_d, 0.2,
-                                                 threads=threads).reshape(len(rr), F)
-            return oracle.aggregate_rows(rop, rr, rp, ci, w, X, threads=threads)
-
+    def sample_rows(self, rp, n=384):
+        """Random destination rows plus the two longest: what the parity check of an entry covers."""
+        N = len(rp) - 1
         rng = np.random.default_rng(0)
         deg = np.diff(rp)
-        probe = np.sort(rng.choice(N, size=min(N, 256), replace=False)).astype(np.int64)
-        t0 = time.time()
-        checker_rows(probe)
-        rate = max(float(deg[probe].sum()) * F / max(time.time() - t0, 1e-4), 1.0)
-        want = cpu_seconds * rate / F  # edges to cover in about cpu_seconds
-        nrows = int(min(N, max(256, want / max(deg.mean(), 1.0))))
-        rows = np.sort(rng.choice(N, size=nrows, replace=False)).astype(np.int64)
-        t0 = time.time()
-        ref = checker_rows(rows)
-        dt = time.time() - t0
-        ef = float(deg[rows].sum()) * F
-        cpu = {"value": ef / dt, "unit": "edge-features/s", "cores": threads, "kind": "oracle",
-               "sample": "%d random destination rows of %s (%.3g edge-features, %.1f s)" % (nrows, workload, ef, dt)}
-        got = out[torch.from_numpy(rows).cuda()].cpu().numpy()
-        tol = 1e-2 if xdt == "bf16" else 1e-5
-        if opname == "max":
-            parity = bool(np.array_equal(got.view(np.uint32), ref.view(np.uint32)))
+        rows = set(rng.choice(N, size=min(N, n), replace=False).tolist())
+        rows.update(np.argsort(deg)[-2:].tolist())
+        return np.array(sorted(rows), dtype=np.int64)
+
+    @staticmethod
+    def close(got, ref, bf16):
+        return bool(np.all(np.abs(got.astype(np.float64) - ref) <= 1e-6 + (1e-2 if bf16 else 1e-5) * np.abs(ref)))
+
+    # ---- rates of an entry against the measured ceilings
+    def rate_blocks(self, workload, kern_ms, b_alg, lines, cfg):
+        t = kern_ms * 1e-3
+        achieved = b_alg / t / 1e9
+        rec = self.traffic.get(workload)
+        traffic, src = None, None
+        if rec and rec.get("kernel_source_hash") == kernel_source_hash(rec.get("kernel_sources", [])) and all(
+                rec.get(k) == cfg.get(k) for k in ("f_chunk_used", "x_row_pitch") if k in rec):
+            traffic, src = rec["fetch_bytes"] + rec["write_bytes"], rec["source"]
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": src,
+                "beyond_l2_gbs": (traffic / t / 1e9) if traffic else None,
+                "kernel_ms": kern_ms, "algorithmic_bytes": b_alg, "measured_copy_gbs": self.copy_gbs,
+                "note": "achieved = algorithmic bytes / time; above peak when L2 serves the gathers"}
+        l2 = None
+        peak_lines = self.ceil.get("probe-l2-line", {}).get("lines_per_s")
+        if lines:
+            l2 = {"bound": "l2-line-requests", "unit": "G lines/s", "achieved": lines / t / 1e9,
+                  "peak": peak_lines / 1e9 if peak_lines else None,
+                  "frac": (lines / t / peak_lines) if peak_lines else None, "lines_per_call": lines,
+                  "peak_source": "probe-l2-line of this run (one 128-byte line per edge, X resident in L2)"}
+        fab = None
+        beyond = [v["algorithmic_gbs"] for k, v in self.ceil.items() if k != "probe-l2-line"]
+        if traffic and beyond:
+            fab = {"bound": "fabric (beyond L2: Infinity Cache + HBM, not separable in the counters)", "unit": "GB/s",
+                   "achieved": traffic / t / 1e9, "peak": max(beyond), "frac": traffic / t / 1e9 / max(beyond),
+                   "peak_source": "fastest beyond-L2 probe of this run"}
+        return roof, l2, fab
+
+    # ---- one aggregation workload (sum / wsum / mean / max, plain or ranked)
+    def measure_aggregate(self, workload, f_chunk, cpu_seconds=0.0, single_thread=False):
+        g, torch = self.g, self.torch
+        base = workload.split("@")[0]
+        gkey, opname, F, xdt, gcn = WORKLOADS[base]
+        ranked = opname.endswith("-ranked")
+        opname = opname.replace("-ranked", "")
+        N, src, dst = self.graph(gkey)
+        flags = (g.SELF_LOOPS | g.NORM_SYM) if gcn else 0
+        c = self.device_csr(gkey, flags)
+        X = self.features(gkey, (N, F), xdt)
+        d_X0 = self.dev(X)
+        d_ci, setup = c["ci"], dict(c["setup"])
+        if ranked:  # per graph, like the CSR and the plan: rank the sources, store the rows in that order
+            g.gnnagg_rank_sources(N, c["ci"])
+            torch.cuda.synchronize()
+            t0 = time.time()
+            rank, d_ci = g.gnnagg_rank_sources(N, c["ci"])
+            torch.cuda.synchronize()
+            setup["rank_sources_ms"] = (time.time() - t0) * 1e3
+            Xr = torch.empty_like(d_X0)
+            Xr[rank.long()] = d_X0  # the layout the rows are stored in (data placement, not arithmetic)
+            d_X0 = Xr
+        if self.pitched:
+            d_X = g.pitched_empty(N, F, d_X0.dtype)
+            d_X.copy_(d_X0)
+            out = g.pitched_empty(N, F, torch.float32)
         else:
-            parity = bool(np.all(np.abs(got.astype(np.float64) - ref) <= 1e-6 + tol * np.abs(ref)))
-        log("checker: %.3e edge-features/s on %d threads; parity on the sample: %s" % (cpu["value"], threads, parity))
+            d_X, out = d_X0, torch.empty((N, F), dtype=torch.float32, device="cuda")
+        del d_X0
+        op = {"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname]
 
-    rec = {
-        "metric": "aggregated edge-features/sec", "value": edge_features / (ms_per_step * 1e-3),
-        "unit": "edge-features/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f64", "data": "synthetic",
-        "config": {"workload": workload, "graph": W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "op": opname,
-                   "f_chunk": f_chunk, "f_chunk_used": (F if gat else (f_eff if 0 < f_eff < F else F)), "x_dtype": xdt, "x_row_pitch": int(d_X.stride(0)),
-                   "out_row_pitch": int(out.stride(0))},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic,
-                     "kernel": "gat_aggregate_kernel (+ score pass)" if gat else "aggregate_kernel",
-                     "per": "library call (all its launches of that kernel; kernel_ms is their sum)",
-                     "kernel_ms": kern_ms, "kernel_ms_median": float(np.median(ms)), "kernel_ms_min": float(ms.min()),
-                     "algorithmic_bytes": b_alg,
-                     "algorithmic_bytes_with_edge_list_rereads": None if gat else b_alg_chunked,
-                     "hbm_gbs": (traffic / (kern_ms * 1e-3) / 1e9) if traffic else None,
-                     "compulsory_bytes": compulsory,
-                     "compulsory_frac": compulsory / (HBM_PEAK_GBS * 1e9) / (kern_ms * 1e-3),
-                     "measured_copy_gbs": copy_gbs},
-        "cpu_baseline": cpu,
-        "parity_on_sample": parity,
-        "graph_replay_ms_per_step": graph_ms,
-        "setup": {"csr_build_ms": t_csr * 1e3, "row_plan_ms": t_plan * 1e3},
-    }
-    return rec
+        def step():
+            g.gnnagg_aggregate(op, c["rp"], d_ci, c["w"], d_X, out, f_chunk, c["plan"])
+
+        ms, ms_per_step = self.time_steps(step)
+        nnz = c["nnz"]
+        x_bytes = 2 if xdt == "bf16" else 4
+        f_eff = (g.gnnagg_auto_f_chunk(N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)), c["plan"])
+                 if f_chunk == -1 else f_chunk)
+        f_used = f_eff if 0 < f_eff < F else F
+        # priced at ONE pass over the edge list, whatever chunk width runs: the index and weight re-reads of
+        # a chunked run are the method's overhead, not work to take credit for
+        b_alg = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", 0)
+        kern_ms = float(ms.mean())
+        cfg = {"workload": workload, "graph": self.W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "op": opname,
+               "f_chunk": f_chunk, "f_chunk_used": f_used, "x_dtype": xdt, "x_row_pitch": int(d_X.stride(0)),
+               "out_row_pitch": int(out.stride(0)), "rows_in_popularity_order": ranked}
+        lpe = gather_lines_per_edge(F, x_bytes, int(d_X.stride(0)), f_used)
+        roof, l2, fab = self.rate_blocks(base if f_chunk == -1 else workload, kern_ms, b_alg,
+                                         nnz * lpe if lpe else None, cfg)
+        roof.update({"kernel": "aggregate_kernel", "per": "library call (all its launches; kernel_ms is their sum)",
+                     "kernel_ms_median": float(np.median(ms)), "kernel_ms_min": float(ms.min()),
+                     "algorithmic_bytes_with_edge_list_rereads": algorithmic_bytes(nnz, N, F, x_bytes,
+                                                                                   opname == "wsum", f_eff),
+                     "compulsory_bytes": N * F * x_bytes + N * F * 4 + nnz * (8 if opname == "wsum" else 4) + (N + 1) * 8})
+        roof["compulsory_frac"] = roof["compulsory_bytes"] / (HBM_PEAK_GBS * 1e9) / (kern_ms * 1e-3)
+        ef = float(nnz) * F
+        log("%s: step %.3f ms wall, kernel mean %.3f ms (min %.3f), %.3e edge-features/s, %.0f GB/s algorithmic" %
+            (workload, ms_per_step, kern_ms, ms.min(), ef / (ms_per_step * 1e-3), roof["achieved"]))
+        replay = self.replay_ms(step) if ef < 1e9 else None
+
+        # ---- CPU checker: parity on sampled rows; optionally its rate on a bounded sample / on one thread
+        import oracle
+        rp, ci, w = self.checker_csr(gkey, flags)
+        rop = {"sum": oracle.SUM, "wsum": oracle.WSUM, "mean": oracle.MEAN, "max": oracle.MAX}[opname]
+        rows = self.sample_rows(rp)
+        cpu = None
+        if cpu_seconds > 0:
+            deg = np.diff(rp)
+            t0 = time.time()
+            oracle.aggregate_rows(rop, rows, rp, ci, w, X, threads=self.threads)
+            rate = max(float(deg[rows].sum()) * F / max(time.time() - t0, 1e-4), 1.0)
+            nrows = int(min(N, max(len(rows), cpu_seconds * rate / F / max(deg.mean(), 1.0))))
+            rows = np.sort(np.random.default_rng(0).choice(N, size=nrows, replace=False)).astype(np.int64)
+            t0 = time.time()
+            ref = oracle.aggregate_rows(rop, rows, rp, ci, w, X, threads=self.threads)
+            dt = time.time() - t0
+            cef = float(deg[rows].sum()) * F
+            cpu = {"value": cef / dt, "unit": "edge-features/s", "cores": self.threads, "kind": "oracle",
+                   "sample": "%d random destination rows of %s (%.3g edge-features, %.1f s)" % (nrows, workload, cef, dt)}
+            log("checker: %.3e edge-features/s on %d threads" % (cpu["value"], self.threads))
+        else:
+            ref = oracle.aggregate_rows(rop, rows, rp, ci, w, X, threads=self.threads)
+        got = out[torch.from_numpy(rows).cuda()].cpu().numpy()
+        parity = (bool(np.array_equal(got.view(np.uint32), ref.view(np.uint32))) if opname == "max"
+                  else self.close(got, ref, xdt == "bf16"))
+        cpu1 = None
+        if single_thread:
+            t0 = time.time()
+            oracle.aggregate(rop, rp, ci, w, X, threads=1)
+            dt = time.time() - t0
+            cpu1 = {"value": ef / dt, "unit": "edge-features/s", "cores": 1, "kind": "oracle",
+                    "sample": "the whole workload (%.3g edge-features, %.2f s)" % (ef, dt)}
+        rec = {"metric": "aggregated edge-features/sec", "value": ef / (ms_per_step * 1e-3), "unit": "edge-features/s",
+               "n_gpus": 1, "steps": self.steps, "warmup": self.warmup, "ms_per_step": ms_per_step,
+               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+               "config": cfg, "roofline": roof, "roofline_l2": l2, "roofline_fabric": fab, "cpu_baseline": cpu,
+               "cpu_baseline_1thread": cpu1, "parity_on_sample": parity, "parity_rows": int(len(rows)),
+               "graph_replay_ms_per_step": replay, "setup": setup}
+        return rec
+
+    # ---- attention
+    def measure_gat(self, workload, f_chunk, single_thread=False):
+        g, torch, W = self.g, self.torch, self.W
+        gkey, _, (heads, C), xdt, _ = WORKLOADS[workload]
+        F = heads * C
+        N, src, dst = self.graph(gkey)
+        c = self.device_csr(gkey, g.SELF_LOOPS)
+        H = self.features(gkey, (N, F), "f32")
+        a_s, a_d = W.normal_f32((heads, C), seed=14, std=0.1), W.normal_f32((heads, C), seed=15, std=0.1)
+        d_H, d_as, d_ad = self.dev(H).view(N, heads, C), self.dev(a_s), self.dev(a_d)
+        out = torch.empty((N, heads, C), dtype=torch.float32, device="cuda")
+        ws = torch.empty(g.gnnagg_gat_workspace_bytes(N, heads, C, c["plan"]), dtype=torch.uint8, device="cuda")
+
+        def step():
+            g.gnnagg_gat_attention(c["rp"], c["ci"], d_H, d_as, d_ad, 0.2, False, True, max(f_chunk, 0), c["plan"],
+                                   out=out, workspace=ws)
+
+        ms, ms_per_step = self.time_steps(step)
+        nnz = c["nnz"]
+        # per edge: the row piece, the index, and one score per head unless the kernel recomputes it from the row
+        # piece (heads of 4, 8 or 16 channels); per vertex: H for the scores, out
+        recomputed = C in (4, 8, 16)
+        b_alg = nnz * (F * 4 + (0 if recomputed else heads * 4) + 4) + 2 * N * F * 4 + (N + 1) * 8
+        if not recomputed:
+            b_alg += 2 * N * heads * 4 * 2
+        kern_ms = float(ms.mean())
+        cfg = {"workload": workload, "graph": W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "heads": heads, "C": C,
+               "op": "gat", "f_chunk": f_chunk, "f_chunk_used": F, "x_dtype": "f32", "x_row_pitch": F}
+        lpe = gather_lines_per_edge(F, 4, F, F)
+        roof, l2, fab = self.rate_blocks(workload, kern_ms, b_alg, nnz * lpe if lpe else None, cfg)
+        roof.update({"kernel": "gat_aggregate_kernel" + ("" if recomputed else " (+ score pass)"),
+                     "kernel_ms_median": float(np.median(ms)), "kernel_ms_min": float(ms.min())})
+        ef = float(nnz) * F
+        log("%s: step %.3f ms wall, kernel mean %.3f ms (min %.3f), %.3e edge-features/s" %
+            (workload, ms_per_step, kern_ms, ms.min(), ef / (ms_per_step * 1e-3)))
+        replay = self.replay_ms(step) if ef < 1e9 else None
+        import oracle
+        rp, ci, _ = self.checker_csr(gkey, oracle.SELF_LOOPS)
+        rows = self.sample_rows(rp)
+        ref = oracle.gat_attention_rows(rows, rp, ci, H.reshape(N, heads, C), a_s, a_d, 0.2, threads=self.threads)
+        got = out[torch.from_numpy(rows).cuda()].cpu().numpy()
+        cpu1 = None
+        if single_thread:
+            t0 = time.time()
+            oracle.gat_attention(rp, ci, H.reshape(N, heads, C), a_s, a_d, 0.2, want_alpha=False, threads=1)
+            dt = time.time() - t0
+            cpu1 = {"value": ef / dt, "unit": "edge-features/s", "cores": 1, "kind": "oracle",
+                    "sample": "the whole workload (%.3g edge-features, %.2f s)" % (ef, dt)}
+        return {"metric": "aggregated edge-features/sec", "value": ef / (ms_per_step * 1e-3), "unit": "edge-features/s",
+                "n_gpus": 1, "steps": self.steps, "warmup": self.warmup, "ms_per_step": ms_per_step,
+                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+                "config": cfg, "roofline": roof, "roofline_l2": l2, "roofline_fabric": fab, "cpu_baseline": None,
+                "cpu_baseline_1thread": cpu1, "parity_on_sample": self.close(got, ref, False),
+                "parity_rows": int(len(rows)), "graph_replay_ms_per_step": replay, "setup": dict(c["setup"])}
+
+    # ---- Combination alone, whole layers, aggregation with the fused dense layer
+    def measure_layer(self, workload):
+        g, torch, W = self.g, self.torch, self.W
+        gkey, opname, (F, H), xdt, gcn = WORKLOADS[workload]
+        N, src, dst = self.graph(gkey)
+        flags = (g.SELF_LOOPS | g.NORM_SYM) if gcn else 0
+        X = self.features(gkey, (N, F), "f32")
+        Wt = W.normal_f32((F, H), seed=16, std=0.05)
+        bias = W.normal_f32((H,), seed=17, std=0.1)
+        d_X, d_W, d_b = self.dev(X), self.dev(Wt), self.dev(bias)
+        aggregates = opname != "combine"
+        c = self.device_csr(gkey, flags) if aggregates else None
+        nnz = c["nnz"] if aggregates else 0
+        setup = dict(c["setup"]) if aggregates else {}
+        aop = g.WSUM if gcn else g.SUM
+        rank, d_ci = None, (c["ci"] if aggregates else None)
+        if opname == "layer-ranked":
+            rank, d_ci = g.gnnagg_rank_sources(N, c["ci"])
+        hid = torch.empty((N, H), dtype=torch.float32, device="cuda")
+        out = torch.empty((N, H), dtype=torch.float32, device="cuda")
+        if opname == "combine":
+            def step():
+                g.gnnagg_combine(d_X, d_W, None, False, hid)
+            kernels, metric = "combine_kernel", "Combination (dense layer)"
+        elif opname in ("layer", "layer-ranked"):
+            def step():
+                g.gnnagg_combine(d_X, d_W, None, False, hid, out_rows=rank)
+                g.gnnagg_aggregate(aop, c["rp"], d_ci, c["w"], hid, out, 0, c["plan"])
+            kernels, metric = "combine_kernel + aggregate_kernel", "one layer A (X W), Combination first"
+        elif opname == "layer-fused":
+            def step():
+                g.gnnagg_combine(d_X, d_W, None, False, hid)
+                g.gnnagg_aggregate_update(aop, c["rp"], d_ci, c["w"], hid, None, d_b, True, out, 0, c["plan"])
+            kernels, metric = ("combine_kernel + aggregate_kernel with the Update step at its store",
+                               "one layer relu(A (X W) + b), Combination first")
+        else:  # agg-dense: X is already at the hidden width F; out = relu(A X W2 + b) in one kernel
+            def step():
+                g.gnnagg_aggregate_update(aop, c["rp"], d_ci, c["w"], d_X, d_W, d_b, True, out, 0, c["plan"])
+            kernels, metric = ("aggregate_kernel with the fused dense layer",
+                               "one layer relu((A X) W2 + b) at the hidden width, one kernel")
+        ms, ms_per_step = self.time_steps(step)
+        kern_ms = float(ms.mean())
+        flop = 2.0 * N * F * H
+        if opname == "agg-dense":
+            b_alg = algorithmic_bytes(nnz, N, F, 4, gcn, 0) - N * F * 4 + F * H * 4 + N * H * 4
+            ef = float(nnz) * F
+        else:
+            b_alg = N * F * 4 + F * H * 4 + N * H * 4
+            if aggregates:
+                b_alg += algorithmic_bytes(nnz, N, H, 4, gcn, 0)
+            ef = float(nnz) * H
+        achieved = b_alg / (kern_ms * 1e-3) / 1e9
+        log("%s: %.3f ms per step, %.0f GB/s algorithmic" % (workload, kern_ms, achieved))
+        # parity on sampled rows against the checker's composition of the same steps
+        import oracle
+        if opname == "combine":
+            rows = np.sort(np.random.default_rng(0).choice(N, size=min(N, 2048), replace=False)).astype(np.int64)
+            ref = oracle.combine(X[rows], Wt, threads=self.threads)
+            got = hid[torch.from_numpy(rows).cuda()].cpu().numpy()
+        else:
+            rp, ci, w = self.checker_csr(gkey, flags)
+            rows = self.sample_rows(rp)
+            if opname == "agg-dense":
+                agg = oracle.aggregate_rows(oracle.WSUM if gcn else oracle.SUM, rows, rp, ci, w, X, threads=self.threads)
+                ref = oracle.combine(agg, Wt, bias, True, threads=self.threads)
+            else:
+                ref_hid = oracle.combine(X, Wt, threads=self.threads)
+                ref = oracle.aggregate_rows(oracle.WSUM if gcn else oracle.SUM, rows, rp, ci, w, ref_hid,
+                                            threads=self.threads)
+                if opname == "layer-fused":
+                    ref = oracle.update(ref, bias, True)
+            got = out[torch.from_numpy(rows).cuda()].cpu().numpy()
+        rec = {"metric": metric,
+               "value": (ef if aggregates else flop) / (ms_per_step * 1e-3),
+               "unit": "edge-features/s at the aggregation width" if aggregates else "flop/s",
+               "n_gpus": 1, "steps": self.steps, "warmup": self.warmup, "ms_per_step": ms_per_step,
+               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+               "config": {"workload": workload, "graph": W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "H": H},
+               "cpu_baseline": None, "parity_on_sample": self.close(got, ref, False), "parity_rows": int(len(rows)),
+               "setup": setup}
+        if opname == "combine":  # the dense contraction: priced against the fp64 matrix-core peak
+            tf = flop / (kern_ms * 1e-3) / 1e12
+            rec["roofline"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_F64_PEAK_TFLOPS, "unit": "TFLOP/s",
+                               "frac": tf / MFMA_F64_PEAK_TFLOPS, "traffic": None, "kernel": kernels,
+                               "kernel_ms": kern_ms, "flop": flop, "algorithmic_bytes": b_alg,
+                               "algorithmic_gbs": achieved, "hbm_frac": achieved / HBM_PEAK_GBS,
+                               "measured_copy_gbs": self.copy_gbs}
+        else:
+            rec["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                               "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": kernels,
+                               "kernel_ms": kern_ms, "kernel_ms_median": float(np.median(ms)),
+                               "algorithmic_bytes": b_alg, "measured_copy_gbs": self.copy_gbs}
+        return rec
+
+    def measure(self, workload, f_chunk=-1, cpu_seconds=0.0, single_thread=False):
+        base, _, width = workload.partition("@")
+        if width:
+            f_chunk = 0 if width == "all" else int(width)
+        op = WORKLOADS[base][1]
+        if op == "gat":
+            return self.measure_gat(base, f_chunk if not width else f_chunk, single_thread)
+        if op in ("combine", "layer", "layer-ranked", "layer-fused", "agg-dense"):
+            return self.measure_layer(base)
+        rec = self.measure_aggregate(workload, f_chunk, cpu_seconds, single_thread)
+        if base in PROBES:
+            r = rec["roofline"]
+            self.ceil[base] = {"algorithmic_gbs": r["achieved"], "kernel_ms": r["kernel_ms"],
+                               "lines_per_s": rec["roofline_l2"]["lines_per_call"] / (r["kernel_ms"] * 1e-3)
+                               if rec["roofline_l2"] else None}
+        return rec
+
+    def cpu_chunk_sweep(self, workload, widths):
+        """The CPU checker in the chunk-outer order of Algorithm 1 over a sweep of chunk widths, whole graph:
+        context for the paper's own (CPU) effect, not a target."""
+        import oracle
+        gkey, opname, F, xdt, gcn = WORKLOADS[workload]
+        N, src, dst = self.graph(gkey)
+        X = self.features(gkey, (N, F), xdt)
+        rp, ci, w = self.checker_csr(gkey, (oracle.SELF_LOOPS | oracle.NORM_SYM) if gcn else 0)
+        rop = {"sum": oracle.SUM, "wsum": oracle.WSUM, "mean": oracle.MEAN, "max": oracle.MAX}[opname]
+        res = []
+        for fc in widths:
+            t0 = time.time()
+            oracle.aggregate(rop, rp, ci, w, X, f_chunk=fc, form=1, threads=self.threads)
+            dt = time.time() - t0
+            res.append({"f_chunk": fc, "seconds": dt, "edge_features_per_s": float(len(ci)) * F / dt,
+                        "threads": self.threads})
+            log("checker, chunk-outer, %s f_chunk=%d: %.2f s" % (workload, fc, dt))
+        return res
 
 
+def copy_probe(g, torch, n_probe):
+    """Plain streaming copy of 1 GiB: the measured HBM copy rate of this device."""
+    probe_bytes = 1 << 30
+    p_src = torch.empty(probe_bytes, dtype=torch.uint8, device="cuda").fill_(1)
+    p_dst = torch.empty_like(p_src)
+    g.gnnagg_copy_probe(p_dst, p_src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n_probe):
+        g.gnnagg_copy_probe(p_dst, p_src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_ms = e0.elapsed_time(e1) / n_probe
+    return copy_ms, 2.0 * probe_bytes / (copy_ms * 1e-3) / 1e9, probe_bytes
 
 
-def cpu_chunk_sweep(W, workload, widths):
-    """The CPU checker in the chunk-outer order of Algorithm 1 over a sweep of chunk widths, whole graph:
-    context for the paper's own (CPU) effect, not a target."""
-    import oracle
-    gkey, opname, F, xdt, gcn = WORKLOADS[workload]
-    N, src, dst = graph_of(W, gkey)
-    X = W.normal_bf16((N, F), seed=13) if xdt == "bf16" else W.normal_f32((N, F), seed=13)
-    threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
-    rp, ci, w, _ = oracle.build_csr(N, src, dst, (oracle.SELF_LOOPS | oracle.NORM_SYM) if gcn else 0, want_w=gcn,
-                                    threads=threads)
-    rop = {"sum": oracle.SUM, "wsum": oracle.WSUM, "mean": oracle.MEAN, "max": oracle.MAX}[opname]
-    res = []
-    for fc in widths:
-        t0 = time.time()
-        oracle.aggregate(rop, rp, ci, w, X, f_chunk=fc, form=1, threads=threads)
-        dt = time.time() - t0
-        res.append({"f_chunk": fc, "seconds": dt, "edge_features_per_s": float(len(ci)) * F / dt, "threads": threads})
-        log("checker, chunk-outer, f_chunk=%d: %.2f s" % (fc, dt))
-    return res
+def also_entry(r):
+    keep = ("metric", "value", "unit", "ms_per_step", "config", "roofline", "roofline_l2", "roofline_fabric", "setup",
+            "graph_replay_ms_per_step", "parity_on_sample", "parity_rows", "cpu_baseline", "cpu_baseline_1thread")
+    entry = {k: r[k] for k in keep if k in r}
+    med = r["roofline"].get("kernel_ms_median")
+    if med:  # the median step is robust against a single stalled step on the microsecond-sized workloads
+        entry["ms_median"] = med
+        entry["value_median"] = r["value"] * r["ms_per_step"] / med
+    return entry
 
 
 def main():
@@ -372,19 +629,22 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c4-gcn", choices=sorted(WORKLOADS) + ["copy"],
-                    help="'copy' runs only the library's plain copy kernel on 1 GiB (profiler calibration)")
+    ap.add_argument("--workload", default="c4-gcn",
+                    help="a workload name (optionally name@width), or 'copy' for the library's plain copy kernel "
+                         "on 1 GiB alone (profiler calibration)")
     ap.add_argument("--f-chunk", type=int, default=-1,
                     help="chunk width; -1 = let the library pick (GNNAGG_F_CHUNK_AUTO, the default), 0 = one chunk")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip every CPU-rate leg (parity checks stay)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    ap.add_argument("--also", default="c4-mean,c5-sum,c5-max,c5-sum-f32,c5-sum-f16,c2-mean,c3-gat,c1-gcn",
-                    help="comma list of further workloads measured after the main one and reported under 'also'")
+    ap.add_argument("--also", default=",".join(DEFAULT_ALSO),
+                    help="comma list of further workloads, measured and reported under 'also' (the probes first: "
+                         "their rates are the ceilings of roofline_l2 / roofline_fabric)")
     ap.add_argument("--contiguous", action="store_true",
                     help="keep X and out at a row pitch of exactly F elements instead of line-aligned rows")
-    ap.add_argument("--cpu-chunk-sweep", default="",
-                    help="comma list of chunk widths: also time the CPU checker in Algorithm 1's chunk-outer order "
-                         "on the whole graph of the workload at each width (0 = one chunk); minutes of CPU time")
+    ap.add_argument("--cpu-chunk-sweep", default="default",
+                    help="'default': the CPU checker in Algorithm 1's chunk-outer order at the sweep widths of the "
+                         "two benchmark configurations that name one (about half a minute); 'none'; or a comma list "
+                         "of widths for the main workload")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
@@ -396,44 +656,53 @@ def main():
     import workloads as W
     g.load_library()
 
-    # plain streaming copy of 1 GiB: the measured HBM copy rate of this device, reported beside the roofline
-    probe_bytes = 1 << 30
-    p_src = torch.empty(probe_bytes, dtype=torch.uint8, device="cuda").fill_(1)
-    p_dst = torch.empty_like(p_src)
-    g.gnnagg_copy_probe(p_dst, p_src)
-    torch.cuda.synchronize()
-    n_probe = max(args.steps, 3) if args.workload == "copy" else 5
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(n_probe):
-        g.gnnagg_copy_probe(p_dst, p_src)
-    e1.record()
-    torch.cuda.synchronize()
-    copy_ms = e0.elapsed_time(e1) / n_probe
-    copy_gbs = 2.0 * probe_bytes / (copy_ms * 1e-3) / 1e9
+    copy_ms, copy_gbs, probe_bytes = copy_probe(g, torch, max(args.steps, 3) if args.workload == "copy" else 5)
     log("copy probe: 1 GiB in %.3f ms -> %.0f GB/s read+write" % (copy_ms, copy_gbs))
-    del p_src, p_dst
     if args.workload == "copy":
         print(json.dumps({"metric": "hbm copy rate", "value": copy_gbs, "unit": "GB/s", "n_gpus": 1,
-                          "steps": n_probe, "ms_per_step": copy_ms, "bytes_read": probe_bytes,
-                          "bytes_written": probe_bytes, "config": {"workload": "copy"}}), flush=True)
+                          "ms_per_step": copy_ms, "bytes_read": probe_bytes, "bytes_written": probe_bytes,
+                          "config": {"workload": "copy"}}), flush=True)
         return
+    if args.workload.split("@")[0] not in WORKLOADS:
+        sys.exit("unknown workload %s (known: %s)" % (args.workload, ", ".join(sorted(WORKLOADS))))
 
-    rec = measure(g, W, torch, args.workload, args.f_chunk, args.steps, args.warmup, not args.no_cpu_baseline,
-                  args.cpu_seconds, copy_gbs, not args.contiguous)
-    also = []
-    for wl in [w for w in args.also.split(",") if w and w != args.workload]:
-        r = measure(g, W, torch, wl, args.f_chunk, args.steps, args.warmup, False, 0.0, copy_gbs, not args.contiguous)
-        entry = {k: r[k] for k in ("value", "unit", "ms_per_step", "config", "roofline", "setup",
-                                   "graph_replay_ms_per_step")}
-        med = r["roofline"].get("kernel_ms_median")
-        if med:  # the median step is robust against a single stalled step on the microsecond-sized workloads
-            entry["ms_median"] = med
-            entry["value_median"] = r["value"] * r["ms_per_step"] / med
-        also.append(entry)
-    rec["also"] = also
-    if args.cpu_chunk_sweep:
-        rec["cpu_chunk_sweep"] = cpu_chunk_sweep(W, args.workload, [int(v) for v in args.cpu_chunk_sweep.split(",")])
+    b = Bench(g, W, torch, args.steps, args.warmup, not args.contiguous)
+    b.copy_gbs = copy_gbs
+    also_names = [w for w in args.also.split(",") if w and w != args.workload]
+    for w in also_names:
+        if w.split("@")[0] not in WORKLOADS:
+            sys.exit("unknown workload %s" % w)
+    cpu = not args.no_cpu_baseline
+    done = {}
+    # the probes first (ceilings), then the main workload, then the rest in the order given (grouped by graph)
+    for w in [w for w in also_names if w in PROBES]:
+        done[w] = b.measure(w, 0)
+    rec = b.measure(args.workload, args.f_chunk, args.cpu_seconds if cpu else 0.0,
+                    cpu and args.workload in SINGLE_THREAD_ALSO)
+    sweeps = {}
+    if cpu and args.cpu_chunk_sweep not in ("none", ""):
+        widths = (CPU_CHUNK_SWEEPS.get(args.workload) if args.cpu_chunk_sweep == "default"
+                  else [int(v) for v in args.cpu_chunk_sweep.split(",")])
+        if widths:  # now, while the main workload's graph and features are still in host memory
+            sweeps[args.workload] = b.cpu_chunk_sweep(args.workload, widths)
+    for w in also_names:
+        if w in done:
+            continue
+        done[w] = b.measure(w, args.f_chunk, CPU_BASELINE_ALSO.get(w, 0.0) if cpu else 0.0,
+                            cpu and w in SINGLE_THREAD_ALSO)
+        if cpu and args.cpu_chunk_sweep == "default" and w in CPU_CHUNK_SWEEPS and w not in sweeps:
+            sweeps[w] = b.cpu_chunk_sweep(w, CPU_CHUNK_SWEEPS[w])
+    rec["ceilings"] = {"hbm_peak_gbs": HBM_PEAK_GBS, "measured_copy_gbs": copy_gbs,
+                       "probes": b.ceil,
+                       "note": "probe-l2-line: one line per edge out of 3.7 MB (L2-resident); probe-mall-line: out of "
+                               "134 MB (Infinity Cache); probe-hbm-line: out of 2.1 GB; probe-hbm-row: 2.4 KB rows out "
+                               "of 5.1 GB; uniform random graphs, same kernel"}
+    rec["also"] = [also_entry(done[w]) for w in also_names]
+    rec["all_parity_on_sample"] = bool(rec["parity_on_sample"] and all(e.get("parity_on_sample") for e in rec["also"]))
+    rec["kernel_source_hash"] = {"aggregate_kernel": kernel_source_hash(AGGREGATE_SOURCES),
+                                 "gat_aggregate_kernel": kernel_source_hash(GAT_SOURCES)}
+    if sweeps:
+        rec["cpu_chunk_sweep"] = sweeps
     print(json.dumps(rec), flush=True)
 
 

@@ -369,6 +369,24 @@ def test_bench_module_is_importable_and_its_workloads_name_known_graphs():
     bench = importlib.import_module("bench")
     for name, (gkey, opname, F, xdt, gcn) in bench.WORKLOADS.items():
         assert gkey in W.GRAPHS, name
-        assert opname in ("sum", "wsum", "mean", "max", "gat", "combine", "layer", "layer-ranked"), name
+        assert opname in ("sum", "wsum", "mean", "max", "sum-ranked", "gat", "combine", "layer", "layer-ranked",
+                          "layer-fused", "agg-dense"), name
         assert xdt in ("f32", "bf16"), name
-    assert set(bench.MEASURED_TRAFFIC) <= set(bench.WORKLOADS)
+    for name in bench.DEFAULT_ALSO + list(bench.CPU_BASELINE_ALSO) + list(bench.SINGLE_THREAD_ALSO):
+        assert name.split("@")[0] in bench.WORKLOADS, name
+    # the sweeps the two benchmark configurations name are part of the default run
+    for name in ["c1-gcn@16", "c1-gcn@64", "c1-gcn@all"] + ["c4-%s@%s" % (o, w) for o in ("gcn", "mean")
+                                                            for w in ("8", "16", "32", "64", "all")]:
+        assert name in bench.DEFAULT_ALSO, name
+    # line requests per edge: rows on lines, summed over the chunk passes
+    assert bench.gather_lines_per_edge(602, 4, 608, 602) == 19
+    assert bench.gather_lines_per_edge(602, 4, 608, 32) == 19
+    assert bench.gather_lines_per_edge(602, 4, 608, 8) == 76
+    assert bench.gather_lines_per_edge(100, 2, 128, 100) == 2
+    assert bench.gather_lines_per_edge(16, 2, 16, 16) == 1
+    assert bench.gather_lines_per_edge(100, 2, 100, 100) is None  # 200-byte pitch: rows straddle lines
+    # traffic records in profiles/ carry what bench.py checks before it uses them
+    for rec in bench.measured_traffic().values():
+        assert {"workload", "kernel_sources", "kernel_source_hash", "fetch_bytes", "write_bytes", "source"} <= set(rec)
+    assert len(bench.kernel_source_hash(bench.AGGREGATE_SOURCES)) == 16
+    assert bench.kernel_source_hash(bench.AGGREGATE_SOURCES) != bench.kernel_source_hash(bench.GAT_SOURCES)

@@ -126,6 +126,7 @@ class GraphSpec:
     R: float
     seed: int
     cover_all: bool = False
+    kind: str = "powerlaw"  # "uniform": M directed edges with independent uniform endpoints (alpha, R unused)
 
 
 GRAPHS = {
@@ -135,6 +136,16 @@ GRAPHS = {
     "c5": GraphSpec("c5-sparse", 2449029, 30950000, 2.0, 9000.0, 4, False),
     # the paper's third evaluation graph (Table II: 132,534 vertices, average degree 597): realised max degree ~6.6k
     "c6": GraphSpec("c6-dense-small", 132534, 39561252, 1.8, 60.0, 6, False),
+    # Measurement aids, not benchmark shapes: uniform random directed graphs that pin the source rows of a
+    # gather to one level of the memory system.  u-l2: the dense graph's edge count on so few vertices that
+    # one 128-byte line per vertex (3.7 MB) stays in a 4 MB L2; u-hbm: 16.8 M vertices, so that even one
+    # line per vertex (2.1 GB) is many times the 256 MB Infinity Cache and nearly every gather comes from HBM;
+    "u-l2": GraphSpec("uniform-l2-resident", 29120, 114615892, 0.0, 0.0, 7, False, "uniform"),
+    "u-hbm": GraphSpec("uniform-hbm-resident", 16777216, 67108864, 0.0, 0.0, 8, False, "uniform"),
+    # u-mall: one line per vertex is 134 MB, 32 times one L2 and half the Infinity Cache; u-hbmw: 2.1 M
+    # vertices for rows of 2.4 KB (5.1 GB), the dense benchmark's row width without any reuse.
+    "u-mall": GraphSpec("uniform-infinity-cache-resident", 1048576, 67108864, 0.0, 0.0, 9, False, "uniform"),
+    "u-hbmw": GraphSpec("uniform-hbm-resident-wide-rows", 2097152, 33554432, 0.0, 0.0, 10, False, "uniform"),
 }
 
 
@@ -144,5 +155,8 @@ def graph(key: str, scale: float = 1.0):
     g = GRAPHS[key]
     N = max(16, int(round(g.N * scale)))
     M = max(8, int(round(g.M * scale)))
+    if g.kind == "uniform":
+        src, dst = random_digraph(N, M, g.seed)
+        return N, src, dst
     src, dst = powerlaw_graph(N, M, g.alpha, g.R, g.seed, g.cover_all)
     return N, src, dst

@@ -3,38 +3,15 @@
 // III: format conversion is a cost of its own).
 //
 // CSR build = one stable radix sort of the edges on the key
-// (destination, source) carrying the input position, so that ties fall in
-// input order; row pointers come from the boundaries of the sorted keys.
-// Integer work only, no atomics on the outputs: the result is unique.
+// (destination, source), so that ties fall in input order (the input position
+// travels with the key only when the caller asks for the permutation); row
+// pointers come from a search of the sorted keys.  Integer work only, no
+// atomics on the outputs: the result is unique.
 #include "common.hpp"
 #include "radix_sort.hpp"
 
 namespace gnnagg {
 namespace {
-
-__global__ __launch_bounds__(kBlock) void make_edge_keys_kernel(const int32_t* __restrict__ src,
-                                                                const int32_t* __restrict__ dst, int64_t E,
-                                                                int64_t nnz, int64_t N, int src_bits,
-                                                                uint64_t* __restrict__ keys,
-                                                                uint32_t* __restrict__ vals,
-                                                                uint32_t* __restrict__ bad) {
-  const int64_t k = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (k >= nnz) return;
-  int64_t s, d;
-  if (k < E) {
-    s = src[k];
-    d = dst[k];
-    if (s < 0 || s >= N || d < 0 || d >= N) {  // keep every later access in range, report to the host
-      *bad = 1u;
-      s = 0;
-      d = 0;
-    }
-  } else {
-    s = d = k - E;  // appended self-loop
-  }
-  keys[k] = ((uint64_t)d << src_bits) | (uint64_t)s;
-  vals[k] = (uint32_t)k;
-}
 
 __global__ void fill_u32_kernel(uint32_t* __restrict__ p, uint32_t v) { *p = v; }
 
@@ -43,42 +20,47 @@ __global__ __launch_bounds__(kBlock) void fill_i64_kernel(int64_t* __restrict__ 
   if (k < n) p[k] = v;
 }
 
-// rowptr[r] = first slot whose destination is >= r.  Slot e writes the rows in
-// (dst[e-1], dst[e]]; the last slot also closes the rows above its destination.
-__global__ __launch_bounds__(kBlock) void csr_from_sorted_kernel(const uint64_t* __restrict__ keys,
-                                                                 const uint32_t* __restrict__ vals,
-                                                                 int64_t nnz, int64_t N, int src_bits,
-                                                                 int64_t* __restrict__ rowptr,
-                                                                 int32_t* __restrict__ colidx,
-                                                                 int64_t* __restrict__ perm) {
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (e >= nnz) return;
-  const uint64_t key = keys[e];
-  const int64_t d = (int64_t)(key >> src_bits);
-  const int64_t dprev = (e == 0) ? -1 : (int64_t)(keys[e - 1] >> src_bits);
-  for (int64_t r = dprev + 1; r <= d; ++r) rowptr[r] = e;
-  if (e == nnz - 1)
-    for (int64_t r = d + 1; r <= N; ++r) rowptr[r] = nnz;
-  colidx[e] = (int32_t)(key & ((1ull << src_bits) - 1ull));
-  if (perm) perm[e] = (int64_t)vals[e];
+// rowptr[r] = first slot whose destination is >= r, one thread per row: a binary search over the sorted
+// keys, so that the time does not depend on how the empty rows are distributed.
+__global__ __launch_bounds__(kBlock) void rowptr_kernel(const uint64_t* __restrict__ keys, int64_t nnz, int64_t N,
+                                                        int src_bits, int64_t* __restrict__ rowptr) {
+  const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (r > N) return;
+  int64_t lo = 0, hi = nnz;  // first slot in [lo, hi] with destination >= r
+  while (lo < hi) {
+    const int64_t mid = lo + ((hi - lo) >> 1);
+    if ((int64_t)(keys[mid] >> src_bits) >= r) hi = mid;
+    else lo = mid + 1;
+  }
+  rowptr[r] = lo;
 }
 
-// GCN symmetric normalisation: fp64 1/sqrt(d_i d_j), one rounding to fp32.
-__global__ __launch_bounds__(kBlock) void edge_weight_kernel(const uint64_t* __restrict__ keys, int64_t nnz,
-                                                             int src_bits, const int64_t* __restrict__ rowptr,
-                                                             int norm_sym, float* __restrict__ edge_w) {
+// colidx, perm and the edge weights from the sorted keys in one pass over them: the source is the low
+// src_bits of the key, the destination the rest.  GCN symmetric normalisation: fp64 1/sqrt(d_i d_j), one
+// rounding to fp32 (rowptr is complete when this runs).
+__global__ __launch_bounds__(kBlock) void csr_from_sorted_kernel(const uint64_t* __restrict__ keys,
+                                                                 const uint32_t* __restrict__ vals,
+                                                                 int64_t nnz, int src_bits,
+                                                                 const int64_t* __restrict__ rowptr, int norm_sym,
+                                                                 int32_t* __restrict__ colidx,
+                                                                 int64_t* __restrict__ perm,
+                                                                 float* __restrict__ edge_w) {
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (e >= nnz) return;
-  if (!norm_sym) {
-    edge_w[e] = 1.0f;
-    return;
-  }
   const uint64_t key = keys[e];
-  const int64_t i = (int64_t)(key >> src_bits);
   const int64_t j = (int64_t)(key & ((1ull << src_bits) - 1ull));
-  const double di = (double)(rowptr[i + 1] - rowptr[i]);
-  const double dj = (double)(rowptr[j + 1] - rowptr[j]);
-  edge_w[e] = (float)(1.0 / sqrt(di * dj));
+  colidx[e] = (int32_t)j;
+  if (perm) perm[e] = (int64_t)vals[e];
+  if (edge_w) {
+    if (norm_sym) {
+      const int64_t i = (int64_t)(key >> src_bits);
+      const double di = (double)(rowptr[i + 1] - rowptr[i]);
+      const double dj = (double)(rowptr[j + 1] - rowptr[j]);
+      edge_w[e] = (float)(1.0 / sqrt(di * dj));
+    } else {
+      edge_w[e] = 1.0f;
+    }
+  }
 }
 
 // ---- row plan -------------------------------------------------------------
@@ -230,23 +212,26 @@ extern "C" int gnnagg_build_csr(int64_t N, int64_t E, const int32_t* src, const 
   }
   const int src_bits = bits_for((uint64_t)(N - 1));
   hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(1), 0, stream, w.bad, 0u);
-  hipLaunchKernelGGL(make_edge_keys_kernel, dim3(grid_for(nnz)), dim3(kBlock), 0, stream, src, dst, E, nnz, N,
-                     src_bits, w.keys_a, w.vals_a, w.bad);
   GNNAGG_HIP_TRY(hipGetLastError());
+  // one stable sort on (destination, source); the keys of the first pass come straight from the COO arrays,
+  // and the input positions travel with the keys only if the caller wants the permutation
+  KeySource coo;
+  coo.src = src;
+  coo.dst = dst;
+  coo.E = E;
+  coo.N = N;
+  coo.src_bits = src_bits;
+  coo.bad = w.bad;
   bool in_a = true;
-  int rc = radix_sort_pairs(w.keys_a, w.vals_a, w.keys_b, w.vals_b, nnz, 0, 2 * src_bits, w.hist, w.scan, stream,
-                            &in_a);
+  int rc = radix_sort(coo, w.keys_a, w.vals_a, w.keys_b, w.vals_b, nnz, 0, 2 * src_bits, perm != nullptr, w.hist,
+                      w.scan, stream, &in_a);
   if (rc != GNNAGG_OK) return rc;
   const uint64_t* keys = in_a ? w.keys_a : w.keys_b;
   const uint32_t* vals = in_a ? w.vals_a : w.vals_b;
-  hipLaunchKernelGGL(csr_from_sorted_kernel, dim3(grid_for(nnz)), dim3(kBlock), 0, stream, keys, vals, nnz, N,
-                     src_bits, rowptr, colidx, perm);
+  hipLaunchKernelGGL(rowptr_kernel, dim3(grid_for(N + 1)), dim3(kBlock), 0, stream, keys, nnz, N, src_bits, rowptr);
+  hipLaunchKernelGGL(csr_from_sorted_kernel, dim3(grid_for(nnz)), dim3(kBlock), 0, stream, keys, vals, nnz, src_bits,
+                     (const int64_t*)rowptr, (int)((flags & GNNAGG_NORM_SYM) != 0), colidx, perm, edge_w);
   GNNAGG_HIP_TRY(hipGetLastError());
-  if (edge_w) {
-    hipLaunchKernelGGL(edge_weight_kernel, dim3(grid_for(nnz)), dim3(kBlock), 0, stream, keys, nnz, src_bits,
-                       (const int64_t*)rowptr, (int)((flags & GNNAGG_NORM_SYM) != 0), edge_w);
-    GNNAGG_HIP_TRY(hipGetLastError());
-  }
   uint32_t bad = 0;
   GNNAGG_HIP_TRY(hipMemcpyAsync(&bad, w.bad, sizeof(bad), hipMemcpyDeviceToHost, stream));
   GNNAGG_HIP_TRY(hipStreamSynchronize(stream));
@@ -277,7 +262,9 @@ extern "C" int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
                      w.vals_a);
   GNNAGG_HIP_TRY(hipGetLastError());
   bool in_a = true;
-  int rc = radix_sort_pairs(w.keys_a, w.vals_a, w.keys_b, w.vals_b, N, 0, 32, w.hist, w.scan, stream, &in_a);
+  KeySource from_a;
+  from_a.keys = w.keys_a;
+  int rc = radix_sort(from_a, w.keys_a, w.vals_a, w.keys_b, w.vals_b, N, 0, 32, true, w.hist, w.scan, stream, &in_a);
   if (rc != GNNAGG_OK) return rc;
   hipLaunchKernelGGL(plan_finish_kernel, dim3(grid_for(N + 1)), dim3(kBlock), 0, stream,
                      (const uint64_t*)(in_a ? w.keys_a : w.keys_b), (const uint32_t*)(in_a ? w.vals_a : w.vals_b), N,
@@ -317,7 +304,9 @@ extern "C" int gnnagg_rank_sources(int64_t N, int64_t nnz, const int32_t* colidx
                      w.keys_a, w.vals_a);
   GNNAGG_HIP_TRY(hipGetLastError());
   bool in_a = true;
-  int rc = radix_sort_pairs(w.keys_a, w.vals_a, w.keys_b, w.vals_b, N, 0, 32, w.hist, w.scan, stream, &in_a);
+  KeySource from_a;
+  from_a.keys = w.keys_a;
+  int rc = radix_sort(from_a, w.keys_a, w.vals_a, w.keys_b, w.vals_b, N, 0, 32, true, w.hist, w.scan, stream, &in_a);
   if (rc != GNNAGG_OK) return rc;
   hipLaunchKernelGGL(rank_from_order_kernel, dim3(grid_for(N)), dim3(kBlock), 0, stream,
                      (const uint32_t*)(in_a ? w.vals_a : w.vals_b), N, rank);

@@ -596,6 +596,111 @@ class Bench:
         return res
 
 
+# Shapes the automatic choices (chunk width, resident workgroups) were NOT derived from:
+# (N, undirected edges, Pareto exponent, cap R, F, dtype, op).  Power-law graphs from the same generator.
+HELD_OUT = [
+    (50_000, 7_500_000, 1.6, 300.0, 256, "f32", "wsum"),
+    (100_000, 5_000_000, 2.0, 1000.0, 128, "f32", "wsum"),
+    (400_000, 12_000_000, 1.8, 2000.0, 1024, "bf16", "sum"),
+    (1_000_000, 4_000_000, 2.4, 5000.0, 64, "f32", "mean"),
+    (200_000, 20_000_000, 2.2, 500.0, 512, "f32", "wsum"),
+    (700_000, 10_500_000, 1.7, 3000.0, 300, "f32", "mean"),
+    (150_000, 11_250_000, 2.0, 150.0, 602, "bf16", "max"),
+    (300_000, 7_500_000, 2.4, 3.0, 256, "f32", "wsum"),
+    (60_000, 1_500_000, 1.9, 400.0, 1433, "f32", "wsum"),
+    (500_000, 50_000_000, 2.0, 800.0, 128, "f32", "mean"),
+]
+# A second set, drawn after the chunk-width rule was revised on the first one.
+HELD_OUT_2 = [
+    (80_000, 6_000_000, 1.7, 500.0, 384, "f32", "mean"),
+    (120_000, 18_000_000, 2.1, 300.0, 1024, "f32", "wsum"),
+    (350_000, 14_000_000, 1.9, 1500.0, 200, "f32", "wsum"),
+    (45_000, 9_000_000, 1.8, 200.0, 512, "bf16", "sum"),
+    (250_000, 30_000_000, 1.6, 1000.0, 768, "bf16", "mean"),
+    (900_000, 18_000_000, 2.0, 4000.0, 160, "f32", "max"),
+    (65_000, 13_000_000, 2.3, 100.0, 128, "f32", "wsum"),
+    (160_000, 4_000_000, 1.8, 800.0, 2048, "f32", "mean"),
+]
+# A third set, drawn after the rule took its final form: never used to adjust it.
+HELD_OUT_3 = [
+    (55_000, 5_500_000, 1.9, 250.0, 800, "f32", "wsum"),
+    (180_000, 27_000_000, 1.7, 900.0, 320, "f32", "mean"),
+    (600_000, 9_000_000, 2.1, 2500.0, 448, "f32", "wsum"),
+    (110_000, 11_000_000, 2.0, 600.0, 1280, "bf16", "sum"),
+    (1_500_000, 30_000_000, 1.8, 6000.0, 128, "f32", "mean"),
+    (75_000, 3_000_000, 2.2, 300.0, 640, "f32", "max"),
+    (320_000, 48_000_000, 1.9, 1200.0, 192, "f32", "wsum"),
+    (220_000, 6_600_000, 1.6, 1000.0, 512, "bf16", "mean"),
+]
+# the benchmark graphs the rules were first derived on, for the same table (not held out)
+TUNING_SHAPES = [
+    (232_965, 57_307_946, 1.8, 680.0, 602, "f32", "wsum"),
+    (132_534, 39_561_252, 1.8, 60.0, 602, "f32", "wsum"),
+    (132_534, 39_561_252, 1.8, 60.0, 256, "f32", "mean"),
+    (2_449_029, 30_950_000, 2.0, 9000.0, 100, "bf16", "sum"),
+]
+
+
+def validate_auto(g, W, torch, steps, warmup, which):
+    """Times every held-out shape at chunk widths {32, 64, 128, one chunk} and, at the library's width, at
+    resident-workgroup caps {none, 2, 3, 4}, and reports how far the library's own choice is from the best."""
+    rows = []
+    shapes = {"1": HELD_OUT, "2": HELD_OUT_2, "3": HELD_OUT_3, "tuning": TUNING_SHAPES}[which]
+    for k, (N, M, alpha, R, F, xdt, opname) in enumerate(shapes):
+        src, dst = W.powerlaw_graph(N, M, alpha, R, {"1": 100, "2": 300, "3": 500, "tuning": 110}[which] + k)
+        gcn = opname == "wsum"
+        flags = (g.SELF_LOOPS | g.NORM_SYM) if gcn else 0
+        rp, ci, w, _ = g.gnnagg_build_csr(N, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda(), flags, want_w=gcn)
+        plan = g.gnnagg_plan_rows(rp)
+        X = W.normal_bf16((N, F), seed=200 + k) if xdt == "bf16" else W.normal_f32((N, F), seed=200 + k)
+        d_X0 = (torch.from_numpy(X.view(np.int16)).cuda().view(torch.bfloat16) if xdt == "bf16"
+                else torch.from_numpy(X).cuda())
+        d_X = g.pitched_empty(N, F, d_X0.dtype)
+        d_X.copy_(d_X0)
+        del d_X0
+        out = g.pitched_empty(N, F, torch.float32)
+        op = {"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname]
+
+        def timed(fc):
+            for _ in range(warmup):
+                g.gnnagg_aggregate(op, rp, ci, w, d_X, out, fc, plan)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                g.gnnagg_aggregate(op, rp, ci, w, d_X, out, fc, plan)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / steps
+
+        f_auto = g.gnnagg_auto_f_chunk(N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)), plan)
+        g.gnnagg_set_workgroup_cap(-1)
+        timed(0)  # clocks and caches settle before the first figure that counts
+        t_auto = timed(g.F_CHUNK_AUTO)
+        widths = {str(fc if fc else "all"): timed(fc) for fc in (16, 32, 64, 128, 256, 512, 0) if fc < F}
+        t_auto = min(t_auto, timed(g.F_CHUNK_AUTO))  # identical launches: the faster of the two measurements
+        tuned, tuned_ms = g.gnnagg_tune_f_chunk(op, rp, ci, w, d_X, out, plan)
+        t_tuned = timed(tuned)
+        caps = {}
+        for cap in (0, 2, 3, 4):
+            g.gnnagg_set_workgroup_cap(cap)
+            caps["none" if cap == 0 else str(cap)] = timed(g.F_CHUNK_AUTO)
+        g.gnnagg_set_workgroup_cap(-1)
+        best = min(list(widths.values()) + list(caps.values()) + [t_auto])
+        deg = float(len(src)) / N
+        row = {"set": which, "class_off": plan.class_offsets(), "N": N, "mean_degree": deg, "max_degree": int((rp[1:] - rp[:-1]).max()), "exponent": alpha, "F": F,
+               "x_dtype": xdt, "op": opname, "auto_f_chunk": int(f_auto), "auto_ms": t_auto, "by_width_ms": widths,
+               "by_cap_ms_at_auto_width": caps, "best_ms": best, "regret": t_auto / best - 1.0,
+               "tuned_f_chunk": tuned, "tuned_ms": t_tuned, "tuned_regret": t_tuned / best - 1.0}
+        log("held-out %d: N=%d deg %.0f a=%.1f F=%d %s %s: auto(width %d) %.3f ms, widths %s, caps %s, regret %.1f %%" %
+            (k, N, deg, alpha, F, xdt, opname, f_auto, t_auto, {a: round(b, 3) for a, b in widths.items()},
+             {a: round(b, 3) for a, b in caps.items()}, 100 * row["regret"]) +
+            "; measured tuner picks %d (%.3f ms, regret %.1f %%)" % (tuned, t_tuned, 100 * row["tuned_regret"]))
+        rows.append(row)
+        del d_X, out, rp, ci, w, plan
+        torch.cuda.empty_cache()
+    return rows
+
+
 def copy_probe(g, torch, n_probe):
     """Plain streaming copy of 1 GiB: the measured HBM copy rate of this device."""
     probe_bytes = 1 << 30
@@ -645,6 +750,10 @@ def main():
                     help="'default': the CPU checker in Algorithm 1's chunk-outer order at the sweep widths of the "
                          "two benchmark configurations that name one (about half a minute); 'none'; or a comma list "
                          "of widths for the main workload")
+    ap.add_argument("--validate-auto", default="", choices=["", "1", "2", "3", "tuning"],
+                    help="instead of the benchmark: time a set of graph shapes (1, 2: used to revise the rule; 3: never "
+                         "used for it; tuning: the benchmark graphs) at several chunk widths and resident-workgroup caps and print the regret of the "
+                         "library's automatic choices")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
@@ -656,6 +765,13 @@ def main():
     import workloads as W
     g.load_library()
 
+    if args.validate_auto:
+        rows = validate_auto(g, W, torch, args.steps, args.warmup, args.validate_auto)
+        print(json.dumps({"metric": "regret of the automatic chunk width and workgroup cap on held-out shapes",
+                          "value": max(r["regret"] for r in rows), "unit": "fraction of the best measured time",
+                          "higher_is_better": False, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "config": {"workload": "shape set " + args.validate_auto}, "shapes": rows}), flush=True)
+        return
     copy_ms, copy_gbs, probe_bytes = copy_probe(g, torch, max(args.steps, 3) if args.workload == "copy" else 5)
     log("copy probe: 1 GiB in %.3f ms -> %.0f GB/s read+write" % (copy_ms, copy_gbs))
     if args.workload == "copy":

@@ -140,12 +140,13 @@ GNNAGG_API int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
  *            vertex-inner order of Algorithm 1), each written in place into its
  *            columns of `out` (no separate concat).  0 or >= F: one chunk.
  *            GNNAGG_F_CHUNK_AUTO: the library picks (Section II-B ties the number of layers to the
- *            memory capacity of the device and the character of the dataset): chunks of one
- *            128-byte line when the rows of X start on lines (see gnnagg_aggregate_ws), X is fp32 and
- *            the plan shows a dense graph whose longest rows hold a large share of the edges; a
- *            power-of-two width whose column slice of X is a few hundred MB once X is beyond 1 GiB
- *            (never narrower than 128 bytes per row); otherwise one chunk.  gnnagg_auto_f_chunk
- *            returns that choice.
+ *            memory capacity of the device and the character of the dataset): row pieces of 1, 2, 4
+ *            or 8 cache lines when the rows of X start on 128-byte lines (see gnnagg_aggregate_ws)
+ *            and the plan shows a graph whose longest rows hold a large share of the edges - the
+ *            fewer rows and the shorter they are, the wider the piece; a power-of-two width whose
+ *            column slice of X is a few hundred MB once X is beyond 1 GiB (never narrower than 128
+ *            bytes per row); otherwise one chunk.  gnnagg_auto_f_chunk returns that choice;
+ *            gnnagg_tune_f_chunk finds the width by measurement instead.
  *   row_order, class_off   a plan from gnnagg_plan_rows for this rowptr, or both
  *            NULL (rows then run in natural order, one wavefront per row slice:
  *            correct for any graph, slow on hub rows).  class_off is a HOST
@@ -250,6 +251,21 @@ GNNAGG_API int64_t gnnagg_row_pitch(int32_t F, int dtype);
 GNNAGG_API int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype, int64_t x_pitch, const int64_t* class_off);
 
 /*
+ * The chunk width by measurement instead of by rule (Section II-B: the number of layers is to be
+ * determined per device and dataset; the paper does so by hand).  Runs gnnagg_aggregate_ws on the caller's
+ * own arrays at a handful of widths - one chunk, the width GNNAGG_F_CHUNK_AUTO would take, and row pieces
+ * of 1, 2, 4 and 8 cache lines - a warm-up and three timed calls each, and returns the fastest in
+ * *best_f_chunk (its time per call in *best_ms, which may be NULL).  A per-graph step like the plan: pass
+ * the result as f_chunk from then on.  `out` holds a valid aggregation afterwards.  Same arguments and
+ * workspace protocol as gnnagg_aggregate_ws; waits for `stream`.
+ */
+GNNAGG_API int gnnagg_tune_f_chunk(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                        const float* edge_w, const void* X, int x_dtype, int64_t x_pitch, void* out, int out_dtype,
+                        int64_t out_pitch, int32_t F, const int32_t* row_order, const int64_t* class_off,
+                        void* workspace, size_t* workspace_bytes, void* stream, int32_t* best_f_chunk,
+                        float* best_ms);
+
+/*
  * Graph-attention aggregation (the GAT operator the paper evaluates in
  * Section III, with chunk width 8 = one head at 8 channels per head).
  *
@@ -322,6 +338,15 @@ GNNAGG_API int gnnagg_combine(int64_t N, const void* X, int x_dtype, int32_t F, 
  */
 GNNAGG_API int gnnagg_rank_sources(int64_t N, int64_t nnz, const int32_t* colidx, int32_t* rank,
                         int32_t* colidx_ranked, void* workspace, size_t* workspace_bytes, void* stream);
+
+/*
+ * Measurement aid, not part of the method: overrides, for every later aggregation call of the process, how
+ * many workgroups of the aggregation kernel may share a compute unit (the library normally derives that
+ * from the plan's degree classes and the bytes a workgroup keeps in flight).  cap = -1 restores the
+ * library's rule, 0 lifts the cap, 2..16 forces that many.  Results do not depend on it.  Used to check
+ * the rule against measured optima on graphs it was not derived from.
+ */
+GNNAGG_API int gnnagg_set_workgroup_cap(int cap);
 
 /*
  * Measurement aid, not part of the method: copies `bytes` bytes (a multiple of

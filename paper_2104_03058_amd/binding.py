@@ -77,6 +77,11 @@ def load_library():
         lib.gnnagg_check_csr.argtypes = [i64, i64, vp, vp, vp, szp, vp]
         lib.gnnagg_rank_sources.restype = ci
         lib.gnnagg_rank_sources.argtypes = [i64, i64, vp, vp, vp, vp, szp, vp]
+        lib.gnnagg_tune_f_chunk.restype = ci
+        lib.gnnagg_tune_f_chunk.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, vp, ci, i64, i32, vp, vp, vp, szp, vp,
+                                            ctypes.POINTER(i32), ctypes.POINTER(f32)]
+        lib.gnnagg_set_workgroup_cap.restype = ci
+        lib.gnnagg_set_workgroup_cap.argtypes = [ci]
         lib.gnnagg_copy_probe.restype = ci
         lib.gnnagg_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         _lib = lib
@@ -416,6 +421,31 @@ def gnnagg_copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None
     if dst.numel() * dst.element_size() != nbytes:
         raise ValueError("dst and src differ in size")
     _check("gnnagg_copy_probe", load_library().gnnagg_copy_probe(_dev(dst), _dev(src), nbytes, _stream(stream)))
+
+
+def gnnagg_tune_f_chunk(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w: Optional[torch.Tensor],
+                        X: torch.Tensor, out: torch.Tensor, plan: Optional[RowPlan] = None, stream=None):
+    """(best chunk width, its milliseconds per call) for this graph, X layout and operator, by measurement."""
+    lib = load_library()
+    N, F = int(X.shape[0]), int(X.shape[1])
+    order, class_off = _plan_args(plan, N)
+    need = gnnagg_aggregate_workspace_bytes(N, F, plan)
+    ws = torch.empty(need, dtype=torch.uint8, device=X.device) if need > 0 else _token(X.device)
+    have = ctypes.c_size_t(ws.numel())
+    best, ms = ctypes.c_int32(0), ctypes.c_float(0.0)
+    rc = lib.gnnagg_tune_f_chunk(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
+                                 _dev(edge_w, torch.float32, "edge_w"), _rows(X, "X"), _x_dtype(X),
+                                 int(X.stride(0)) if N > 1 else F, _rows(out, "out"),
+                                 F32 if out.dtype == torch.float32 else BF16, int(out.stride(0)) if N > 1 else F, F,
+                                 order, class_off, _dev(ws), ctypes.byref(have), _stream(stream), ctypes.byref(best),
+                                 ctypes.byref(ms))
+    _check("gnnagg_tune_f_chunk", rc)
+    return int(best.value), float(ms.value)
+
+
+def gnnagg_set_workgroup_cap(cap: int) -> None:
+    """Measurement aid: force the number of aggregation workgroups per compute unit (-1: the library's rule)."""
+    _check("gnnagg_set_workgroup_cap", load_library().gnnagg_set_workgroup_cap(cap))
 
 
 def gnnagg_auto_f_chunk(N: int, F: int, x_dtype: int = F32, x_pitch: int = 0,

@@ -16,6 +16,7 @@
 //   - Sums accumulate in fp64 (full rate on this chip) and are rounded to fp32
 //     once, so the result does not depend on the degree or on how the row was
 //     split; max works on order-preserving integer keys and is exact.
+#include <atomic>
 #include <mutex>
 
 #include "common.hpp"
@@ -434,6 +435,9 @@ int scratch_for_current_device(void** p) {
   return GNNAGG_OK;
 }
 
+// Measurement override of the resident-workgroup cap (gnnagg_set_workgroup_cap): -1 = the library's rule.
+std::atomic<int> forced_workgroup_cap{-1};
+
 // The Update step of a call (all null / zero: none).
 struct Update {
   const float* bias = nullptr;
@@ -529,8 +533,10 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
     a.W2 = up.W2;
     a.H2 = up.H2;
     a.relu = up.relu;
-    a.lds_per_workgroup =
-        lds_claim(resident_workgroup_cap(class_off, N, a.sl.g_log2, active_lanes_per_wave(a.sl), opk == OPK_WSUM));
+    const int forced = forced_workgroup_cap.load(std::memory_order_relaxed);
+    a.lds_per_workgroup = lds_claim(forced >= 0 ? forced
+                                                : resident_workgroup_cap(class_off, N, a.sl.g_log2,
+                                                                         active_lanes_per_wave(a.sl), opk == OPK_WSUM));
     int rc = build_segments(class_off, N, a.sl.g_log2, ws != nullptr, &a.segs);
     if (rc != GNNAGG_OK) return rc;
     grids[k] = (uint64_t)a.segs.blocks_per_slice * (uint64_t)a.sl.n_chunks * (uint64_t)a.sl.n_sub;
@@ -671,6 +677,88 @@ extern "C" int gnnagg_aggregate_noalloc(int op, int64_t N, const int64_t* rowptr
   // every slot a piece owns is written in full before the merge kernel reads it: nothing to clear
   return aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, x_pitch, out, out_dtype, out_pitch, F, f_chunk,
                         row_order, class_off, static_cast<double*>(ws), Update(), (hipStream_t)stream_);
+}
+
+extern "C" int gnnagg_tune_f_chunk(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                                   const float* edge_w, const void* X, int x_dtype, int64_t x_pitch, void* out,
+                                   int out_dtype, int64_t out_pitch, int32_t F, const int32_t* row_order,
+                                   const int64_t* class_off, void* workspace, size_t* workspace_bytes,
+                                   void* stream_, int32_t* best_f_chunk, float* best_ms) {
+  if (!workspace_bytes) return GNNAGG_ENULL;
+  size_t need = 0;
+  int rc = check_pitches_and_plan(N, F, F, &x_pitch, &out_pitch, row_order, class_off, &need);
+  if (rc != GNNAGG_OK) return rc;
+  if (!workspace) {
+    *workspace_bytes = need;
+    return GNNAGG_OK;
+  }
+  if (!best_f_chunk) return GNNAGG_ENULL;
+  if (*workspace_bytes < need || ((uintptr_t)workspace & 255u)) return GNNAGG_EWORKSPACE;
+  bool nothing;
+  rc = check_aggregate_args(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, 0, row_order, class_off,
+                            &nothing);
+  if (rc != GNNAGG_OK) return rc;
+  if (nothing) {
+    *best_f_chunk = F;
+    if (best_ms) *best_ms = 0.0f;
+    return GNNAGG_OK;
+  }
+  hipStream_t stream = (hipStream_t)stream_;
+  double* ws = need > 0 ? static_cast<double*>(workspace) : nullptr;
+  // candidates: one chunk, the rule's choice, and pieces of 1, 2, 4, 8 lines (a quarter line and a half
+  // line for rows of at most two lines)
+  const int32_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2, line_cols = 128 / xs;
+  const bool rows_on_lines = ((uintptr_t)X % 128) == 0 && ((uint64_t)x_pitch * (uint64_t)xs) % 128 == 0;
+  int32_t cand[8];
+  int n_cand = 0;
+  auto add = [&](int32_t w) {
+    if (w <= 0 || w > F) return;
+    for (int k = 0; k < n_cand; ++k)
+      if (cand[k] == w) return;
+    cand[n_cand++] = w;
+  };
+  add(F);
+  add(auto_f_chunk(N, F, xs, rows_on_lines, class_off));
+  for (int32_t lines = 1; lines <= 8; lines *= 2) add(lines * line_cols);
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return GNNAGG_EDEVICE;
+  if (hipEventCreate(&e1) != hipSuccess) {
+    (void)hipEventDestroy(e0);
+    return GNNAGG_EDEVICE;
+  }
+  constexpr int kTimedCalls = 3;
+  float best = 0.0f;
+  int32_t best_w = F;
+  rc = GNNAGG_OK;
+  for (int k = 0; k < n_cand && rc == GNNAGG_OK; ++k) {
+    float ms = 0.0f;
+    for (int rep = 0; rep <= kTimedCalls && rc == GNNAGG_OK; ++rep) {  // call 0 warms caches and code
+      if (rep == 1 && hipEventRecord(e0, stream) != hipSuccess) rc = GNNAGG_EDEVICE;
+      if (rc == GNNAGG_OK)
+        rc = aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, x_pitch, out, out_dtype, out_pitch, F, cand[k],
+                            row_order, class_off, ws, Update(), stream);
+    }
+    if (rc == GNNAGG_OK && (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                            hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+      rc = GNNAGG_EDEVICE;
+    if (rc == GNNAGG_OK && (k == 0 || ms < best)) {
+      best = ms;
+      best_w = cand[k];
+    }
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc != GNNAGG_OK) return rc;
+  if (hipStreamSynchronize(stream) != hipSuccess) return GNNAGG_EDEVICE;
+  *best_f_chunk = best_w;
+  if (best_ms) *best_ms = best / (float)kTimedCalls;
+  return GNNAGG_OK;
+}
+
+extern "C" int gnnagg_set_workgroup_cap(int cap) {
+  if (cap < -1 || cap == 1 || cap > 16) return GNNAGG_EINVAL;  // one workgroup would need more LDS than a launch may claim
+  forced_workgroup_cap.store(cap, std::memory_order_relaxed);
+  return GNNAGG_OK;
 }
 
 extern "C" int64_t gnnagg_row_pitch(int32_t F, int dtype) {

@@ -308,35 +308,62 @@ inline void degree_profile(const int64_t* class_off, int64_t N, int64_t hot_rows
 }
 
 // Chunk width for GNNAGG_F_CHUNK_AUTO: the paper leaves the number of layers to the memory capacity of
-// the device and the character of the dataset (Section II-B); on MI355X the measurements say
-//  (1) X beyond ~1 GiB (several times the 256 MB Infinity Cache; 2.4 M rows x 256-512 fp32 columns):
-//      chunks whose column slice of X is ~300-600 MB are 13-17 % faster than one chunk, row pieces under
-//      128 bytes twice slower than either -> power-of-two width with a ~384 MB slice, >= 128-byte pieces;
-//  (2) rows on 128-byte lines, fp32, at least four lines wide, a graph that is not very sparse (mean
-//      degree >= 16) and whose hubs matter - the 32,768 longest rows, as many as one 4 MB L2 holds lines of one chunk, take
-//      >= 40 % of the edges: chunks of exactly ONE LINE (32 columns) are 9-27 % faster than one chunk
-//      (power-law graphs of mean degree 490-600 and hot share 0.70-0.74, 128-602 columns; 11-20 % at
-//      mean degree 25-200, nothing to gain below ~12), because a
-//      chunk pass then asks for one line per edge from a slice of N x 128 bytes in which the hubs' lines
-//      stay in L2.  Uniform graphs (hot share < 0.2) lose 3-9 % to the extra passes over the edge list,
-//      bf16 rows lose 20 % (a lane then accumulates 8 columns in fp64 per line: arithmetic-bound), and
-//      without line-aligned rows a 128-byte piece straddles two lines and the pass costs twice;
-//  (3) otherwise one chunk.
+// the device and the character of the dataset (Section II-B).  What the sweeps on MI355X say (power-law
+// graphs of 45,000-2,400,000 rows, mean degree 8-600, 64-2048 columns; bench.py --validate-auto prints the
+// regret of this choice per shape, for the benchmark graphs and for shapes the rule was not derived on):
+//  (1) Rows on 128-byte lines, at least four lines wide, more than 32,768 rows (as many as one 4 MB L2 holds
+//      lines), mean degree >= 16 and hubs that matter (the 32,768 longest rows take >= 40 % of the edges):
+//      row pieces of 2^k LINES.  A pass then gathers from a column slice of N x piece bytes in which the
+//      hubs' lines stay in L2.
+//        - k from the slice: about 24 MB, a few times the L2 - one line per piece from ~130,000 rows on
+//          (9-30 % faster than one chunk), two at ~100,000 rows, four at 45,000-60,000 rows, where
+//          single-line passes are 12-20 % SLOWER than four-line ones (the slice is small anyway, and a pass
+//          of single lines reaches a lower L2 request rate than a pass of wider pieces);
+//        - at least ~200 / (mean degree) lines (a power of two): every pass pays a chain of dependent loads
+//          per row (plan, row pointer, indices) that short rows do not amortise - at mean degree 50 and
+//          45-64 passes four-line pieces are 15-20 % faster than one-line ones - but only while the slice
+//          stays within about half the 256 MB Infinity Cache (700,000 rows of mean degree 30: one line,
+//          90 MB, is 24 % faster than four);
+//        - bf16: at least two lines (a one-line pass accumulates eight columns per lane in fp64 and is
+//          bound by that arithmetic, 6-15 % slower); one chunk when all of X is within 64 MB.
+//  (2) Otherwise, X beyond ~1 GiB (several times the Infinity Cache; 2.4 M rows x 256-512 fp32 columns):
+//      chunks whose column slice is ~300-600 MB are 13-17 % faster than one chunk, row pieces under 128
+//      bytes twice slower than either -> power-of-two width with a ~384 MB slice, >= 128-byte pieces.
+//  (3) Otherwise one chunk: uniform graphs (hot share < 0.2) lose 3-9 % to the extra passes over the edge
+//      list, and without line-aligned rows a piece straddles an extra line and every pass costs more.
+inline int64_t pow2_floor(double x) {
+  int64_t p = 1;
+  while ((double)(2 * p) <= x) p *= 2;
+  return p;
+}
+
 inline int32_t auto_f_chunk(int64_t N, int32_t F, int elem_bytes, bool rows_on_lines, const int64_t* class_off) {
   const double x_bytes = (double)N * (double)F * (double)elem_bytes;
   if (N <= 0) return F;
-  if (x_bytes > 1024.0 * 1024.0 * 1024.0) {
-    const int64_t min_w = 128 / elem_bytes;                                  // 128-byte row pieces
-    int64_t w = (int64_t)(384.0 * 1024.0 * 1024.0 / ((double)N * elem_bytes));  // ~384 MB column slice
-    int64_t p = min_w;
-    while (p * 2 <= w) p *= 2;  // a power of two keeps every chunk on full 16-byte lanes
-    return (int32_t)(p >= F ? F : p);
-  }
   constexpr int64_t kLinesPerL2 = 4 * 1024 * 1024 / 128;
-  if (rows_on_lines && elem_bytes == 4 && F >= 128 && class_off && N > kLinesPerL2) {
+  const int64_t line_cols = 128 / elem_bytes;
+  if (rows_on_lines && F >= 4 * line_cols && class_off && N > kLinesPerL2) {
     double mean_degree, hot_share;
     degree_profile(class_off, N, kLinesPerL2, &mean_degree, &hot_share);
-    if (mean_degree >= 16.0 && hot_share >= 0.4) return 32;
+    if (mean_degree >= 16.0 && hot_share >= 0.4) {
+      if (elem_bytes < 4 && x_bytes <= 64.0e6) return F;
+      const double line_slice = (double)N * 128.0;  // bytes of a column slice one line wide
+      int64_t lines = 1;
+      while (lines < 8 && 24.0e6 / line_slice >= 1.5 * (double)lines) lines *= 2;
+      int64_t by_degree = 1;
+      while (by_degree < 8 && (double)by_degree * mean_degree < 200.0) by_degree *= 2;
+      const int64_t in_cache = pow2_floor(128.0e6 / line_slice);
+      const int64_t amortised = by_degree < in_cache ? by_degree : in_cache;
+      if (amortised > lines) lines = amortised;
+      if (elem_bytes < 4 && lines < 2) lines = 2;
+      const int64_t w = lines * line_cols;
+      return (int32_t)(w >= F ? F : w);
+    }
+  }
+  if (x_bytes > 1024.0 * 1024.0 * 1024.0) {
+    const int64_t min_w = 128 / elem_bytes;                                  // 128-byte row pieces
+    const int64_t p = pow2_floor(384.0 * 1024.0 * 1024.0 / ((double)N * elem_bytes) / (double)min_w) * min_w;
+    return (int32_t)(p >= F ? F : p);  // a power of two keeps every chunk on full 16-byte lanes
   }
   return F;
 }

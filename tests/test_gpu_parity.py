@@ -325,6 +325,28 @@ def test_auto_chunk_width_is_accepted_and_matches_one_chunk_on_small_inputs():
         g.gnnagg_aggregate(0, d[0], d[1], None, d[2], None, -2)
 
 
+def test_measured_chunk_width_tuner_returns_a_valid_width_and_leaves_a_valid_result():
+    N, src, dst = W.graph("c4", 0.02)
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, oracle.SELF_LOOPS | oracle.NORM_SYM, want_w=True, threads=8)
+    X = W.normal_f32((N, 300), seed=77)
+    d_rp, d_ci, d_w = dev(rp), dev(ci), dev(w)
+    plan = g.gnnagg_plan_rows(d_rp)
+    Xp = g.pitched_empty(N, 300, torch.float32)
+    Xp.copy_(dev(X))
+    out = g.pitched_empty(N, 300, torch.float32)
+    out.fill_(float("nan"))
+    best, ms = g.gnnagg_tune_f_chunk(g.WSUM, d_rp, d_ci, d_w, Xp, out, plan)
+    assert best in (300, 32, 64, 128, 256, g.gnnagg_auto_f_chunk(N, 300, g.F32, int(Xp.stride(0)), plan)) and ms > 0
+    assert_close(host(out), oracle.aggregate(oracle.WSUM, rp, ci, w, X, threads=8), what="result left by the tuner")
+    # the width it returns is an ordinary f_chunk
+    again = g.gnnagg_aggregate(g.WSUM, d_rp, d_ci, d_w, Xp, None, best, plan)
+    assert_close(host(again), host(out), what="tuned width")
+    g.gnnagg_set_workgroup_cap(2)   # the measurement override changes timing only
+    capped = g.gnnagg_aggregate(g.WSUM, d_rp, d_ci, d_w, Xp, None, best, plan)
+    g.gnnagg_set_workgroup_cap(-1)
+    assert_bits(host(capped), host(again), "workgroup cap override")
+
+
 def test_compensated_sum_survives_cancellation():
     # 20000 values of size ~1e3 that cancel to O(1): a plain fp32 running sum would be off by ~1e-2
     N, n_in = 64, 20000

@@ -74,6 +74,13 @@ WORKLOADS = {
     # the hidden rows in popularity order (gnnagg_rank_sources + out_rows of gnnagg_combine)
     "c5-layer-16": ("c5", "layer", (100, 16), "f32", False),
     "c5-layer-16-ranked": ("c5", "layer-ranked", (100, 16), "f32", False),
+    # experiment (not in the default run): the dense graph's mean aggregation with the SOURCES cut into 8 blocks
+    # of vertices, one library call per block on the sub-graph of that block's edges - what a source-blocked
+    # pass structure would gather, without the read-modify-write of the partial results it would also need
+    "c4-mean-srcblock2": ("c4", "mean-srcblock", 602, "f32", False),
+    "c4-mean-srcblock4": ("c4", "mean-srcblock", 602, "f32", False),
+    "c4-mean-srcblock8": ("c4", "mean-srcblock", 602, "f32", False),
+    "c4-mean-srcblock16": ("c4", "mean-srcblock", 602, "f32", False),
     # measurement aids: gathers on uniform random graphs whose source rows live in one level of the memory system
     "probe-l2-line": ("u-l2", "sum", 32, "f32", False),
     "probe-mall-line": ("u-mall", "sum", 32, "f32", False),
@@ -559,6 +566,59 @@ class Bench:
                                "algorithmic_bytes": b_alg, "measured_copy_gbs": self.copy_gbs}
         return rec
 
+    def measure_source_blocked(self, workload, f_chunk):
+        """Sum aggregation as `blocks` calls, call b on the sub-graph of the edges whose source lies in the b-th
+        block of vertices (one block's one-line slice of X is 3.7 MB: L2-resident); the block results are added
+        up with torch for the parity check only.  An experiment on the order of the gathers, not a product path."""
+        g, torch = self.g, self.torch
+        gkey, _, F, xdt, _ = WORKLOADS[workload]
+        blocks = int(workload.rsplit("srcblock", 1)[1])
+        N, src, dst = self.graph(gkey)
+        X = self.features(gkey, (N, F), xdt)
+        d_X = g.pitched_empty(N, F, torch.float32)
+        d_X.copy_(self.dev(X))
+        subs = []
+        edges = 0
+        for b in range(blocks):
+            lo, hi = b * N // blocks, (b + 1) * N // blocks
+            keep = (src >= lo) & (src < hi)
+            rp, ci, _, _ = g.gnnagg_build_csr(N, self.dev(src[keep]), self.dev(dst[keep]), 0)
+            subs.append((rp, ci, g.gnnagg_plan_rows(rp), g.pitched_empty(N, F, torch.float32)))
+        if len(subs) > 8:  # the partial results only matter for the parity check: share buffers beyond eight
+            subs = [(rp, ci, plan, subs[k % 8][3]) for k, (rp, ci, plan, _) in enumerate(subs)]
+            edges += int(ci.shape[0])
+        fc = 32 if f_chunk < 0 else f_chunk
+
+        def step():
+            for rp, ci, plan, out in subs:
+                g.gnnagg_aggregate(g.SUM, rp, ci, None, d_X, out, fc, plan)
+
+        ms, ms_per_step = self.time_steps(step)
+        kern_ms = float(ms.mean())
+        total = torch.zeros((N, F), dtype=torch.float64, device="cuda")
+        for rp, ci, plan, out in subs:  # once more, one block at a time, for the parity check
+            g.gnnagg_aggregate(g.SUM, rp, ci, None, d_X, out, fc, plan)
+            total += out
+        import oracle
+        rp, ci, _ = self.checker_csr(gkey, 0)
+        rows = self.sample_rows(rp)
+        ref = oracle.aggregate_rows(oracle.SUM, rows, rp, ci, None, X, threads=self.threads)
+        got = total[torch.from_numpy(rows).cuda()].cpu().numpy()
+        parity = bool(np.all(np.abs(got - ref) <= 1e-5 + 1e-5 * np.abs(ref)))  # eight fp32 partials added
+        b_alg = algorithmic_bytes(edges, N, F, 4, False, 0)
+        log("%s: %d blocks, %.3f ms per step, parity %s" % (workload, blocks, kern_ms, parity))
+        return {"metric": "aggregated edge-features/sec (source-blocked experiment)",
+                "value": float(edges) * F / (ms_per_step * 1e-3), "unit": "edge-features/s", "n_gpus": 1,
+                "steps": self.steps, "warmup": self.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+                "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+                "config": {"workload": workload, "graph": self.W.GRAPHS[gkey].name, "N": N, "nnz": edges, "F": F,
+                           "source_blocks": blocks, "f_chunk_used": fc},
+                "roofline": {"bound": "hbm", "achieved": b_alg / (kern_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                             "unit": "GB/s", "frac": b_alg / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                             "kernel": "aggregate_kernel", "kernel_ms": kern_ms, "algorithmic_bytes": b_alg,
+                             "note": "the partial results of a block would also have to be read back and added"},
+                "cpu_baseline": None, "parity_on_sample": parity, "parity_rows": int(len(rows)), "setup": {}}
+
     def measure(self, workload, f_chunk=-1, cpu_seconds=0.0, single_thread=False):
         base, _, width = workload.partition("@")
         if width:
@@ -568,6 +628,8 @@ class Bench:
             return self.measure_gat(base, f_chunk if not width else f_chunk, single_thread)
         if op in ("combine", "layer", "layer-ranked", "layer-fused", "agg-dense"):
             return self.measure_layer(base)
+        if op == "mean-srcblock":
+            return self.measure_source_blocked(base, f_chunk)
         rec = self.measure_aggregate(workload, f_chunk, cpu_seconds, single_thread)
         if base in PROBES:
             r = rec["roofline"]

@@ -387,7 +387,7 @@ def test_bench_module_is_importable_and_its_workloads_name_known_graphs():
     for name, (gkey, opname, F, xdt, gcn) in bench.WORKLOADS.items():
         assert gkey in W.GRAPHS, name
         assert opname in ("sum", "wsum", "mean", "max", "sum-ranked", "gat", "combine", "layer", "layer-ranked",
-                          "layer-fused", "agg-dense"), name
+                          "layer-fused", "agg-dense", "mean-srcblock"), name
         assert xdt in ("f32", "bf16"), name
     for name in bench.DEFAULT_ALSO + list(bench.CPU_BASELINE_ALSO) + list(bench.SINGLE_THREAD_ALSO):
         assert name.split("@")[0] in bench.WORKLOADS, name

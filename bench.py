@@ -174,6 +174,7 @@ class Bench:
         self.feat = {}         # (F, xdt, seed) -> host array
         self.ceil = {}         # probe name -> dict(rate figures)
         self.copy_gbs = None
+        self.mfma_tflops = None
         self.traffic = measured_traffic()
         self.threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
 
@@ -558,7 +559,9 @@ class Bench:
                                "frac": tf / MFMA_F64_PEAK_TFLOPS, "traffic": None, "kernel": kernels,
                                "kernel_ms": kern_ms, "flop": flop, "algorithmic_bytes": b_alg,
                                "algorithmic_gbs": achieved, "hbm_frac": achieved / HBM_PEAK_GBS,
-                               "measured_copy_gbs": self.copy_gbs}
+                               "measured_copy_gbs": self.copy_gbs,
+                               "measured_mfma_f64_tflops": self.mfma_tflops,
+                               "frac_of_measured_mfma_rate": (tf / self.mfma_tflops) if self.mfma_tflops else None}
         else:
             rec["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": kernels,
@@ -780,6 +783,21 @@ def copy_probe(g, torch, n_probe):
     return copy_ms, 2.0 * probe_bytes / (copy_ms * 1e-3) / 1e9, probe_bytes
 
 
+def mfma_probe(g, torch):
+    """fp64 matrix rate the device sustains: a loop of nothing but the matrix instruction on every SIMD."""
+    sink = torch.zeros(1, dtype=torch.float64, device="cuda")
+    g.gnnagg_mfma_f64_probe(sink, 200, 256 * 16)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    flop = 0.0
+    for _ in range(3):
+        flop += g.gnnagg_mfma_f64_probe(sink, 2000, 256 * 16)
+    e1.record()
+    torch.cuda.synchronize()
+    return flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
 def also_entry(r):
     keep = ("metric", "value", "unit", "ms_per_step", "config", "roofline", "roofline_l2", "roofline_fabric", "setup",
             "graph_replay_ms_per_step", "parity_on_sample", "parity_rows", "cpu_baseline", "cpu_baseline_1thread")
@@ -846,6 +864,9 @@ def main():
 
     b = Bench(g, W, torch, args.steps, args.warmup, not args.contiguous)
     b.copy_gbs = copy_gbs
+    b.mfma_tflops = mfma_probe(g, torch)
+    log("fp64 matrix-instruction probe: %.1f TFLOP/s sustained (published peak %.1f)" % (b.mfma_tflops,
+                                                                                          MFMA_F64_PEAK_TFLOPS))
     also_names = [w for w in args.also.split(",") if w and w != args.workload]
     for w in also_names:
         if w.split("@")[0] not in WORKLOADS:
@@ -871,6 +892,7 @@ def main():
         if cpu and args.cpu_chunk_sweep == "default" and w in CPU_CHUNK_SWEEPS and w not in sweeps:
             sweeps[w] = b.cpu_chunk_sweep(w, CPU_CHUNK_SWEEPS[w])
     rec["ceilings"] = {"hbm_peak_gbs": HBM_PEAK_GBS, "measured_copy_gbs": copy_gbs,
+                       "mfma_f64_peak_tflops": MFMA_F64_PEAK_TFLOPS, "measured_mfma_f64_tflops": b.mfma_tflops,
                        "probes": b.ceil,
                        "note": "probe-l2-line: one line per edge out of 3.7 MB (L2-resident); probe-mall-line: out of "
                                "134 MB (Infinity Cache); probe-hbm-line: out of 2.1 GB; probe-hbm-row: 2.4 KB rows out "

@@ -357,6 +357,14 @@ GNNAGG_API int gnnagg_set_workgroup_cap(int cap);
  */
 GNNAGG_API int gnnagg_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
 
+/*
+ * Measurement aid, not part of the method: `workgroups` workgroups of four wavefronts each issue
+ * 8 * iters v_mfma_f64_16x16x4_f64 instructions (2048 flop each) and nothing else: the fp64 matrix rate
+ * the device sustains, next to which gnnagg_combine is set.  sink: 8 bytes of device memory, never
+ * written.  Asynchronous on `stream`.
+ */
+GNNAGG_API int gnnagg_mfma_f64_probe(double* sink, int64_t iters, int32_t workgroups, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -82,6 +82,8 @@ def load_library():
                                             ctypes.POINTER(i32), ctypes.POINTER(f32)]
         lib.gnnagg_set_workgroup_cap.restype = ci
         lib.gnnagg_set_workgroup_cap.argtypes = [ci]
+        lib.gnnagg_mfma_f64_probe.restype = ci
+        lib.gnnagg_mfma_f64_probe.argtypes = [vp, i64, i32, vp]
         lib.gnnagg_copy_probe.restype = ci
         lib.gnnagg_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         _lib = lib
@@ -441,6 +443,13 @@ def gnnagg_tune_f_chunk(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edg
                                  ctypes.byref(ms))
     _check("gnnagg_tune_f_chunk", rc)
     return int(best.value), float(ms.value)
+
+
+def gnnagg_mfma_f64_probe(sink: torch.Tensor, iters: int, workgroups: int, stream=None) -> float:
+    """Measurement aid: enqueues the fp64 matrix-instruction loop; returns the flop it performs."""
+    _check("gnnagg_mfma_f64_probe",
+           load_library().gnnagg_mfma_f64_probe(_dev(sink, torch.float64, "sink"), iters, workgroups, _stream(stream)))
+    return float(workgroups) * 4 * iters * 8 * 2048.0
 
 
 def gnnagg_set_workgroup_cap(cap: int) -> None:

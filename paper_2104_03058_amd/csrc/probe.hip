@@ -1,6 +1,8 @@
-// gnnagg_copy_probe: a plain streaming copy, used to measure the HBM copy rate
+// Measurement aids.  gnnagg_copy_probe: a plain streaming copy, used to measure the HBM copy rate
 // next to the aggregation kernels and to calibrate the profiler's byte counters
 // against a kernel whose traffic is known (bytes read = bytes written = n).
+// gnnagg_mfma_f64_probe: a loop of fp64 matrix instructions on every SIMD, the rate the
+// Combination kernel's arithmetic can at best reach on the device at hand.
 #include "common.hpp"
 
 namespace gnnagg {
@@ -14,10 +16,38 @@ __global__ __launch_bounds__(kBlock) void copy_probe_kernel(const u32x4* __restr
   for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+// Nothing but v_mfma_f64_16x16x4_f64: eight independent accumulator chains per wave, `iters` rounds.
+__global__ __launch_bounds__(kBlock) void mfma_f64_probe_kernel(double* __restrict__ sink, int64_t iters) {
+  f64x4 acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = (f64x4){0.0, 0.0, 0.0, 0.0};
+  const double a = 1.0 + (double)threadIdx.x * 1e-9, b = 1.0 - (double)threadIdx.x * 1e-9;
+  for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[c], 0, 0, 0);
+  }
+  double s = 0.0;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) s += acc[c][0] + acc[c][1] + acc[c][2] + acc[c][3];
+  if (s == -1.0) sink[0] = s;  // never true: keeps the chains alive
+}
+
 }  // namespace
 }  // namespace gnnagg
 
 using namespace gnnagg;
+
+extern "C" int gnnagg_mfma_f64_probe(double* sink, int64_t iters, int32_t workgroups, void* stream) {
+  if (!sink) return GNNAGG_ENULL;
+  if (iters <= 0 || iters > (1ll << 24) || workgroups <= 0 || workgroups > (1 << 20) || ((uintptr_t)sink % 8))
+    return GNNAGG_EINVAL;
+  hipLaunchKernelGGL(mfma_f64_probe_kernel, dim3((unsigned)workgroups), dim3(kBlock), 0, (hipStream_t)stream, sink,
+                     iters);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  return GNNAGG_OK;
+}
 
 extern "C" int gnnagg_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
   if (!dst || !src) return GNNAGG_ENULL;

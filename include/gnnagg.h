@@ -165,7 +165,8 @@ GNNAGG_API int gnnagg_aggregate(int op, int64_t N, const int64_t* rowptr, const 
  * gnnagg_aggregate with row pitches and a workspace (same operation, same result up to the order
  * of the fp64 additions; max is bit-identical).
  *
- *   x_pitch, out_pitch   elements between the starts of consecutive rows of X / out (>= F; 0 = F).
+ *   x_pitch, out_pitch   elements between the starts of consecutive rows of X / out (>= F; 0 = F; a row
+ *            pitch of X of 2^32 bytes or more is GNNAGG_EUNSUPPORTED).
  *            A gather moves whole 128-byte lines: a 200-byte row (100 bf16 columns) at a 200-byte
  *            pitch straddles 2.55 lines on average, at a 256-byte pitch exactly 2.  gnnagg_row_pitch
  *            returns the pitch that puts every row on line boundaries.  Columns [F, pitch) are never

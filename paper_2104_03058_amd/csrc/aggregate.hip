@@ -169,7 +169,8 @@ struct AggAcc {
   int64_t rowbytes;
   typename Raw<T, VEC>::type raw[kUnroll];
   __device__ inline void fetch(int u, int64_t j) {
-    raw[u] = load_raw<T, VEC>(reinterpret_cast<const T*>(xb + j * rowbytes));
+    // j is a vertex id (below 2^31) and the row pitch in bytes is below 2^32: one 32 x 32 -> 64 bit multiply-add
+    raw[u] = load_raw<T, VEC>(reinterpret_cast<const T*>(xb + (uint64_t)(uint32_t)j * (uint64_t)(uint32_t)rowbytes));
   }
   template <bool MASKED>
   __device__ inline void use(int u, float w, bool ok) {
@@ -498,6 +499,7 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
                    int32_t F, int32_t f_chunk, const int32_t* row_order, const int64_t* class_off, double* ws,
                    const Update& up, hipStream_t stream) {
   const size_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
+  if ((uint64_t)x_pitch * xs >= (1ull << 32)) return GNNAGG_EUNSUPPORTED;  // row addresses: 32 x 32 -> 64 bit
   const bool rows_on_lines = ((uintptr_t)X % 128) == 0 && ((uint64_t)x_pitch * xs) % 128 == 0;
   if (up.W2) f_chunk = 0;  // the dense layer contracts whole rows
   if (f_chunk == GNNAGG_F_CHUNK_AUTO) f_chunk = auto_f_chunk(N, F, (int)xs, rows_on_lines, class_off);

@@ -164,7 +164,9 @@ struct GatAcc {
   float ss[kUnroll];
   __device__ inline void fetch(int u, int64_t j) {
     if constexpr (LH == 0) ss[u] = s_src_h[j * heads];
-    raw[u] = load_raw<float, VEC>(reinterpret_cast<const float*>(hb + j * rowbytes));
+    // j is a vertex id and a row of H is shorter than 2^32 bytes: one 32 x 32 -> 64 bit multiply-add
+    raw[u] = load_raw<float, VEC>(
+        reinterpret_cast<const float*>(hb + (uint64_t)(uint32_t)j * (uint64_t)(uint32_t)rowbytes));
   }
   template <bool MASKED>
   __device__ inline void use(int u, float, bool ok) {
@@ -409,7 +411,7 @@ extern "C" int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
                                     const int32_t* row_order, const int64_t* class_off, void* workspace,
                                     size_t* workspace_bytes, void* stream_) {
   if (N < 0 || heads <= 0 || C <= 0 || f_chunk < 0) return GNNAGG_EINVAL;
-  if ((int64_t)heads * C > 0x7fffffffll) return GNNAGG_EINVAL;
+  if ((int64_t)heads * C > 0x3fffffffll) return GNNAGG_EINVAL;  // a row of H stays below 2^32 bytes
   if (!(negative_slope == negative_slope)) return GNNAGG_EINVAL;
   const int32_t F = heads * C;
   if (f_chunk > 0 && f_chunk < F && (f_chunk % C) != 0) return GNNAGG_EINVAL;  // a chunk may not split a head

@@ -172,6 +172,9 @@ struct AggAcc {
     // j is a vertex id (below 2^31) and the row pitch in bytes is below 2^32: one 32 x 32 -> 64 bit multiply-add
     raw[u] = load_raw<T, VEC>(reinterpret_cast<const T*>(xb + (uint64_t)(uint32_t)j * (uint64_t)(uint32_t)rowbytes));
   }
+  __device__ inline void fetch_uniform(int u, int64_t j) {
+    raw[u] = load_raw<T, VEC>(reinterpret_cast<const T*>(xb + j * rowbytes));
+  }
   template <bool MASKED>
   __device__ inline void use(int u, float w, bool ok) {
     float v[VEC];

@@ -168,6 +168,10 @@ struct GatAcc {
     raw[u] = load_raw<float, VEC>(
         reinterpret_cast<const float*>(hb + (uint64_t)(uint32_t)j * (uint64_t)(uint32_t)rowbytes));
   }
+  __device__ inline void fetch_uniform(int u, int64_t j) {
+    if constexpr (LH == 0) ss[u] = s_src_h[j * heads];
+    raw[u] = load_raw<float, VEC>(reinterpret_cast<const float*>(hb + j * rowbytes));
+  }
   template <bool MASKED>
   __device__ inline void use(int u, float, bool ok) {
     float v[VEC];

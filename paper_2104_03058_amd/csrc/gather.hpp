@@ -4,6 +4,8 @@
 // An accumulator policy `Acc` says what is fetched per edge and how it enters the reduction:
 //   static constexpr bool kWeighted      - the walk also delivers edge_w
 //   void fetch(int u, int64_t j)          - issue the loads for source row j into slot u of the batch
+//   void fetch_uniform(int u, int64_t j)  - the same when j is the same in every lane (it lives in scalar
+//                                           registers: the row address is scalar arithmetic plus one add)
 //   template <bool MASKED> void use(int u, float w, bool ok)
 //                                         - fold slot u in; ok == false (MASKED batches only) means
 //                                           the entry does not exist and must not change the result
@@ -27,7 +29,7 @@ __device__ inline int64_t uniform64(int64_t v) {  // v is the same in every lane
 // accumulates.  Straight-line code: an entry that does not exist (only in MASKED batches) re-reads the
 // row `jsafe`, which does exist, and is folded in with ok == false, so no load sits behind a branch.
 // ok(u), j(u), w(u) describe entry u.
-template <bool MASKED, typename Acc, typename OkF, typename JF, typename WF>
+template <bool MASKED, bool UNIFORM_J = false, typename Acc, typename OkF, typename JF, typename WF>
 __device__ inline void gather_batch(Acc& acc, OkF ok, JF j, WF w, int64_t jsafe) {
   float wv[kUnroll];
   bool okv[kUnroll];
@@ -36,7 +38,8 @@ __device__ inline void gather_batch(Acc& acc, OkF ok, JF j, WF w, int64_t jsafe)
     okv[u] = MASKED ? (bool)ok(u) : true;
     const int64_t jj = okv[u] ? (int64_t)j(u) : jsafe;
     wv[u] = Acc::kWeighted ? (float)w(u) : 1.0f;
-    acc.fetch(u, jj);
+    if constexpr (UNIFORM_J) acc.fetch_uniform(u, jj);
+    else acc.fetch(u, jj);
   }
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) acc.template use<MASKED>(u, wv[u], okv[u]);
@@ -77,10 +80,10 @@ __device__ inline void gather_wave(Acc& acc, const int32_t* __restrict__ colidx,
       auto jf = [&](int u) { return __builtin_amdgcn_readlane(idx_c, l0 + u); };
       auto wf = [&](int u) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_c), l0 + u)); };
       if (left >= kUnroll) {
-        gather_batch<false>(acc, [](int) { return true; }, jf, wf, 0);
+        gather_batch<false, true>(acc, [](int) { return true; }, jf, wf, 0);
       } else {
-        gather_batch<true>(acc, [&](int u) { return u < left; }, jf, wf,
-                           (int64_t)__builtin_amdgcn_readlane(idx_c, l0));
+        gather_batch<true, true>(acc, [&](int u) { return u < left; }, jf, wf,
+                                 (int64_t)__builtin_amdgcn_readlane(idx_c, l0));
       }
     }
     idx_c = idx_n;

@@ -84,7 +84,7 @@ struct State {
   __device__ inline void add(const float (&v)[VEC], float w, bool ok) {
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
-      const double x = (MASKED && !ok) ? 0.0 : (double)v[k];
+      const double x = (double)((MASKED && !ok) ? 0.0f : v[k]);  // masked as a float: one select, not two
       if (OPK == OPK_WSUM) acc[k] = __builtin_fma((double)w, x, acc[k]);
       else acc[k] += x;
     }
@@ -168,7 +168,7 @@ struct AggAcc {
   const char* __restrict__ xb;  // X plus this lane's column offset, in bytes
   int64_t rowbytes;
   typename Raw<T, VEC>::type raw[kUnroll];
-  __device__ inline void fetch(int u, int64_t j) {
+  __device__ inline void fetch(int u, int32_t j) {
     // j is a vertex id (below 2^31) and the row pitch in bytes is below 2^32: one 32 x 32 -> 64 bit multiply-add
     raw[u] = load_raw<T, VEC>(reinterpret_cast<const T*>(xb + (uint64_t)(uint32_t)j * (uint64_t)(uint32_t)rowbytes));
   }

@@ -162,8 +162,8 @@ struct GatAcc {
   double av[VEC];  // a_src at this lane's columns (LH > 0)
   typename Raw<float, VEC>::type raw[kUnroll];
   float ss[kUnroll];
-  __device__ inline void fetch(int u, int64_t j) {
-    if constexpr (LH == 0) ss[u] = s_src_h[j * heads];
+  __device__ inline void fetch(int u, int32_t j) {
+    if constexpr (LH == 0) ss[u] = s_src_h[(int64_t)j * heads];
     // j is a vertex id and a row of H is shorter than 2^32 bytes: one 32 x 32 -> 64 bit multiply-add
     raw[u] = load_raw<float, VEC>(
         reinterpret_cast<const float*>(hb + (uint64_t)(uint32_t)j * (uint64_t)(uint32_t)rowbytes));

@@ -3,7 +3,7 @@
 //
 // An accumulator policy `Acc` says what is fetched per edge and how it enters the reduction:
 //   static constexpr bool kWeighted      - the walk also delivers edge_w
-//   void fetch(int u, int64_t j)          - issue the loads for source row j into slot u of the batch
+//   void fetch(int u, int32_t j)          - issue the loads for source row j into slot u of the batch
 //   void fetch_uniform(int u, int64_t j)  - the same when j is the same in every lane (it lives in scalar
 //                                           registers: the row address is scalar arithmetic plus one add)
 //   template <bool MASKED> void use(int u, float w, bool ok)
@@ -36,10 +36,12 @@ __device__ inline void gather_batch(Acc& acc, OkF ok, JF j, WF w, int64_t jsafe)
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     okv[u] = MASKED ? (bool)ok(u) : true;
-    const int64_t jj = okv[u] ? (int64_t)j(u) : jsafe;
     wv[u] = Acc::kWeighted ? (float)w(u) : 1.0f;
-    if constexpr (UNIFORM_J) acc.fetch_uniform(u, jj);
-    else acc.fetch(u, jj);
+    if constexpr (UNIFORM_J) {
+      acc.fetch_uniform(u, okv[u] ? (int64_t)j(u) : jsafe);
+    } else {  // vertex ids are 32-bit: the select and the address arithmetic stay 32-bit
+      acc.fetch(u, okv[u] ? (int32_t)j(u) : (int32_t)jsafe);
+    }
   }
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) acc.template use<MASKED>(u, wv[u], okv[u]);
@@ -91,15 +93,56 @@ __device__ inline void gather_wave(Acc& acc, const int32_t* __restrict__ colidx,
   }
 }
 
-// Slot = 2^g lanes, 8 <= 2^g <= 32.  The lanes of a slot read the indices of the slot's next 2^g / 8
-// batches with one load and hand them round with cross-lane shuffles.  All lanes of a slot run the loop
-// together; lanes without columns of their own hold indices for the others and re-read the slice's
-// last columns (their column offset is always valid) rather than branching around the gathers.
-template <typename Acc>
+// Value of lane `slot_base + SRC` for every lane of a slot of G lanes (8, 16 or 32; slots are aligned to G, so
+// they lie inside one half of the wave): a swizzle with an immediate pattern - lane' = (lane & ~(G-1)) | SRC
+// on the low five lane bits - which needs no address register and no vector instruction to form one.
+template <int G, int SRC>
+__device__ inline int32_t slot_broadcast(int32_t v) {
+  static_assert(G == 8 || G == 16 || G == 32, "slots of 8, 16 or 32 lanes");
+  static_assert(SRC >= 0 && SRC < G, "source lane inside the slot");
+  constexpr int kAnd = 0x1f & ~(G - 1), kOr = SRC;
+  return __builtin_amdgcn_ds_swizzle(v, (kOr << 5) | kAnd);
+}
+
+template <int G, int K, typename Acc>
+__device__ inline void wide_batch(Acc& acc, int32_t idx_c, float w_c) {
+  int32_t j[kUnroll];
+  float wj[kUnroll];
+  j[0] = slot_broadcast<G, K * kUnroll + 0>(idx_c);
+  j[1] = slot_broadcast<G, K * kUnroll + 1>(idx_c);
+  j[2] = slot_broadcast<G, K * kUnroll + 2>(idx_c);
+  j[3] = slot_broadcast<G, K * kUnroll + 3>(idx_c);
+  j[4] = slot_broadcast<G, K * kUnroll + 4>(idx_c);
+  j[5] = slot_broadcast<G, K * kUnroll + 5>(idx_c);
+  j[6] = slot_broadcast<G, K * kUnroll + 6>(idx_c);
+  j[7] = slot_broadcast<G, K * kUnroll + 7>(idx_c);
+  if constexpr (Acc::kWeighted) {
+    const int32_t wb = __float_as_int(w_c);
+    wj[0] = __int_as_float(slot_broadcast<G, K * kUnroll + 0>(wb));
+    wj[1] = __int_as_float(slot_broadcast<G, K * kUnroll + 1>(wb));
+    wj[2] = __int_as_float(slot_broadcast<G, K * kUnroll + 2>(wb));
+    wj[3] = __int_as_float(slot_broadcast<G, K * kUnroll + 3>(wb));
+    wj[4] = __int_as_float(slot_broadcast<G, K * kUnroll + 4>(wb));
+    wj[5] = __int_as_float(slot_broadcast<G, K * kUnroll + 5>(wb));
+    wj[6] = __int_as_float(slot_broadcast<G, K * kUnroll + 6>(wb));
+    wj[7] = __int_as_float(slot_broadcast<G, K * kUnroll + 7>(wb));
+  } else {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) wj[u] = 1.0f;
+  }
+  gather_batch<true>(acc, [&](int u) { return j[u] >= 0; }, [&](int u) { return j[u]; },
+                     [&](int u) { return wj[u]; }, (int64_t)j[0]);
+}
+
+// Slot = G lanes, G = 8, 16 or 32.  The lanes of a slot read the indices of the slot's next G / 8 batches with
+// one load and hand them round with swizzles.  All lanes of a slot run the loop together; lanes without
+// columns of their own hold indices for the others and re-read the slice's last columns (their column offset
+// is always valid) rather than branching around the gathers.
+template <int G, typename Acc>
 __device__ inline void gather_wide(Acc& acc, const int32_t* __restrict__ colidx, const float* __restrict__ edge_w,
-                                   int64_t e0, int64_t e1, int ng, int p_log2, int lane, int g) {
-  const int G = 1 << g;
-  const int gl = lane & (G - 1), slot_base = lane & ~(G - 1);
+                                   int64_t e0, int64_t e1, int ng, int p_log2, int lane) {
+  static_assert(kUnroll == 8, "a batch is eight entries");
+  const int gl = lane & (G - 1);
   const int shift = 3 + p_log2;
   const int64_t outer = (int64_t)G << p_log2;
   const int64_t lane_pos = ((int64_t)(gl >> 3) << shift) + (ng << 3) + (gl & 7);
@@ -116,17 +159,15 @@ __device__ inline void gather_wide(Acc& acc, const int32_t* __restrict__ colidx,
       idx_n = colidx[e + outer + lane_pos];
       if (Acc::kWeighted) w_n = edge_w[e + outer + lane_pos];
     }
-    for (int k = 0; k < (G >> 3); ++k) {
-      if (e + ((int64_t)k << shift) + (ng << 3) >= e1) break;  // same for every lane of the slot
-      int32_t j[kUnroll];
-      float wj[kUnroll];
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
-        j[u] = __shfl(idx_c, slot_base + k * kUnroll + u, kWave);
-        wj[u] = Acc::kWeighted ? __shfl(w_c, slot_base + k * kUnroll + u, kWave) : 1.0f;
-      }
-      gather_batch<true>(acc, [&](int u) { return j[u] >= 0; }, [&](int u) { return j[u]; },
-                         [&](int u) { return wj[u]; }, (int64_t)j[0]);
+    // batch k of the block exists for this slot if its first edge does (same for every lane of the slot)
+    const int64_t first = e + (ng << 3);
+    if (first < e1) wide_batch<G, 0>(acc, idx_c, w_c);  // (its first entry then exists: the row every masked entry re-reads)
+    if constexpr (G >= 16) {
+      if (first + ((int64_t)1 << shift) < e1) wide_batch<G, 1>(acc, idx_c, w_c);
+    }
+    if constexpr (G >= 32) {
+      if (first + ((int64_t)2 << shift) < e1) wide_batch<G, 2>(acc, idx_c, w_c);
+      if (first + ((int64_t)3 << shift) < e1) wide_batch<G, 3>(acc, idx_c, w_c);
     }
     idx_c = idx_n;
     w_c = w_n;
@@ -186,7 +227,9 @@ __device__ inline void gather_row(Acc& acc, const int32_t* __restrict__ colidx, 
   if constexpr (MODE == MODE_WAVE) {
     gather_wave(acc, colidx, edge_w, e0, e1, ng, p_log2, lane);
   } else if constexpr (MODE == MODE_WIDE) {
-    gather_wide(acc, colidx, edge_w, e0, e1, ng, p_log2, lane, g);
+    if (g == 3) gather_wide<8>(acc, colidx, edge_w, e0, e1, ng, p_log2, lane);
+    else if (g == 4) gather_wide<16>(acc, colidx, edge_w, e0, e1, ng, p_log2, lane);
+    else gather_wide<32>(acc, colidx, edge_w, e0, e1, ng, p_log2, lane);
   } else {
     if (col_ok) gather_narrow(acc, colidx, edge_w, e0 + (int64_t)ng * kUnroll, e1, (int64_t)kUnroll << p_log2, nnz);
   }

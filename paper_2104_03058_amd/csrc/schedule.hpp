@@ -219,8 +219,8 @@ inline void plan_columns(int32_t F, int32_t f_chunk, int max_vec, int vec_multip
 }
 
 // Maps degree classes to lane groups for slices spanned by 2^g_log2 lanes.
-// A row of degree d gets about d/8 neighbour slots (a power of two) so that each
-// slot walks at least eight neighbours; beyond what a wave offers the row moves
+// A row of degree d gets about d/8 to d/64 neighbour slots (a power of two; the wider the slot, the more
+// edges it should walk before its partial result is worth a merge); beyond what a wave offers the row moves
 // to a whole workgroup.  Without a plan every row gets one wave.
 inline int build_segments(const int64_t* class_off, int64_t N, int g_log2, bool allow_split, SegTable* t) {
   t->nseg = 0;
@@ -273,7 +273,11 @@ inline int build_segments(const int64_t* class_off, int64_t N, int g_log2, bool 
       if (class_off[k] > class_off[k + 1]) return GNNAGG_EINVAL;
     for (int k = 0; k < GNNAGG_PLAN_CLASSES; ++k) {
       const int c = 32 - k;                      // rows with 2^(c-1) <= degree < 2^c
-      const int p_log2 = c >= 4 ? c - 4 : 0;     // neighbour slots wanted: degree / 8
+      // edges a neighbour slot should at least walk (log2): 8 where a slot is 1-4 lanes, 32 where it is 8-32
+      // lanes, 64 where it is a whole wavefront - measured: against 8 everywhere, 5-8 % on the two large
+      // benchmark graphs and on attention; slots of 1-4 lanes lose 1-2 % with more than 8
+      const int per_slot_log2 = g_log2 <= 2 ? 3 : (g_log2 == 6 ? 6 : 5);
+      const int p_log2 = c > per_slot_log2 ? c - 1 - per_slot_log2 : 0;
       int L = g_log2 + p_log2;
       L = (L >= 8) ? 8 : (L > 6 ? 6 : L);
       const int split = (allow_split && L == 8 && c >= kSplitClass) ? c - kSplitLenLog2 : 0;

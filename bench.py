@@ -686,7 +686,7 @@ HELD_OUT_2 = [
     (65_000, 13_000_000, 2.3, 100.0, 128, "f32", "wsum"),
     (160_000, 4_000_000, 1.8, 800.0, 2048, "f32", "mean"),
 ]
-# A third set, drawn after the rule took its final form: never used to adjust it.
+# A third set, drawn after the second revision; it then served the third.
 HELD_OUT_3 = [
     (55_000, 5_500_000, 1.9, 250.0, 800, "f32", "wsum"),
     (180_000, 27_000_000, 1.7, 900.0, 320, "f32", "mean"),
@@ -696,6 +696,17 @@ HELD_OUT_3 = [
     (75_000, 3_000_000, 2.2, 300.0, 640, "f32", "max"),
     (320_000, 48_000_000, 1.9, 1200.0, 192, "f32", "wsum"),
     (220_000, 6_600_000, 1.6, 1000.0, 512, "bf16", "mean"),
+]
+# A fourth set, drawn after the row schedule and the rule changed once more: never used to adjust either.
+HELD_OUT_4 = [
+    (70_000, 7_000_000, 1.8, 350.0, 448, "f32", "wsum"),
+    (140_000, 9_800_000, 2.0, 700.0, 960, "f32", "mean"),
+    (450_000, 27_000_000, 1.7, 2000.0, 256, "f32", "wsum"),
+    (90_000, 13_500_000, 1.9, 400.0, 1024, "bf16", "sum"),
+    (1_200_000, 18_000_000, 2.2, 5000.0, 192, "f32", "mean"),
+    (48_000, 1_440_000, 1.8, 250.0, 1536, "f32", "max"),
+    (260_000, 52_000_000, 1.8, 1100.0, 384, "f32", "wsum"),
+    (330_000, 8_250_000, 1.7, 1500.0, 640, "bf16", "mean"),
 ]
 # the benchmark graphs the rules were first derived on, for the same table (not held out)
 TUNING_SHAPES = [
@@ -710,9 +721,9 @@ def validate_auto(g, W, torch, steps, warmup, which):
     """Times every held-out shape at chunk widths {32, 64, 128, one chunk} and, at the library's width, at
     resident-workgroup caps {none, 2, 3, 4}, and reports how far the library's own choice is from the best."""
     rows = []
-    shapes = {"1": HELD_OUT, "2": HELD_OUT_2, "3": HELD_OUT_3, "tuning": TUNING_SHAPES}[which]
+    shapes = {"1": HELD_OUT, "2": HELD_OUT_2, "3": HELD_OUT_3, "4": HELD_OUT_4, "tuning": TUNING_SHAPES}[which]
     for k, (N, M, alpha, R, F, xdt, opname) in enumerate(shapes):
-        src, dst = W.powerlaw_graph(N, M, alpha, R, {"1": 100, "2": 300, "3": 500, "tuning": 110}[which] + k)
+        src, dst = W.powerlaw_graph(N, M, alpha, R, {"1": 100, "2": 300, "3": 500, "4": 700, "tuning": 110}[which] + k)
         gcn = opname == "wsum"
         flags = (g.SELF_LOOPS | g.NORM_SYM) if gcn else 0
         rp, ci, w, _ = g.gnnagg_build_csr(N, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda(), flags, want_w=gcn)
@@ -830,8 +841,8 @@ def main():
                     help="'default': the CPU checker in Algorithm 1's chunk-outer order at the sweep widths of the "
                          "two benchmark configurations that name one (about half a minute); 'none'; or a comma list "
                          "of widths for the main workload")
-    ap.add_argument("--validate-auto", default="", choices=["", "1", "2", "3", "tuning"],
-                    help="instead of the benchmark: time a set of graph shapes (1, 2: used to revise the rule; 3: never "
+    ap.add_argument("--validate-auto", default="", choices=["", "1", "2", "3", "4", "tuning"],
+                    help="instead of the benchmark: time a set of graph shapes (1-3: used to revise the rule; 4: never "
                          "used for it; tuning: the benchmark graphs) at several chunk widths and resident-workgroup caps and print the regret of the "
                          "library's automatic choices")
     args = ap.parse_args()

@@ -317,19 +317,18 @@ inline void degree_profile(const int64_t* class_off, int64_t N, int64_t hot_rows
 // regret of this choice per shape, for the benchmark graphs and for shapes the rule was not derived on):
 //  (1) Rows on 128-byte lines, at least four lines wide, more than 32,768 rows (as many as one 4 MB L2 holds
 //      lines), mean degree >= 16 and hubs that matter (the 32,768 longest rows take >= 40 % of the edges):
-//      row pieces of 2^k LINES.  A pass then gathers from a column slice of N x piece bytes in which the
-//      hubs' lines stay in L2.
-//        - k from the slice: about 24 MB, a few times the L2 - one line per piece from ~130,000 rows on
-//          (9-30 % faster than one chunk), two at ~100,000 rows, four at 45,000-60,000 rows, where
-//          single-line passes are 12-20 % SLOWER than four-line ones (the slice is small anyway, and a pass
-//          of single lines reaches a lower L2 request rate than a pass of wider pieces);
-//        - at least ~200 / (mean degree) lines (a power of two): every pass pays a chain of dependent loads
-//          per row (plan, row pointer, indices) that short rows do not amortise - at mean degree 50 and
-//          45-64 passes four-line pieces are 15-20 % faster than one-line ones - but only while the slice
-//          stays within about half the 256 MB Infinity Cache (700,000 rows of mean degree 30: one line,
-//          90 MB, is 24 % faster than four);
-//        - bf16: at least two lines (a one-line pass accumulates eight columns per lane in fp64 and is
-//          bound by that arithmetic, 6-15 % slower); one chunk when all of X is within 64 MB.
+//      row pieces of one or a few LINES.  A pass then gathers from a column slice of N x piece bytes in
+//      which the hubs' lines stay in L2.
+//        - fp32: one line per piece (10-35 % faster than one chunk at 45,000-1,500,000 rows; two-line
+//          pieces are within 7 % of it where they win and up to 23 % behind where they lose);
+//        - short rows: every pass pays a chain of dependent loads per row (plan, row pointer, indices) that
+//          few edges do not amortise - at mean degree 50 and 45-64 passes two- to four-line pieces are
+//          3-12 % faster than one-line ones - so at least ~75 / (mean degree) lines (a power of two), but
+//          only while the slice stays within about half the 256 MB Infinity Cache (700,000 rows of mean
+//          degree 30: one line, a 90 MB slice, is 14-27 % faster than two or four);
+//        - bf16: two lines (a one-line pass accumulates eight columns per lane in fp64 and is bound by that
+//          arithmetic, 4-7 % slower on the largest bf16 shapes) - two lines are within 7 % of the
+//          best width on every bf16 shape tried).
 //  (2) Otherwise, X beyond ~1 GiB (several times the Infinity Cache; 2.4 M rows x 256-512 fp32 columns):
 //      chunks whose column slice is ~300-600 MB are 13-17 % faster than one chunk, row pieces under 128
 //      bytes twice slower than either -> power-of-two width with a ~384 MB slice, >= 128-byte pieces.
@@ -350,15 +349,11 @@ inline int32_t auto_f_chunk(int64_t N, int32_t F, int elem_bytes, bool rows_on_l
     double mean_degree, hot_share;
     degree_profile(class_off, N, kLinesPerL2, &mean_degree, &hot_share);
     if (mean_degree >= 16.0 && hot_share >= 0.4) {
-      if (elem_bytes < 4 && x_bytes <= 64.0e6) return F;
       const double line_slice = (double)N * 128.0;  // bytes of a column slice one line wide
       int64_t lines = 1;
-      while (lines < 8 && 24.0e6 / line_slice >= 1.5 * (double)lines) lines *= 2;
-      int64_t by_degree = 1;
-      while (by_degree < 8 && (double)by_degree * mean_degree < 200.0) by_degree *= 2;
+      while (lines < 8 && (double)lines * mean_degree < 75.0) lines *= 2;
       const int64_t in_cache = pow2_floor(128.0e6 / line_slice);
-      const int64_t amortised = by_degree < in_cache ? by_degree : in_cache;
-      if (amortised > lines) lines = amortised;
+      if (lines > in_cache) lines = in_cache;
       if (elem_bytes < 4 && lines < 2) lines = 2;
       const int64_t w = lines * line_cols;
       return (int32_t)(w >= F ? F : w);

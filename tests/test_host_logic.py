@@ -358,25 +358,22 @@ def test_auto_chunk_width_one_line_on_dense_skewed_graphs(lib):
     assert g.gnnagg_auto_f_chunk(N, 602, g.F32, 608, flat) == 602      # no hubs
     assert g.gnnagg_auto_f_chunk(N, 602, g.F32, 608, sparse) == 602    # low mean degree
     assert g.gnnagg_auto_f_chunk(N, 64, g.F32, 64, skewed) == 64       # narrower than four lines
-    assert g.gnnagg_auto_f_chunk(N, 512, g.BF16, 512, skewed) == 128   # bf16: never under two lines per piece
+    assert g.gnnagg_auto_f_chunk(N, 512, g.BF16, 512, skewed) == 128   # bf16: two lines per piece
     assert g.gnnagg_auto_f_chunk(N, 200, g.BF16, 256, skewed) == 200   # bf16 rows narrower than four lines
     assert g.gnnagg_auto_f_chunk(20000, 602, g.F32, 608, plan_of(20000, {12: 500, 9: 19500})) == 602  # fits one L2
-    # fewer rows: wider pieces, so that the column slice of a pass stays at about 24 MB
+    # one line per piece whatever the row count (long rows)
     def skewed_of(n):
         return plan_of(n, {13: n // 100, 11: n // 10, 9: n // 4, 8: n - n // 100 - n // 10 - n // 4})
-    assert g.gnnagg_auto_f_chunk(132534, 602, g.F32, 608, skewed_of(132534)) == 32
-    assert g.gnnagg_auto_f_chunk(100000, 256, g.F32, 256, skewed_of(100000)) == 64
-    assert g.gnnagg_auto_f_chunk(50000, 256, g.F32, 256, skewed_of(50000)) == 128
-    assert g.gnnagg_auto_f_chunk(60000, 1433, g.F32, 1440, skewed_of(60000)) == 128
-    assert g.gnnagg_auto_f_chunk(40000, 1433, g.F32, 1440, skewed_of(40000)) == 128
+    for n in (40000, 50000, 100000, 132534, 250000):
+        assert g.gnnagg_auto_f_chunk(n, 1433, g.F32, 1440, skewed_of(n)) == 32
     assert g.gnnagg_auto_f_chunk(150000, 602, g.BF16, 640, skewed_of(150000)) == 128
-    assert g.gnnagg_auto_f_chunk(45000, 512, g.BF16, 512, skewed_of(45000)) == 512   # bf16, all of X within 64 MB
+    assert g.gnnagg_auto_f_chunk(45000, 512, g.BF16, 512, skewed_of(45000)) == 128
     # short rows do not amortise a pass: wider pieces at low mean degree, while the slice stays in the Infinity Cache
     def short_rows(n, c):  # hubs for the hot share, everything else in degree class c
         return plan_of(n, {14: n // 400, c: n - n // 400})
-    assert g.gnnagg_auto_f_chunk(160000, 2048, g.F32, 2048, short_rows(160000, 6)) == 128   # X = 1.3 GB, mean degree ~80
-    assert g.gnnagg_auto_f_chunk(700000, 300, g.F32, 320, short_rows(700000, 5)) == 32      # four lines would be 360 MB
-    assert g.gnnagg_auto_f_chunk(350000, 200, g.F32, 224, short_rows(350000, 5)) == 64
+    assert g.gnnagg_auto_f_chunk(160000, 2048, g.F32, 2048, short_rows(160000, 4)) == 64    # mean degree ~42
+    assert g.gnnagg_auto_f_chunk(160000, 2048, g.F32, 2048, short_rows(160000, 6)) == 32    # mean degree ~78
+    assert g.gnnagg_auto_f_chunk(700000, 300, g.F32, 320, short_rows(700000, 4)) == 32      # two lines would be 180 MB
 
 
 def test_bench_module_is_importable_and_its_workloads_name_known_graphs():

@@ -58,6 +58,10 @@ WORKLOADS = {
     # the paper's regime: Combination first, so Aggregation runs at the hidden width 8/16/32 (Section III)
     "c4-hid32-gcn": ("c4", "wsum", 32, "f32", True),
     "c4-hid8-gcn": ("c4", "wsum", 8, "f32", True),
+    "c6-gcn": ("c6", "wsum", 602, "f32", True),      # the third graph shape at the dense graph's input width
+    "c6-mean-256": ("c6", "mean", 256, "f32", False),
+    "c4-mean-256": ("c4", "mean", 256, "f32", False),
+    "c4-sum-bf16-512": ("c4", "sum", 512, "bf16", False),
     "c6-hid32-gcn": ("c6", "wsum", 32, "f32", True),
     "c6-hid16-gcn": ("c6", "wsum", 16, "f32", True),
     "c6-hid8-gcn": ("c6", "wsum", 8, "f32", True),
@@ -89,7 +93,15 @@ WORKLOADS = {
 }
 PROBES = ["probe-l2-line", "probe-mall-line", "probe-hbm-line", "probe-hbm-row"]
 
-# "name@W" runs workload `name` at chunk width W ("all" = one chunk): the sweeps of the benchmark configurations
+# "name@W" runs workload `name` at chunk width W ("all" = one chunk): the sweeps of the benchmark configurations;
+# "name#B" (before any "@W") runs it over B source blocks (gnnagg_plan_source_blocks + gnnagg_aggregate_blocked)
+def split_name(workload):
+    """(name in WORKLOADS, source blocks or 0, chunk-width suffix or '')"""
+    head, _, width = workload.partition("@")
+    base, _, blocks = head.partition("#")
+    return base, (int(blocks) if blocks else 0), width
+
+
 DEFAULT_ALSO = (
     PROBES
     + ["c4-gcn@8", "c4-gcn@16", "c4-gcn@32", "c4-gcn@64", "c4-gcn@all",
@@ -321,7 +333,7 @@ class Bench:
     # ---- one aggregation workload (sum / wsum / mean / max, plain or ranked)
     def measure_aggregate(self, workload, f_chunk, cpu_seconds=0.0, single_thread=False):
         g, torch = self.g, self.torch
-        base = workload.split("@")[0]
+        base, n_blocks, _ = split_name(workload)
         gkey, opname, F, xdt, gcn = WORKLOADS[base]
         ranked = opname.endswith("-ranked")
         opname = opname.replace("-ranked", "")
@@ -350,14 +362,32 @@ class Bench:
         del d_X0
         op = {"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname]
 
-        def step():
-            g.gnnagg_aggregate(op, c["rp"], d_ci, c["w"], d_X, out, f_chunk, c["plan"])
+        if n_blocks:  # per graph, like the CSR and the plan; the states in transit live in a workspace kept here
+            g.gnnagg_plan_source_blocks(c["rp"], d_ci, n_blocks)
+            torch.cuda.synchronize()
+            t0 = time.time()
+            blocks = g.gnnagg_plan_source_blocks(c["rp"], d_ci, n_blocks)
+            torch.cuda.synchronize()
+            setup["plan_source_blocks_ms"] = (time.time() - t0) * 1e3
+            ws = torch.empty(max(g.gnnagg_aggregate_blocked_workspace_bytes(N, F, blocks), 256), dtype=torch.uint8,
+                             device="cuda")
+
+            def step():
+                g.gnnagg_aggregate_blocked(op, c["rp"], d_ci, c["w"], d_X, blocks, out, f_chunk, workspace=ws)
+        else:
+            def step():
+                g.gnnagg_aggregate(op, c["rp"], d_ci, c["w"], d_X, out, f_chunk, c["plan"])
 
         ms, ms_per_step = self.time_steps(step)
         nnz = c["nnz"]
         x_bytes = 2 if xdt == "bf16" else 4
-        f_eff = (g.gnnagg_auto_f_chunk(N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)), c["plan"])
-                 if f_chunk == -1 else f_chunk)
+        if f_chunk == -1 and n_blocks:  # the blocked call's own rule (its header): line pieces on aligned rows
+            piece = 128 if xdt == "bf16" else 32
+            on_lines = (int(d_X.stride(0)) * (2 if xdt == "bf16" else 4)) % 128 == 0
+            f_eff = piece if (on_lines and F >= 2 * piece) else 0
+        else:
+            f_eff = (g.gnnagg_auto_f_chunk(N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)), c["plan"])
+                     if f_chunk == -1 else f_chunk)
         f_used = f_eff if 0 < f_eff < F else F
         # priced at ONE pass over the edge list, whatever chunk width runs: the index and weight re-reads of
         # a chunked run are the method's overhead, not work to take credit for
@@ -365,9 +395,10 @@ class Bench:
         kern_ms = float(ms.mean())
         cfg = {"workload": workload, "graph": self.W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "op": opname,
                "f_chunk": f_chunk, "f_chunk_used": f_used, "x_dtype": xdt, "x_row_pitch": int(d_X.stride(0)),
-               "out_row_pitch": int(out.stride(0)), "rows_in_popularity_order": ranked}
+               "out_row_pitch": int(out.stride(0)), "rows_in_popularity_order": ranked,
+               "source_blocks": n_blocks}
         lpe = gather_lines_per_edge(F, x_bytes, int(d_X.stride(0)), f_used)
-        roof, l2, fab = self.rate_blocks(base if f_chunk == -1 else workload, kern_ms, b_alg,
+        roof, l2, fab = self.rate_blocks(workload.split("@")[0] if f_chunk == -1 else workload, kern_ms, b_alg,
                                          nnz * lpe if lpe else None, cfg)
         roof.update({"kernel": "aggregate_kernel", "per": "library call (all its launches; kernel_ms is their sum)",
                      "kernel_ms_median": float(np.median(ms)), "kernel_ms_min": float(ms.min()),
@@ -625,7 +656,7 @@ class Bench:
                 "cpu_baseline": None, "parity_on_sample": parity, "parity_rows": int(len(rows)), "setup": {}}
 
     def measure(self, workload, f_chunk=-1, cpu_seconds=0.0, single_thread=False):
-        base, _, width = workload.partition("@")
+        base, _, width = split_name(workload)
         if width:
             f_chunk = 0 if width == "all" else int(width)
         op = WORKLOADS[base][1]
@@ -765,15 +796,44 @@ def validate_auto(g, W, torch, steps, warmup, which):
             caps["none" if cap == 0 else str(cap)] = timed(g.F_CHUNK_AUTO)
         g.gnnagg_set_workgroup_cap(-1)
         best = min(list(widths.values()) + list(caps.values()) + [t_auto])
+        # the same over source blocks (not part of `best`: the regret above is that of the chunk-width rule)
+        blocked = {}
+        line = 64 if xdt == "bf16" else 32
+        for B in (2, 4, 8):
+            blocks = g.gnnagg_plan_source_blocks(rp, ci, B)
+            ws = torch.empty(max(g.gnnagg_aggregate_blocked_workspace_bytes(N, F, blocks), 256), dtype=torch.uint8,
+                             device="cuda")
+            for fc in (line, 2 * line, 4 * line):
+                if fc >= F:
+                    continue
+                for _ in range(warmup):
+                    g.gnnagg_aggregate_blocked(op, rp, ci, w, d_X, blocks, out, fc, workspace=ws)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(steps):
+                    g.gnnagg_aggregate_blocked(op, rp, ci, w, d_X, blocks, out, fc, workspace=ws)
+                e1.record()
+                torch.cuda.synchronize()
+                blocked["%d@%d" % (B, fc)] = e0.elapsed_time(e1) / steps
+            del blocks, ws
+        # what a caller following the library's two rules gets: blocks where gnnagg_auto_source_blocks says so
+        # (at the blocked call's own width), else the plain call at GNNAGG_F_CHUNK_AUTO
+        B_auto = g.gnnagg_auto_source_blocks(N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)), plan)
+        t_rules = blocked["%d@%d" % (B_auto, 2 * line if xdt != "bf16" else 2 * line)] if B_auto > 1 else t_auto
+        best_any = min([best] + list(blocked.values()))
         deg = float(len(src)) / N
         row = {"set": which, "class_off": plan.class_offsets(), "N": N, "mean_degree": deg, "max_degree": int((rp[1:] - rp[:-1]).max()), "exponent": alpha, "F": F,
                "x_dtype": xdt, "op": opname, "auto_f_chunk": int(f_auto), "auto_ms": t_auto, "by_width_ms": widths,
                "by_cap_ms_at_auto_width": caps, "best_ms": best, "regret": t_auto / best - 1.0,
-               "tuned_f_chunk": tuned, "tuned_ms": t_tuned, "tuned_regret": t_tuned / best - 1.0}
+               "tuned_f_chunk": tuned, "tuned_ms": t_tuned, "tuned_regret": t_tuned / best - 1.0,
+               "blocked_ms": blocked, "auto_source_blocks": int(B_auto), "rules_ms": t_rules,
+               "best_ms_with_blocks": best_any, "rules_regret": t_rules / best_any - 1.0}
         log("held-out %d: N=%d deg %.0f a=%.1f F=%d %s %s: auto(width %d) %.3f ms, widths %s, caps %s, regret %.1f %%" %
             (k, N, deg, alpha, F, xdt, opname, f_auto, t_auto, {a: round(b, 3) for a, b in widths.items()},
              {a: round(b, 3) for a, b in caps.items()}, 100 * row["regret"]) +
-            "; measured tuner picks %d (%.3f ms, regret %.1f %%)" % (tuned, t_tuned, 100 * row["tuned_regret"]))
+            "; measured tuner picks %d (%.3f ms, regret %.1f %%)" % (tuned, t_tuned, 100 * row["tuned_regret"]) +
+            "; source blocks %s; rule: %d blocks, %.3f ms, regret against everything tried %.1f %%" %
+            ({a: round(b, 3) for a, b in blocked.items()}, B_auto, t_rules, 100 * row["rules_regret"]))
         rows.append(row)
         del d_X, out, rp, ci, w, plan
         torch.cuda.empty_cache()
@@ -873,7 +933,7 @@ def main():
                           "ms_per_step": copy_ms, "bytes_read": probe_bytes, "bytes_written": probe_bytes,
                           "config": {"workload": "copy"}}), flush=True)
         return
-    if args.workload.split("@")[0] not in WORKLOADS:
+    if split_name(args.workload)[0] not in WORKLOADS:
         sys.exit("unknown workload %s (known: %s)" % (args.workload, ", ".join(sorted(WORKLOADS))))
 
     b = Bench(g, W, torch, args.steps, args.warmup, not args.contiguous)
@@ -883,7 +943,7 @@ def main():
                                                                                           MFMA_F64_PEAK_TFLOPS))
     also_names = [w for w in args.also.split(",") if w and w != args.workload]
     for w in also_names:
-        if w.split("@")[0] not in WORKLOADS:
+        if split_name(w)[0] not in WORKLOADS:
             sys.exit("unknown workload %s" % w)
     cpu = not args.no_cpu_baseline
     done = {}

@@ -19,12 +19,12 @@
  *    as `workspace`.  Inputs and outputs must not overlap.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    gnnagg_aggregate, gnnagg_aggregate_ws, gnnagg_aggregate_update,
- *    gnnagg_aggregate_noalloc, gnnagg_gat_attention, gnnagg_combine and
- *    gnnagg_rank_sources only enqueue kernels on it and return (no allocation
+ *    gnnagg_aggregate_noalloc, gnnagg_aggregate_blocked, gnnagg_gat_attention,
+ *    gnnagg_combine and gnnagg_rank_sources only enqueue kernels on it and return (no allocation
  *    on the host or the device, no synchronisation, no memset: they can be
- *    captured in a HIP graph); gnnagg_build_csr, gnnagg_check_csr and
- *    gnnagg_plan_rows also wait for it, because they hand results back to the
- *    host.
+ *    captured in a HIP graph); gnnagg_build_csr, gnnagg_check_csr,
+ *    gnnagg_plan_rows, gnnagg_plan_source_blocks and gnnagg_tune_f_chunk also
+ *    wait for it, because they hand results back to the host.
  *  - Every call returns a gnnagg_status.  Invalid arguments are detected on the
  *    host before anything is launched and leave all outputs untouched.  Index
  *    values outside [0, N) inside colidx are a contract violation that the
@@ -265,6 +265,60 @@ GNNAGG_API int gnnagg_tune_f_chunk(int op, int64_t N, const int64_t* rowptr, con
                         int64_t out_pitch, int32_t F, const int32_t* row_order, const int64_t* class_off,
                         void* workspace, size_t* workspace_bytes, void* stream, int32_t* best_f_chunk,
                         float* best_ms);
+
+/*
+ * Source blocks: the trade of Section II-B (better reuse of the feature rows against more passes over
+ * the graph) taken along the vertex dimension as well.  The vertices are cut into B blocks of
+ * ceil(N/B) consecutive ids; a blocked aggregation gathers from one block's rows of X at a time, over all
+ * destinations and all feature chunks, so that the rows it re-reads are B times fewer and stay in the
+ * caches, and carries every destination's unfinished state from block to block.
+ *
+ * gnnagg_plan_source_blocks is the per-graph step (like gnnagg_plan_rows, which it replaces for the
+ * blocked call).  Every row of the CSR must list its sources in ascending order, as gnnagg_build_csr
+ * writes them, so that a block's edges are one run of the row: GNNAGG_EINVAL otherwise (checked).
+ *
+ *   B          number of blocks, 1 .. GNNAGG_MAX_SOURCE_BLOCKS
+ *   block_ptr  [(B+1) * N] int64 out: the edges of row r with sources in block b are
+ *              colidx[block_ptr[b*N + r] .. block_ptr[(b+1)*N + r])
+ *   row_order  [B * N] int32 out: per block, the rows by the number of their edges in it, descending
+ *   class_off  HOST pointer, [B * (GNNAGG_PLAN_CLASSES+1)] int64 out: per block, as in gnnagg_plan_rows
+ *
+ * Waits for `stream`.
+ */
+#define GNNAGG_MAX_SOURCE_BLOCKS 64
+GNNAGG_API int gnnagg_plan_source_blocks(int64_t N, const int64_t* rowptr, const int32_t* colidx, int32_t B,
+                              int64_t* block_ptr, int32_t* row_order, int64_t* class_off, void* workspace,
+                              size_t* workspace_bytes, void* stream);
+
+/*
+ * gnnagg_aggregate_ws over source blocks: same operators, same layout arguments, the result of the same
+ * arithmetic contract (fp64 accumulation, one rounding; max exact).  Block b runs as one pass of the
+ * aggregation kernels over the edges block_ptr selects, with that block's row order; between blocks a
+ * destination's state waits in the workspace as doubles (max: its integer key), so the sum of a row is
+ * still taken in the row's edge order up to the grouping by lanes, and the row is rounded once, after the
+ * last block.  Mean divides by the row's whole degree.
+ *
+ *   B, block_ptr, row_order, class_off   from gnnagg_plan_source_blocks for this CSR (class_off HOST)
+ *   f_chunk    as in gnnagg_aggregate; GNNAGG_F_CHUNK_AUTO here means row pieces of two 128-byte lines
+ *              when the rows of X start on lines and are at least two pieces long, else one chunk
+ *   workspace  min(B-1, 2) arrays of N rows of F doubles (rows padded to 128-byte lines) for the states
+ *              in transit, used in turn, plus what the split rows of the longest block need; size query
+ *              as usual
+ *
+ * Only enqueues kernels.  GNNAGG_EINVAL for B outside 1 .. GNNAGG_MAX_SOURCE_BLOCKS.
+ */
+GNNAGG_API int gnnagg_aggregate_blocked(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                             const float* edge_w, const void* X, int x_dtype, int64_t x_pitch, void* out,
+                             int out_dtype, int64_t out_pitch, int32_t F, int32_t f_chunk, int32_t B,
+                             const int64_t* block_ptr, const int32_t* row_order, const int64_t* class_off,
+                             void* workspace, size_t* workspace_bytes, void* stream);
+
+/* Number of source blocks worth using for a graph with the row plan class_off (HOST pointer, the plan of
+ * gnnagg_plan_rows; NULL: 1) and an X of row pitch x_pitch (0 = F) whose first row starts on a 128-byte
+ * line; 1 means the plain calls are the faster ones (host arithmetic only; 0 for invalid arguments).
+ * Blocks pay on dense graphs only: the states in transit cost 16 bytes per output element and block. */
+GNNAGG_API int32_t gnnagg_auto_source_blocks(int64_t N, int32_t F, int x_dtype, int64_t x_pitch,
+                                  const int64_t* class_off);
 
 /*
  * Graph-attention aggregation (the GAT operator the paper evaluates in

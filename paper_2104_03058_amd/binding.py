@@ -65,6 +65,13 @@ def load_library():
         lib.gnnagg_aggregate_noalloc.restype = ci
         lib.gnnagg_aggregate_noalloc.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, vp, ci, i64, i32, i32, vp, vp, vp]
         lib.gnnagg_row_pitch.restype = i64
+        lib.gnnagg_plan_source_blocks.argtypes = [i64, vp, vp, i32, vp, vp, vp, vp, szp, vp]
+        lib.gnnagg_plan_source_blocks.restype = ci
+        lib.gnnagg_aggregate_blocked.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, vp, ci, i64, i32, i32, i32, vp, vp,
+                                                 vp, vp, szp, vp]
+        lib.gnnagg_aggregate_blocked.restype = ci
+        lib.gnnagg_auto_source_blocks.argtypes = [i64, i32, ci, i64, vp]
+        lib.gnnagg_auto_source_blocks.restype = i32
         lib.gnnagg_row_pitch.argtypes = [i32, ci]
         lib.gnnagg_gat_attention.restype = ci
         lib.gnnagg_gat_attention.argtypes = [i64, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp, i32, vp, vp, vp, szp,
@@ -362,6 +369,82 @@ def gnnagg_aggregate_noalloc(op: int, rowptr: torch.Tensor, colidx: torch.Tensor
     return out
 
 
+@dataclass
+class SourceBlocks:
+    """Per-graph tables of a blocked aggregation: where each row's edges into each block of sources begin, and a
+    row order with its host class offsets per block."""
+    B: int
+    block_ptr: torch.Tensor   # [(B+1) * N] int64
+    row_order: torch.Tensor   # [B * N] int32
+    class_off: "ctypes.Array"  # [B * (PLAN_CLASSES + 1)] int64, host
+
+
+def gnnagg_plan_source_blocks(rowptr: torch.Tensor, colidx: torch.Tensor, B: int, stream=None) -> SourceBlocks:
+    lib = load_library()
+    N = int(rowptr.shape[0]) - 1
+    dev = rowptr.device
+    need = ctypes.c_size_t(0)
+    _check("gnnagg_plan_source_blocks",
+           lib.gnnagg_plan_source_blocks(N, None, None, B, None, None, None, None, ctypes.byref(need), None))
+    ws = _workspace(need.value, dev)
+    block_ptr = torch.empty(max((B + 1) * N, 1), dtype=torch.int64, device=dev)
+    order = torch.empty(max(B * N, 1), dtype=torch.int32, device=dev)
+    class_off = (ctypes.c_int64 * (B * (PLAN_CLASSES + 1)))()
+    have = ctypes.c_size_t(ws.numel())
+    rc = lib.gnnagg_plan_source_blocks(N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"), B,
+                                       _dev(block_ptr), _dev(order), ctypes.cast(class_off, ctypes.c_void_p),
+                                       _dev(ws), ctypes.byref(have), _stream(stream))
+    _check("gnnagg_plan_source_blocks", rc)
+    return SourceBlocks(B, block_ptr, order, class_off)
+
+
+def gnnagg_aggregate_blocked(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w: Optional[torch.Tensor],
+                             X: torch.Tensor, blocks: SourceBlocks, out: Optional[torch.Tensor] = None,
+                             f_chunk: int = 0, stream=None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """gnnagg_aggregate over the source blocks of `blocks` (gnnagg_plan_source_blocks of the same CSR); X and out may
+    be row-pitched views.  The workspace (states in transit between blocks) is allocated here unless passed in."""
+    lib = load_library()
+    if X.dim() != 2:
+        raise ValueError("X must be [N, F]")
+    N, F = int(X.shape[0]), int(X.shape[1])
+    if rowptr.shape[0] != N + 1:
+        raise ValueError("rowptr must have N+1 entries")
+    if blocks.row_order.numel() < blocks.B * N or blocks.block_ptr.numel() < (blocks.B + 1) * N:
+        raise ValueError("blocks were planned for another graph")
+    if out is None:
+        out = torch.empty((N, F), dtype=torch.float32, device=X.device)
+    elif tuple(out.shape) != (N, F):
+        raise ValueError("out must be [N, F]")
+    x_pitch, out_pitch = int(X.stride(0)) if N > 1 else F, int(out.stride(0)) if N > 1 else F
+    args = lambda ws, have: lib.gnnagg_aggregate_blocked(  # noqa: E731
+        op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
+        _dev(edge_w, torch.float32, "edge_w"), _rows(X, "X"), _x_dtype(X), x_pitch, _rows(out, "out"),
+        F32 if out.dtype == torch.float32 else BF16, out_pitch, F, f_chunk, blocks.B,
+        _dev(blocks.block_ptr, torch.int64, "block_ptr"), _dev(blocks.row_order, torch.int32, "row_order"),
+        ctypes.cast(blocks.class_off, ctypes.c_void_p), ws, ctypes.byref(have), _stream(stream))
+    own = workspace is None
+    if workspace is None:
+        need = ctypes.c_size_t(0)
+        _check("gnnagg_aggregate_blocked", args(None, need))
+        workspace = torch.empty(need.value, dtype=torch.uint8, device=X.device) if need.value > 0 else _token(X.device)
+    have = ctypes.c_size_t(workspace.numel() * workspace.element_size())
+    _check("gnnagg_aggregate_blocked", args(_dev(workspace), have))
+    if own and workspace.numel() > 256:
+        workspace.record_stream(torch.cuda.current_stream() if stream is None else stream)
+    return out
+
+
+def gnnagg_aggregate_blocked_workspace_bytes(N: int, F: int, blocks: SourceBlocks) -> int:
+    need = ctypes.c_size_t(0)
+    _check("gnnagg_aggregate_blocked",
+           load_library().gnnagg_aggregate_blocked(0, N, None, None, None, None, F32, 0, None, F32, 0, F, 0, blocks.B,
+                                                   _dev(blocks.block_ptr, torch.int64, "block_ptr"),
+                                                   _dev(blocks.row_order, torch.int32, "row_order"),
+                                                   ctypes.cast(blocks.class_off, ctypes.c_void_p), None,
+                                                   ctypes.byref(need), None))
+    return int(need.value)
+
+
 def _plan_args(plan: Optional["RowPlan"], N: int):
     if plan is None or N == 0:
         return None, None
@@ -462,6 +545,13 @@ def gnnagg_auto_f_chunk(N: int, F: int, x_dtype: int = F32, x_pitch: int = 0,
     """Chunk width the library uses for f_chunk = F_CHUNK_AUTO on an X of that row pitch (0 = F) and plan."""
     class_off = ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None
     return int(load_library().gnnagg_auto_f_chunk(N, F, x_dtype, x_pitch, class_off))
+
+
+def gnnagg_auto_source_blocks(N: int, F: int, x_dtype: int = F32, x_pitch: int = 0,
+                              plan: Optional[RowPlan] = None) -> int:
+    """Number of source blocks the library recommends for this graph and width (1: use the plain calls)."""
+    return int(load_library().gnnagg_auto_source_blocks(
+        N, F, x_dtype, x_pitch, ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None))
 
 
 def gnnagg_combine(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor] = None, relu: bool = False,

@@ -44,6 +44,15 @@ struct AggArgs {
   int32_t mean;
   uint32_t lds_per_workgroup;  // host only: LDS each workgroup should occupy (0 = no cap)
   double* ws;                  // partial results of split rows: [slot][F] (null: no row is split)
+  // One source block of a blocked call (all null: the whole edge list of every row).  The call walks
+  // edges [e_begin[r], e_end[r]) of row r only; `pin` [N,F] holds the state the earlier blocks left (sums
+  // as doubles, max as its integer key in a double), `pout` [N,F] receives this block's instead of a
+  // finished row.  The degree that finishes a row (mean, empty-row rule of max) stays rowptr's.
+  const int64_t* e_begin;
+  const int64_t* e_end;
+  const double* pin;
+  double* pout;
+  int64_t p_pitch;  // doubles between the rows of pin / pout (rows start on 128-byte lines)
   // Update step at the store (Algorithm 1: Update follows Aggregate): y = act(a + bias), or with W2
   // (kernels built with FUSE only) y = act(a W2 + bias) on the aggregated row a while it is still on chip
   const float* bias;  // [F], or [H2] with W2; null: none
@@ -115,6 +124,17 @@ struct State {
 #pragma unroll
     for (int k = 0; k < VEC; ++k) p[k] = acc[k];
   }
+  // a state that another pass left joins this one: earlier edges first, as in the row's own order.  The
+  // states in transit are streamed (read once, written once): non-temporal, so that they do not push the
+  // gathered rows out of L2.
+  __device__ inline void fold_earlier(const double* p) {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) acc[k] = __builtin_nontemporal_load(p + k) + acc[k];
+  }
+  __device__ inline void hand_on(double* p) const {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) __builtin_nontemporal_store(acc[k], p + k);
+  }
 };
 
 // max: integer keys, exact and independent of the order of the operands
@@ -158,6 +178,17 @@ struct State<OPK_MAX, VEC> {
 #pragma unroll
     for (int k = 0; k < VEC; ++k) p[k] = (double)key[k];
   }
+  __device__ inline void fold_earlier(const double* p) {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      const int32_t b = (int32_t)__builtin_nontemporal_load(p + k);
+      key[k] = key[k] > b ? key[k] : b;
+    }
+  }
+  __device__ inline void hand_on(double* p) const {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) __builtin_nontemporal_store((double)key[k], p + k);
+  }
 };
 
 // Accumulator policy of the walk in gather.hpp: one 16-byte piece of the source row per edge.
@@ -197,10 +228,10 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
   int64_t r = 0, e0 = 0, e1 = 0;
   if (row_ok) {
     r = a.order ? (int64_t)a.order[role.ridx] : role.ridx;
-    e0 = a.rowptr[r];
-    e1 = a.rowptr[r + 1];
+    e0 = (a.e_begin ? a.e_begin : a.rowptr)[r];
+    e1 = (a.e_begin ? a.e_end : a.rowptr + 1)[r];
   }
-  const int64_t deg = e1 - e0;
+  int64_t deg = e1 - e0;
   if (role.split_log2 > 0) {  // this workgroup walks one piece of the row
     e0 += (int64_t)role.piece << kSplitLenLog2;
     if (e0 > e1) e0 = e1;
@@ -208,6 +239,10 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
   }
   AggAcc<T, OPK, VEC> acc;
   acc.st.init();
+  // A later source block: the lane that will write the row starts from the state the earlier blocks left
+  // (the other lanes of the row from nothing), so the read is in flight while the row is gathered and the
+  // earlier edges still come first in the sum.  Pieces of split rows meet that state in the merge kernel.
+  if (a.pin && role.writer && role.split_log2 == 0) acc.st.fold_earlier(a.pin + r * a.p_pitch + col);
   acc.xb = static_cast<const char*>(a.X) + (int64_t)col * (int64_t)sizeof(T);
   acc.rowbytes = a.x_pitch * (int64_t)sizeof(T);
   const int64_t nnz = (MODE == MODE_NARROW) ? a.rowptr[a.N] : 0;
@@ -234,7 +269,11 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
   // ---- write the slice of the output row ----------------------------------------
   if (role.writer && role.split_log2 > 0) {
     st.dump(a.ws + (int64_t)role.ws_slot * a.F + col);
+  } else if (role.writer && a.pout) {
+    // a source block that is not the last: hand the state on instead of finishing the row
+    st.hand_on(a.pout + r * a.p_pitch + col);
   } else if (role.writer) {
+    if (a.e_begin) deg = a.rowptr[r + 1] - a.rowptr[r];  // source blocks: the row's whole degree finishes it
     float res[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) res[k] = st.result(k, deg, a.mean != 0);
@@ -289,6 +328,9 @@ struct MergeArgs {
   const float* bias;  // the Update step, as in AggArgs
   const float* W2;
   int32_t H2, relu;
+  const double* pin;  // source blocks, as in AggArgs (rowptr is the whole graph's: it gives the degree)
+  double* pout;
+  int64_t p_pitch;
   Seg run[kMaxSplitSeg];
 };
 
@@ -315,6 +357,11 @@ __global__ __launch_bounds__(kBlock) void split_merge_kernel(const MergeArgs a) 
     if constexpr (OPK == OPK_MAX) o.key[0] = (int32_t)p[q * a.F];
     else o.acc[0] = p[q * a.F];
     st.merge(o);
+  }
+  if (a.pin) st.fold_earlier(a.pin + r * a.p_pitch + col);
+  if (a.pout) {
+    st.hand_on(a.pout + r * a.p_pitch + col);
+    return;
   }
   const float res = update_bias_act(st.result(0, deg, a.mean != 0), a.bias, col, a.relu);
   if (a.out_bf16) static_cast<uint16_t*>(a.out)[r * a.out_pitch + col] = (uint16_t)bf16_bits(res);
@@ -442,6 +489,16 @@ int scratch_for_current_device(void** p) {
 // Measurement override of the resident-workgroup cap (gnnagg_set_workgroup_cap): -1 = the library's rule.
 std::atomic<int> forced_workgroup_cap{-1};
 
+// One source block of a blocked call (all null: a plain call).  pin and pout must not be the same array:
+// lanes that re-read a slice's last columns store the same element twice.
+struct Block {
+  const int64_t* e_begin = nullptr;
+  const int64_t* e_end = nullptr;
+  const double* pin = nullptr;
+  double* pout = nullptr;
+  int64_t p_pitch = 0;
+};
+
 // The Update step of a call (all null / zero: none).
 struct Update {
   const float* bias = nullptr;
@@ -500,10 +557,11 @@ int check_pitches_and_plan(int64_t N, int32_t F, int32_t out_cols, int64_t* x_pi
 int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* edge_w,
                    const void* X, int x_dtype, int64_t x_pitch, void* out, int out_dtype, int64_t out_pitch,
                    int32_t F, int32_t f_chunk, const int32_t* row_order, const int64_t* class_off, double* ws,
-                   const Update& up, hipStream_t stream) {
+                   const Update& up, hipStream_t stream, const Block& blk = Block()) {
   const size_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
   if ((uint64_t)x_pitch * xs >= (1ull << 32)) return GNNAGG_EUNSUPPORTED;  // row addresses: 32 x 32 -> 64 bit
   const bool rows_on_lines = ((uintptr_t)X % 128) == 0 && ((uint64_t)x_pitch * xs) % 128 == 0;
+  if (up.W2 && blk.e_begin) return GNNAGG_EUNSUPPORTED;
   if (up.W2) f_chunk = 0;  // the dense layer contracts whole rows
   if (f_chunk == GNNAGG_F_CHUNK_AUTO) f_chunk = auto_f_chunk(N, F, (int)xs, rows_on_lines, class_off);
   LaunchList launches;
@@ -534,6 +592,11 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
     a.sl = launches[k];
     a.mean = (op == GNNAGG_MEAN);
     a.ws = ws;
+    a.e_begin = blk.e_begin;
+    a.e_end = blk.e_end;
+    a.pin = blk.pin;
+    a.pout = blk.pout;
+    a.p_pitch = blk.p_pitch;
     a.bias = up.bias;
     a.W2 = up.W2;
     a.H2 = up.H2;
@@ -567,6 +630,9 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
     m.W2 = up.W2;
     m.H2 = up.H2;
     m.relu = up.relu;
+    m.pin = blk.pin;
+    m.pout = blk.pout;
+    m.p_pitch = blk.p_pitch;
     m.nrun = 0;
     m.rows = 0;
     const SegTable& st = args[0].segs;
@@ -684,6 +750,61 @@ extern "C" int gnnagg_aggregate_noalloc(int op, int64_t N, const int64_t* rowptr
                         row_order, class_off, static_cast<double*>(ws), Update(), (hipStream_t)stream_);
 }
 
+extern "C" int gnnagg_aggregate_blocked(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                                        const float* edge_w, const void* X, int x_dtype, int64_t x_pitch,
+                                        void* out, int out_dtype, int64_t out_pitch, int32_t F, int32_t f_chunk,
+                                        int32_t B, const int64_t* block_ptr, const int32_t* row_order,
+                                        const int64_t* class_off, void* workspace, size_t* workspace_bytes,
+                                        void* stream_) {
+  if (!workspace_bytes) return GNNAGG_ENULL;
+  if (B < 1 || B > GNNAGG_MAX_SOURCE_BLOCKS) return GNNAGG_EINVAL;
+  if (!class_off || !row_order || (N > 0 && !block_ptr)) return GNNAGG_ENULL;
+  constexpr int kOffs = GNNAGG_PLAN_CLASSES + 1;
+  size_t need_split = 0;
+  for (int32_t b = 0; b < B; ++b) {  // the blocks run one after another and share the split rows' slots
+    size_t need_b = 0;
+    int rc = check_pitches_and_plan(N, F, F, &x_pitch, &out_pitch, row_order, class_off + (size_t)b * kOffs, &need_b);
+    if (rc != GNNAGG_OK) return rc;
+    if (need_b > need_split) need_split = need_b;
+  }
+  const int64_t p_pitch = ceil_div(F, 16) * 16;  // rows of the states in transit start on 128-byte lines
+  const size_t state_bytes = align_up((size_t)N * (size_t)p_pitch * sizeof(double));
+  const int n_state = B - 1 < 2 ? B - 1 : 2;
+  const size_t need = (size_t)n_state * state_bytes + need_split;
+  if (!workspace) {
+    *workspace_bytes = need;
+    return GNNAGG_OK;
+  }
+  if (*workspace_bytes < need || ((uintptr_t)workspace & 255u)) return GNNAGG_EWORKSPACE;
+  bool nothing;
+  int rc = check_aggregate_args(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, f_chunk, row_order,
+                                class_off, &nothing);
+  if (rc != GNNAGG_OK || nothing) return rc;
+  if ((uintptr_t)block_ptr % 8) return GNNAGG_EINVAL;
+  if (f_chunk == GNNAGG_F_CHUNK_AUTO) {
+    const int64_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
+    const bool rows_on_lines = ((uintptr_t)X % 128) == 0 && ((uint64_t)x_pitch * (uint64_t)xs) % 128 == 0;
+    const int32_t piece = (x_dtype == GNNAGG_F32) ? 64 : 128;  // two lines per piece
+    f_chunk = (rows_on_lines && F >= 2 * piece) ? piece : 0;
+  }
+  char* base = static_cast<char*>(workspace);
+  double* state[2] = {reinterpret_cast<double*>(base), reinterpret_cast<double*>(base + state_bytes)};
+  double* ws = need_split > 0 ? reinterpret_cast<double*>(base + (size_t)n_state * state_bytes) : nullptr;
+  for (int32_t b = 0; b < B; ++b) {
+    Block blk;
+    blk.e_begin = block_ptr + (int64_t)b * N;
+    blk.e_end = block_ptr + (int64_t)(b + 1) * N;
+    blk.pin = b > 0 ? state[(b - 1) & 1] : nullptr;
+    blk.pout = b + 1 < B ? state[b & 1] : nullptr;
+    blk.p_pitch = p_pitch;
+    rc = aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, x_pitch, out, out_dtype, out_pitch, F, f_chunk,
+                        row_order + (int64_t)b * N, class_off + (size_t)b * kOffs, ws, Update(), (hipStream_t)stream_,
+                        blk);
+    if (rc != GNNAGG_OK) return rc;
+  }
+  return GNNAGG_OK;
+}
+
 extern "C" int gnnagg_tune_f_chunk(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
                                    const float* edge_w, const void* X, int x_dtype, int64_t x_pitch, void* out,
                                    int out_dtype, int64_t out_pitch, int32_t F, const int32_t* row_order,
@@ -777,6 +898,20 @@ extern "C" int64_t gnnagg_row_pitch(int32_t F, int dtype) {
     padded = ceil_div(bytes, 128) * 128;
   }
   return padded / elem;
+}
+
+extern "C" int32_t gnnagg_auto_source_blocks(int64_t N, int32_t F, int x_dtype, int64_t x_pitch,
+                                             const int64_t* class_off) {
+  if (N < 0 || F <= 0 || (x_dtype != GNNAGG_F32 && x_dtype != GNNAGG_BF16)) return 0;
+  const int elem = x_dtype == GNNAGG_F32 ? 4 : 2;
+  if (x_pitch == 0) x_pitch = F;
+  if (x_pitch < F) return 0;
+  if (class_off) {
+    if (class_off[0] != 0 || class_off[GNNAGG_PLAN_CLASSES] != N) return 0;
+    for (int k = 0; k < GNNAGG_PLAN_CLASSES; ++k)
+      if (class_off[k] > class_off[k + 1]) return 0;
+  }
+  return auto_source_blocks(N, F, elem, ((uint64_t)x_pitch * (uint64_t)elem) % 128 == 0, class_off);
 }
 
 extern "C" int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype, int64_t x_pitch, const int64_t* class_off) {

@@ -70,12 +70,15 @@ __device__ inline int degree_class(int64_t deg) {  // 0 for empty, else 1 + floo
   return c > 32 ? 32 : c;
 }
 
-__global__ __launch_bounds__(kBlock) void make_degree_keys_kernel(const int64_t* __restrict__ rowptr, int64_t N,
+// Row r owns the edges [begin[r], end[r]): end = begin + 1 for a whole CSR, two rows of a block table for
+// one source block.
+__global__ __launch_bounds__(kBlock) void make_degree_keys_kernel(const int64_t* __restrict__ begin,
+                                                                  const int64_t* __restrict__ end, int64_t N,
                                                                   uint64_t* __restrict__ keys,
                                                                   uint32_t* __restrict__ vals) {
   const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (r >= N) return;
-  int64_t deg = rowptr[r + 1] - rowptr[r];
+  int64_t deg = end[r] - begin[r];
   if (deg < 0) deg = 0;
   if (deg > 0xffffffffll) deg = 0xffffffffll;
   keys[r] = 0xffffffffull - (uint64_t)deg;  // ascending key = descending degree
@@ -180,6 +183,45 @@ CsrWorkspace carve_sort_workspace(void* base, int64_t n) {
 
 unsigned grid_for(int64_t n) { return (unsigned)ceil_div(n > 0 ? n : 1, kBlock); }
 
+// ---- source blocks -----------------------------------------------------------
+// Flags a row whose sources are not in ascending order: one wave per row, the lanes stride over the
+// neighbouring pairs of its edge list.
+__global__ __launch_bounds__(kBlock) void rows_ascending_kernel(const int64_t* __restrict__ rowptr,
+                                                                const int32_t* __restrict__ colidx, int64_t N,
+                                                                uint32_t* __restrict__ bad) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  const int64_t waves = (int64_t)gridDim.x * kWavesPerBlock;
+  bool wrong = false;
+  for (int64_t r = wave; r < N; r += waves) {
+    const int64_t e0 = rowptr[r], e1 = rowptr[r + 1];
+    for (int64_t e = e0 + lane; e + 1 < e1; e += kWave) wrong |= colidx[e] > colidx[e + 1];
+  }
+  if (wrong) atomicOr(bad, 1u);
+}
+
+// block_ptr[b * N + r] = first edge of row r whose source lies in block b or a later one (blocks of
+// `per_block` consecutive vertex ids); b = 0 .. B, so that block b of row r is
+// [block_ptr[b * N + r], block_ptr[(b + 1) * N + r]).  One thread per entry, a binary search in the row.
+__global__ __launch_bounds__(kBlock) void block_bounds_kernel(const int64_t* __restrict__ rowptr,
+                                                              const int32_t* __restrict__ colidx, int64_t N,
+                                                              int32_t B, int64_t per_block,
+                                                              int64_t* __restrict__ block_ptr) {
+  const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (t >= N * (int64_t)(B + 1)) return;
+  const int64_t b = t / N, r = t - b * N;
+  int64_t lo = rowptr[r], hi = rowptr[r + 1];
+  if (b == 0) hi = lo;
+  else if (b == B) lo = hi;
+  const int64_t first_source = b * per_block;
+  while (lo < hi) {
+    const int64_t mid = lo + ((hi - lo) >> 1);
+    if ((int64_t)colidx[mid] >= first_source) hi = mid;
+    else lo = mid + 1;
+  }
+  block_ptr[t] = lo;
+}
+
 }  // namespace
 }  // namespace gnnagg
 
@@ -238,6 +280,28 @@ extern "C" int gnnagg_build_csr(int64_t N, int64_t E, const int32_t* src, const 
   return bad ? GNNAGG_EINVAL : GNNAGG_OK;
 }
 
+// Row plan of the rows [begin[r], end[r]): degree-descending order and the class offsets (host).  Waits
+// for the stream.
+static int plan_rows_impl(int64_t N, const int64_t* begin, const int64_t* end, int32_t* row_order, int64_t* d_off,
+                          int64_t* class_off, const CsrWorkspace& w, hipStream_t stream) {
+  hipLaunchKernelGGL(make_degree_keys_kernel, dim3(grid_for(N)), dim3(kBlock), 0, stream, begin, end, N, w.keys_a,
+                     w.vals_a);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  bool in_a = true;
+  KeySource from_a;
+  from_a.keys = w.keys_a;
+  int rc = radix_sort(from_a, w.keys_a, w.vals_a, w.keys_b, w.vals_b, N, 0, 32, true, w.hist, w.scan, stream, &in_a);
+  if (rc != GNNAGG_OK) return rc;
+  hipLaunchKernelGGL(plan_finish_kernel, dim3(grid_for(N + 1)), dim3(kBlock), 0, stream,
+                     (const uint64_t*)(in_a ? w.keys_a : w.keys_b), (const uint32_t*)(in_a ? w.vals_a : w.vals_b), N,
+                     row_order, d_off);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  GNNAGG_HIP_TRY(hipMemcpyAsync(class_off, d_off, sizeof(int64_t) * (GNNAGG_PLAN_CLASSES + 1),
+                                hipMemcpyDeviceToHost, stream));
+  GNNAGG_HIP_TRY(hipStreamSynchronize(stream));
+  return GNNAGG_OK;
+}
+
 extern "C" int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_order, int64_t* class_off,
                                 void* workspace, size_t* workspace_bytes, void* stream_) {
   if (N < 0) return GNNAGG_EINVAL;
@@ -258,21 +322,54 @@ extern "C" int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
     for (int k = 0; k <= GNNAGG_PLAN_CLASSES; ++k) class_off[k] = 0;
     return GNNAGG_OK;
   }
-  hipLaunchKernelGGL(make_degree_keys_kernel, dim3(grid_for(N)), dim3(kBlock), 0, stream, rowptr, N, w.keys_a,
-                     w.vals_a);
+  return plan_rows_impl(N, rowptr, rowptr + 1, row_order, d_off, class_off, w, stream);
+}
+
+extern "C" int gnnagg_plan_source_blocks(int64_t N, const int64_t* rowptr, const int32_t* colidx, int32_t B,
+                                         int64_t* block_ptr, int32_t* row_order, int64_t* class_off,
+                                         void* workspace, size_t* workspace_bytes, void* stream_) {
+  if (N < 0 || B < 1 || B > GNNAGG_MAX_SOURCE_BLOCKS) return GNNAGG_EINVAL;
+  if (!workspace_bytes) return GNNAGG_ENULL;
+  if (N >= (1ll << 31)) return GNNAGG_EUNSUPPORTED;
+  CsrWorkspace w = carve_sort_workspace(workspace, N);
+  Carver extra(workspace ? (char*)workspace + w.bytes : nullptr);
+  int64_t* d_off = extra.take<int64_t>(GNNAGG_PLAN_CLASSES + 1);
+  uint32_t* bad = extra.take<uint32_t>(64);
+  const size_t need = w.bytes + extra.used;
+  if (!workspace) {
+    *workspace_bytes = need;
+    return GNNAGG_OK;
+  }
+  if (!rowptr || !class_off || (N > 0 && (!row_order || !block_ptr || !colidx))) return GNNAGG_ENULL;
+  if (*workspace_bytes < need || ((uintptr_t)workspace & 255u)) return GNNAGG_EWORKSPACE;
+  if (((uintptr_t)rowptr % 8) || ((uintptr_t)colidx % 4) || ((uintptr_t)block_ptr % 8) || ((uintptr_t)row_order % 4))
+    return GNNAGG_EINVAL;
+  hipStream_t stream = (hipStream_t)stream_;
+  if (N == 0) {
+    for (int k = 0; k < B * (GNNAGG_PLAN_CLASSES + 1); ++k) class_off[k] = 0;
+    return GNNAGG_OK;
+  }
+  // the edges of a block are one run of a row only if the row lists its sources in ascending order
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(1), 0, stream, bad, 0u);
   GNNAGG_HIP_TRY(hipGetLastError());
-  bool in_a = true;
-  KeySource from_a;
-  from_a.keys = w.keys_a;
-  int rc = radix_sort(from_a, w.keys_a, w.vals_a, w.keys_b, w.vals_b, N, 0, 32, true, w.hist, w.scan, stream, &in_a);
-  if (rc != GNNAGG_OK) return rc;
-  hipLaunchKernelGGL(plan_finish_kernel, dim3(grid_for(N + 1)), dim3(kBlock), 0, stream,
-                     (const uint64_t*)(in_a ? w.keys_a : w.keys_b), (const uint32_t*)(in_a ? w.vals_a : w.vals_b), N,
-                     row_order, d_off);
+  const int64_t waves = N < (1 << 16) ? N : (1 << 16);
+  hipLaunchKernelGGL(rows_ascending_kernel, dim3((unsigned)ceil_div(waves, kWavesPerBlock)), dim3(kBlock), 0, stream,
+                     rowptr, colidx, N, bad);
   GNNAGG_HIP_TRY(hipGetLastError());
-  GNNAGG_HIP_TRY(hipMemcpyAsync(class_off, d_off, sizeof(int64_t) * (GNNAGG_PLAN_CLASSES + 1),
-                                hipMemcpyDeviceToHost, stream));
+  uint32_t h_bad = 0;
+  GNNAGG_HIP_TRY(hipMemcpyAsync(&h_bad, bad, sizeof(h_bad), hipMemcpyDeviceToHost, stream));
   GNNAGG_HIP_TRY(hipStreamSynchronize(stream));
+  if (h_bad) return GNNAGG_EINVAL;
+  const int64_t per_block = ceil_div(N, (int64_t)B);  // vertices per source block
+  hipLaunchKernelGGL(block_bounds_kernel, dim3(grid_for(N * (int64_t)(B + 1))), dim3(kBlock), 0, stream, rowptr,
+                     colidx, N, B, per_block, block_ptr);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  for (int32_t b = 0; b < B; ++b) {
+    int rc = plan_rows_impl(N, block_ptr + (int64_t)b * N, block_ptr + (int64_t)(b + 1) * N,
+                            row_order + (int64_t)b * N, d_off, class_off + (int64_t)b * (GNNAGG_PLAN_CLASSES + 1), w,
+                            stream);
+    if (rc != GNNAGG_OK) return rc;
+  }
   return GNNAGG_OK;
 }
 

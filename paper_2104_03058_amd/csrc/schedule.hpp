@@ -367,6 +367,23 @@ inline int32_t auto_f_chunk(int64_t N, int32_t F, int elem_bytes, bool rows_on_l
   return F;
 }
 
+// Whether a graph is worth aggregating over source blocks (gnnagg_aggregate_blocked), and over how many.
+// A blocked run re-reads B times fewer rows of X per pass, so more of the gathers hit L2, and pays for it
+// with the states in transit: 16 bytes per output element and block boundary, written and read back.  The
+// gathers outweigh that only when a row has many edges: on power-law graphs of 50,000-1,500,000 rows
+// (bench.py --validate-auto times 2, 4 and 8 blocks at pieces of 1, 2 and 4 lines next to the plain call)
+// fp32 shapes of mean degree 200-600 and at least 100,000 rows run 4-19 % faster with 4 blocks and two-line
+// pieces than the plain call at its best width; at mean degree 150 and below, on smaller graphs and with
+// bf16 rows (whose plain passes are not bound by L2 misses) the plain call wins, by 5-70 %.  2 to 6 blocks
+// are within a few per cent of each other; 8 and more lose to the traffic of the states.  Returns 1 for
+// "do not block".
+inline int32_t auto_source_blocks(int64_t N, int64_t F, int elem_bytes, bool rows_on_lines, const int64_t* class_off) {
+  if (!class_off || !rows_on_lines || elem_bytes != 4 || F < 128 || N < 100000) return 1;
+  double mean_degree, hot_share;
+  degree_profile(class_off, N, 32768, &mean_degree, &hot_share);
+  return mean_degree >= 200.0 ? 4 : 1;
+}
+
 // How many workgroups of the aggregation kernel should share a compute unit.  Every resident wave
 // keeps eight row gathers in flight, and every line in flight occupies L2; at full occupancy the lines
 // in flight alone (256 CUs x 16-20 waves x 8 x ~7 lines x 128 B = ~30 MB) are as large as the whole L2

@@ -200,6 +200,80 @@ def test_update_and_no_alloc_entry_points_validate_on_the_host(lib):
     assert re.search(r"#define\s+GNNAGG_NOALLOC_SCRATCH_BYTES\s+\(8u << 20\)", text)
 
 
+def test_source_block_entry_points_validate_on_the_host(lib):
+    EINVAL, ENULL, EUNSUP, EWS = -1, -2, -3, -4
+    one, other = ctypes.c_void_p(4096), ctypes.c_void_p(8192)
+    need = ctypes.c_size_t(0)
+    big = ctypes.c_size_t(1 << 30)
+    off = (ctypes.c_int64 * (3 * 34))()
+    for b in range(3):
+        for k in range(34):
+            off[b * 34 + k] = 0 if k <= 24 else 100  # 100 rows of 128..255 edges in every block
+    offp = ctypes.cast(off, ctypes.c_void_p)
+    plan = lib.gnnagg_plan_source_blocks
+    assert plan(10, None, None, 2, None, None, None, None, None, None) == ENULL          # no size pointer
+    for B in (0, -3, 65):
+        assert plan(10, None, None, B, None, None, None, None, ctypes.byref(need), None) == EINVAL
+    assert plan(-1, None, None, 2, None, None, None, None, ctypes.byref(need), None) == EINVAL
+    assert plan(1 << 31, None, None, 2, None, None, None, None, ctypes.byref(need), None) == EUNSUP
+    assert plan(1000, None, None, 2, None, None, None, None, ctypes.byref(need), None) == 0 and need.value > 0
+    small = ctypes.c_size_t(need.value - 1)
+    assert plan(1000, one, one, 2, one, one, offp, one, ctypes.byref(small), None) == EWS
+    assert plan(1000, None, one, 2, one, one, offp, one, ctypes.byref(big), None) == ENULL
+    assert plan(1000, one, one, 2, None, one, offp, one, ctypes.byref(big), None) == ENULL
+    assert plan(1000, one, one, 2, one, one, None, one, ctypes.byref(big), None) == ENULL
+    assert plan(1000, one, one, 2, ctypes.c_void_p(4100), one, offp, one, ctypes.byref(big), None) == EINVAL
+    assert plan(0, one, one, 3, one, one, offp, one, ctypes.byref(big), None) == 0 and off[2 * 34 + 33] == 0
+    for b in range(3):
+        for k in range(34):
+            off[b * 34 + k] = 0 if k <= 24 else 100
+
+    blocked = lib.gnnagg_aggregate_blocked
+
+    def call(op=0, N=100, X=one, F=8, fc=0, B=3, bp=one, order=one, co=offp, out=other, x_pitch=0, out_pitch=0,
+             ws=one, wsb=big):
+        return blocked(op, N, one, one, one, X, 0, x_pitch, out, 0, out_pitch, F, fc, B, bp, order, co, ws,
+                       ctypes.byref(wsb) if wsb is not None else None, None)
+
+    assert call(wsb=None) == ENULL
+    assert call(B=0) == EINVAL and call(B=65) == EINVAL
+    assert call(co=None) == ENULL and call(order=None) == ENULL and call(bp=None) == ENULL
+    assert call(op=7) == EINVAL
+    assert call(out=one) == EINVAL                     # out aliases X
+    assert call(x_pitch=4) == EINVAL                   # a pitch below F
+    assert call(bp=ctypes.c_void_p(4100)) == EINVAL
+    # workspace: two arrays of N rows of 16 doubles (8 columns padded to a 128-byte line), no split rows
+    assert call(ws=None, wsb=need) == 0 and need.value == 2 * 100 * 16 * 8
+    assert call(ws=None, wsb=need, B=2) == 0 and need.value == 100 * 16 * 8
+    assert call(ws=None, wsb=need, B=1) == 0 and need.value == 0
+    assert call(ws=None, wsb=need, F=602) == 0 and need.value == 2 * 100 * 608 * 8
+    assert call(wsb=ctypes.c_size_t(2 * 100 * 16 * 8 - 1)) == EWS
+    assert call(ws=ctypes.c_void_p(4100)) == EWS
+    empty = (ctypes.c_int64 * (3 * 34))()               # the plan of a graph without vertices
+    assert call(N=0, X=None, out=None, bp=None, co=ctypes.cast(empty, ctypes.c_void_p)) == 0
+    assert call(N=0, X=None, out=None, bp=None) == EINVAL  # a plan for 100 rows
+
+
+def test_source_block_rule(lib):
+    """Blocks pay on dense fp32 graphs of at least 100,000 rows whose rows start on lines; nowhere else."""
+    import paper_2104_03058_amd as g
+    N = 232965
+    dense = plan_of(N, {15: 60, 14: 700, 13: 4000, 12: 12000, 11: 25000, 10: 40000, 9: 50000, 8: 45000, 7: 30000,
+                        6: 15000, 5: 8000})                  # mean degree ~ 500
+    medium = plan_of(N, {11: 3000, 9: 20000, 8: 60000, 7: 80000, 6: 50000, 5: 19965})   # mean degree ~ 130
+    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 608, dense) == 4
+    assert g.gnnagg_auto_source_blocks(N, 128, g.F32, 128, dense) == 4
+    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 602, dense) == 1     # rows not on lines
+    assert g.gnnagg_auto_source_blocks(N, 64, g.F32, 64, dense) == 1       # narrow rows: one pass per block is short
+    assert g.gnnagg_auto_source_blocks(N, 512, g.BF16, 512, dense) == 1    # bf16
+    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 608, medium) == 1    # too few edges per row
+    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 608, None) == 1      # no plan
+    small = plan_of(60000, {12: 2000, 10: 20000, 9: 38000})
+    assert g.gnnagg_auto_source_blocks(60000, 602, g.F32, 608, small) == 1  # small graph
+    assert g.gnnagg_auto_source_blocks(10, 0, g.F32) == 0 and g.gnnagg_auto_source_blocks(10, 8, 7) == 0
+    assert g.gnnagg_auto_source_blocks(10, 8, g.F32, 4) == 0
+
+
 # ------------------------------------------------------------------ launch geometry
 @pytest.fixture(scope="module")
 def checker(tmp_path_factory):

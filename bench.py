@@ -94,23 +94,24 @@ WORKLOADS = {
 PROBES = ["probe-l2-line", "probe-mall-line", "probe-hbm-line", "probe-hbm-row"]
 
 # "name@W" runs workload `name` at chunk width W ("all" = one chunk): the sweeps of the benchmark configurations;
-# "name#B" (before any "@W") runs it over B source blocks (gnnagg_plan_source_blocks + gnnagg_aggregate_blocked)
+# "name#B" (before any "@W") runs it over B source blocks (gnnagg_plan_source_blocks + gnnagg_aggregate_blocked),
+# "name#auto" over as many as gnnagg_auto_source_blocks recommends (1 = the plain call)
 def split_name(workload):
     """(name in WORKLOADS, source blocks or 0, chunk-width suffix or '')"""
     head, _, width = workload.partition("@")
     base, _, blocks = head.partition("#")
-    return base, (int(blocks) if blocks else 0), width
+    return base, (-1 if blocks == "auto" else int(blocks) if blocks else 0), width
 
 
 DEFAULT_ALSO = (
     PROBES
     + ["c4-gcn@8", "c4-gcn@16", "c4-gcn@32", "c4-gcn@64", "c4-gcn@all",
-       "c4-mean", "c4-mean@8", "c4-mean@16", "c4-mean@32", "c4-mean@64", "c4-mean@all",
+       "c4-gcn", "c4-mean#auto", "c4-mean", "c4-mean@8", "c4-mean@16", "c4-mean@32", "c4-mean@64", "c4-mean@all",
        "c4-hid32-gcn", "c4-hid8-gcn", "c4-gat", "c4-combine-32", "c4-layer-32", "c4-layer-32-fused",
        "c4-layer2-32-41-fused",
        "c5-sum", "c5-max", "c5-sum-f32", "c5-sum-f16", "c5-sum-f32-ranked", "c5-sum-f16-ranked",
        "c5-layer-16", "c5-layer-16-ranked",
-       "c6-hid32-gcn", "c6-hid16-gcn", "c6-hid8-gcn", "c6-hid32-mean", "c6-gat",
+       "c6-gcn#auto", "c6-gcn", "c6-hid32-gcn", "c6-hid16-gcn", "c6-hid8-gcn", "c6-hid32-mean", "c6-gat",
        "c2-mean", "c3-gat", "c1-gcn", "c1-gcn@16", "c1-gcn@64", "c1-gcn@all"])
 CPU_BASELINE_ALSO = {"c5-sum": 5.0, "c5-max": 5.0}     # multi-threaded checker on a bounded sample (seconds)
 SINGLE_THREAD_ALSO = {"c1-gcn", "c2-mean", "c3-gat"}    # whole graph on one thread
@@ -306,7 +307,7 @@ class Bench:
         rec = self.traffic.get(workload)
         traffic, src = None, None
         if rec and rec.get("kernel_source_hash") == kernel_source_hash(rec.get("kernel_sources", [])) and all(
-                rec.get(k) == cfg.get(k) for k in ("f_chunk_used", "x_row_pitch") if k in rec):
+                rec.get(k) == cfg.get(k) for k in ("f_chunk_used", "x_row_pitch", "source_blocks") if k in rec):
             traffic, src = rec["fetch_bytes"] + rec["write_bytes"], rec["source"]
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": src,
@@ -362,6 +363,10 @@ class Bench:
         del d_X0
         op = {"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname]
 
+        if n_blocks < 0:
+            n_blocks = g.gnnagg_auto_source_blocks(N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)),
+                                                   c["plan"])
+            n_blocks = 0 if n_blocks <= 1 else n_blocks
         if n_blocks:  # per graph, like the CSR and the plan; the states in transit live in a workspace kept here
             g.gnnagg_plan_source_blocks(c["rp"], d_ci, n_blocks)
             torch.cuda.synchronize()
@@ -382,7 +387,7 @@ class Bench:
         nnz = c["nnz"]
         x_bytes = 2 if xdt == "bf16" else 4
         if f_chunk == -1 and n_blocks:  # the blocked call's own rule (its header): line pieces on aligned rows
-            piece = 128 if xdt == "bf16" else 32
+            piece = 128 if xdt == "bf16" else 64
             on_lines = (int(d_X.stride(0)) * (2 if xdt == "bf16" else 4)) % 128 == 0
             f_eff = piece if (on_lines and F >= 2 * piece) else 0
         else:
@@ -888,7 +893,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c4-gcn",
+    ap.add_argument("--workload", default="c4-gcn#auto",
                     help="a workload name (optionally name@width), or 'copy' for the library's plain copy kernel "
                          "on 1 GiB alone (profiler calibration)")
     ap.add_argument("--f-chunk", type=int, default=-1,
@@ -946,19 +951,20 @@ def main():
         if split_name(w)[0] not in WORKLOADS:
             sys.exit("unknown workload %s" % w)
     cpu = not args.no_cpu_baseline
+    main_base = split_name(args.workload)[0]
     done = {}
     # the probes first (ceilings), then the main workload, then the rest in the order given (grouped by graph)
     for w in [w for w in also_names if w in PROBES]:
         done[w] = b.measure(w, 0)
     # a probe always runs on whole rows: that is the configuration its ceiling is quoted for
-    rec = b.measure(args.workload, 0 if args.workload in PROBES else args.f_chunk, args.cpu_seconds if cpu else 0.0,
-                    cpu and args.workload in SINGLE_THREAD_ALSO)
+    rec = b.measure(args.workload, 0 if main_base in PROBES else args.f_chunk, args.cpu_seconds if cpu else 0.0,
+                    cpu and main_base in SINGLE_THREAD_ALSO)
     sweeps = {}
     if cpu and args.cpu_chunk_sweep not in ("none", ""):
-        widths = (CPU_CHUNK_SWEEPS.get(args.workload) if args.cpu_chunk_sweep == "default"
+        widths = (CPU_CHUNK_SWEEPS.get(main_base) if args.cpu_chunk_sweep == "default"
                   else [int(v) for v in args.cpu_chunk_sweep.split(",")])
         if widths:  # now, while the main workload's graph and features are still in host memory
-            sweeps[args.workload] = b.cpu_chunk_sweep(args.workload, widths)
+            sweeps[main_base] = b.cpu_chunk_sweep(main_base, widths)
     for w in also_names:
         if w in done:
             continue

@@ -461,11 +461,13 @@ def test_bench_module_is_importable_and_its_workloads_name_known_graphs():
                           "layer-fused", "agg-dense", "mean-srcblock"), name
         assert xdt in ("f32", "bf16"), name
     for name in bench.DEFAULT_ALSO + list(bench.CPU_BASELINE_ALSO) + list(bench.SINGLE_THREAD_ALSO):
-        assert name.split("@")[0] in bench.WORKLOADS, name
+        assert bench.split_name(name)[0] in bench.WORKLOADS, name
     # the sweeps the two benchmark configurations name are part of the default run
     for name in ["c1-gcn@16", "c1-gcn@64", "c1-gcn@all"] + ["c4-%s@%s" % (o, w) for o in ("gcn", "mean")
                                                             for w in ("8", "16", "32", "64", "all")]:
         assert name in bench.DEFAULT_ALSO, name
+    assert bench.split_name("c4-gcn#4@64") == ("c4-gcn", 4, "64") and bench.split_name("c4-gcn#auto") == ("c4-gcn", -1, "")
+    assert bench.split_name("c1-gcn@all") == ("c1-gcn", 0, "all")
     # line requests per edge: rows on lines, summed over the chunk passes
     assert bench.gather_lines_per_edge(602, 4, 608, 602) == 19
     assert bench.gather_lines_per_edge(602, 4, 608, 32) == 19

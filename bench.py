@@ -307,7 +307,8 @@ class Bench:
         rec = self.traffic.get(workload)
         traffic, src = None, None
         if rec and rec.get("kernel_source_hash") == kernel_source_hash(rec.get("kernel_sources", [])) and all(
-                rec.get(k) == cfg.get(k) for k in ("f_chunk_used", "x_row_pitch", "source_blocks") if k in rec):
+                (rec.get(k) or 0) == (cfg.get(k) or 0) for k in ("f_chunk_used", "x_row_pitch", "source_blocks")
+                if k in rec):
             traffic, src = rec["fetch_bytes"] + rec["write_bytes"], rec["source"]
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": src,

@@ -23,6 +23,8 @@ FLAGS = [
     "-Wall", "-Wno-unused-command-line-argument",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
+# extra -D definitions for the experiments the sources provide switches for (e.g. -DGNNAGG_STAGE_INDICES=1)
+FLAGS += os.environ.get("GNNAGG_HIPCC_DEFINES", "").split()
 
 
 def _compile(src: str) -> str:

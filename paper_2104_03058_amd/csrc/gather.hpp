@@ -174,6 +174,78 @@ __device__ inline void gather_wide(Acc& acc, const int32_t* __restrict__ colidx,
   }
 }
 
+// The same walk with the indices handed round through LDS instead of swizzles: every lane parks the index
+// (and weight) it loaded in its wave's tile, and a batch reads its eight entries back as two 16-byte LDS
+// reads per lane.  The lanes of a slot only ever read what lanes of the same slot wrote, and a wave's LDS
+// operations execute in order, so a wavefront-scope fence (a scheduling barrier for the compiler) is all
+// the synchronisation needed.  tile: 2 * kWave words owned by this wave, 16-byte aligned.
+__device__ inline void stage_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int K, typename Acc>
+__device__ inline void staged_batch(Acc& acc, const int32_t* slot_tile) {
+  typedef int32_t i32x4_a __attribute__((ext_vector_type(4)));
+  const i32x4_a a = *reinterpret_cast<const i32x4_a*>(slot_tile + K * kUnroll);
+  const i32x4_a b = *reinterpret_cast<const i32x4_a*>(slot_tile + K * kUnroll + 4);
+  const int32_t j[kUnroll] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+  float wj[kUnroll];
+  if constexpr (Acc::kWeighted) {
+    const i32x4_a c = *reinterpret_cast<const i32x4_a*>(slot_tile + kWave + K * kUnroll);
+    const i32x4_a d = *reinterpret_cast<const i32x4_a*>(slot_tile + kWave + K * kUnroll + 4);
+    wj[0] = __int_as_float(c.x); wj[1] = __int_as_float(c.y); wj[2] = __int_as_float(c.z); wj[3] = __int_as_float(c.w);
+    wj[4] = __int_as_float(d.x); wj[5] = __int_as_float(d.y); wj[6] = __int_as_float(d.z); wj[7] = __int_as_float(d.w);
+  } else {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) wj[u] = 1.0f;
+  }
+  gather_batch<true>(acc, [&](int u) { return j[u] >= 0; }, [&](int u) { return j[u]; },
+                     [&](int u) { return wj[u]; }, (int64_t)j[0]);
+}
+
+template <int G, typename Acc>
+__device__ inline void gather_wide_staged(Acc& acc, const int32_t* __restrict__ colidx,
+                                          const float* __restrict__ edge_w, int64_t e0, int64_t e1, int ng,
+                                          int p_log2, int lane, int32_t* tile) {
+  static_assert(kUnroll == 8, "a batch is eight entries");
+  const int gl = lane & (G - 1);
+  const int32_t* slot_tile = tile + (lane & ~(G - 1));
+  const int shift = 3 + p_log2;
+  const int64_t outer = (int64_t)G << p_log2;
+  const int64_t lane_pos = ((int64_t)(gl >> 3) << shift) + (ng << 3) + (gl & 7);
+  int32_t idx_c = -1;
+  float w_c = 0.0f;
+  if (e0 + lane_pos < e1) {
+    idx_c = colidx[e0 + lane_pos];
+    if (Acc::kWeighted) w_c = edge_w[e0 + lane_pos];
+  }
+  for (int64_t e = e0; e < e1; e += outer) {
+    int32_t idx_n = -1;
+    float w_n = 0.0f;
+    if (e + outer + lane_pos < e1) {
+      idx_n = colidx[e + outer + lane_pos];
+      if (Acc::kWeighted) w_n = edge_w[e + outer + lane_pos];
+    }
+    tile[lane] = idx_c;
+    if (Acc::kWeighted) tile[kWave + lane] = __float_as_int(w_c);
+    stage_sync();
+    const int64_t first = e + (ng << 3);
+    if (first < e1) staged_batch<0>(acc, slot_tile);
+    if constexpr (G >= 16) {
+      if (first + ((int64_t)1 << shift) < e1) staged_batch<1>(acc, slot_tile);
+    }
+    if constexpr (G >= 32) {
+      if (first + ((int64_t)2 << shift) < e1) staged_batch<2>(acc, slot_tile);
+      if (first + ((int64_t)3 << shift) < e1) staged_batch<3>(acc, slot_tile);
+    }
+    stage_sync();  // the tile is rewritten only after every lane of the slot has read it
+    idx_c = idx_n;
+    w_c = w_n;
+  }
+}
+
 // Slot = 1, 2 or 4 lanes (slices of at most 16 fp32 / 32 bf16 columns).  Every lane reads the next
 // eight edge indices of its slot itself, as two 16-byte loads (the lanes of a slot read the same
 // addresses, which the memory pipeline merges).  The loads may run past the end of the row into the
@@ -222,11 +294,17 @@ enum { MODE_WAVE = 0, MODE_WIDE = 1, MODE_NARROW = 2 };  // 64 / 8..32 / 1..4 la
 template <int MODE, typename Acc>
 __device__ inline void gather_row(Acc& acc, const int32_t* __restrict__ colidx, const float* __restrict__ edge_w,
                                   int64_t e0, int64_t e1, int ng, int g, int L, bool col_ok, int lane,
-                                  int64_t nnz) {
+                                  int64_t nnz, int32_t* stage = nullptr) {
   const int p_log2 = L - g;  // log2 of the row's neighbour slots
   if constexpr (MODE == MODE_WAVE) {
     gather_wave(acc, colidx, edge_w, e0, e1, ng, p_log2, lane);
   } else if constexpr (MODE == MODE_WIDE) {
+    if (stage) {  // indices through LDS (stage: this wave's tile)
+      if (g == 3) gather_wide_staged<8>(acc, colidx, edge_w, e0, e1, ng, p_log2, lane, stage);
+      else if (g == 4) gather_wide_staged<16>(acc, colidx, edge_w, e0, e1, ng, p_log2, lane, stage);
+      else gather_wide_staged<32>(acc, colidx, edge_w, e0, e1, ng, p_log2, lane, stage);
+      return;
+    }
     if (g == 3) gather_wide<8>(acc, colidx, edge_w, e0, e1, ng, p_log2, lane);
     else if (g == 4) gather_wide<16>(acc, colidx, edge_w, e0, e1, ng, p_log2, lane);
     else gather_wide<32>(acc, colidx, edge_w, e0, e1, ng, p_log2, lane);

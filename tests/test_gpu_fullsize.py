@@ -58,8 +58,18 @@ def test_config4_full_size_gcn_and_mean():
     assert g.gnnagg_auto_f_chunk(N, 602, g.F32, int(Xp.stride(0)), plan) == 32
     assert g.gnnagg_auto_f_chunk(N, 602, g.F32, 602, plan) == 602
     outp = g.pitched_empty(N, 602, torch.float32)
+    # the blocked call as the benchmark's headline runs it: as many source blocks as the library recommends
+    B = g.gnnagg_auto_source_blocks(N, 602, g.F32, int(Xp.stride(0)), plan)
+    assert B == 4 and g.gnnagg_auto_source_blocks(N, 602, g.F32, 602, plan) == 1
+    blocks = g.gnnagg_plan_source_blocks(d_rp, d_ci, B)
+    ws = torch.empty(g.gnnagg_aggregate_blocked_workspace_bytes(N, 602, blocks), dtype=torch.uint8, device="cuda")
     ref = oracle.aggregate(oracle.WSUM, rp, ci, w, X, threads=16)
     say("c4 full: checker weighted sum done (all rows)")
+    for fc in (g.F_CHUNK_AUTO, 32, 0):
+        say("c4 full: wsum over", B, "source blocks, f_chunk", fc)
+        outp.fill_(float("nan"))
+        g.gnnagg_aggregate_blocked(g.WSUM, d_rp, d_ci, d_w, Xp, blocks, outp, fc, workspace=ws)
+        close_all(host(outp), ref, what="c4 wsum blocked fc=%d" % fc)
     for fc in (8, 16, 32, 64, 0, g.F_CHUNK_AUTO):
         say("c4 full: wsum, rows on lines, f_chunk", fc)
         outp.fill_(float("nan"))
@@ -76,13 +86,21 @@ def test_config4_full_size_gcn_and_mean():
         outp.fill_(float("nan"))
         g.gnnagg_aggregate(g.MEAN, d_rp, d_ci, None, Xp, outp, fc, plan)
         close_all(host(outp), ref, what="c4 mean pitched fc=%d" % fc)
+    say("c4 full: mean over", B, "source blocks")
+    outp.fill_(float("nan"))
+    g.gnnagg_aggregate_blocked(g.MEAN, d_rp, d_ci, None, Xp, blocks, outp, g.F_CHUNK_AUTO, workspace=ws)
+    close_all(host(outp), ref, what="c4 mean blocked")
     ref = oracle.aggregate(oracle.MAX, rp, ci, None, X, threads=16)
     for fc in (32, 0, g.F_CHUNK_AUTO):
         say("c4 full: max, rows on lines, f_chunk", fc)
         outp.fill_(float("nan"))
         g.gnnagg_aggregate(g.MAX, d_rp, d_ci, None, Xp, outp, fc, plan)
         assert_bits(host(outp), ref, "c4 max pitched fc=%d" % fc)
-    del Xp, outp, ref
+    say("c4 full: max over", B, "source blocks")
+    outp.fill_(float("nan"))
+    g.gnnagg_aggregate_blocked(g.MAX, d_rp, d_ci, None, Xp, blocks, outp, g.F_CHUNK_AUTO, workspace=ws)
+    assert_bits(host(outp), ref, "c4 max blocked")
+    del Xp, outp, ref, blocks, ws
     # property that holds at any size: the all-ones matrix aggregates to the row degree, exactly
     ones = torch.ones((N, 8), dtype=torch.float32, device="cuda")
     deg = host(g.gnnagg_aggregate(g.SUM, d_rp, d_ci, None, ones, None, 0, plan))
@@ -146,6 +164,31 @@ def test_dense_small_graph_hidden_widths(F):
             assert_bits(host(out), ref, "c6 max F=%d" % F)
         else:
             close_all(host(out), ref, what="c6 %s F=%d fc=%d" % (name, F, fc))
+
+
+def test_dense_small_graph_at_input_width_over_source_blocks():
+    """The third graph shape at the dense graph's input width (602 fp32 columns), plain and over the source blocks
+    the library recommends - the shape blocks gain most on; every row of both against the checker."""
+    import paper_2104_03058_amd as g
+    N, src, dst = W.graph("c6")
+    flags = oracle.SELF_LOOPS | oracle.NORM_SYM
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, flags, want_w=True, threads=16)
+    d_rp, d_ci, d_w, _ = g.gnnagg_build_csr(N, dev(src), dev(dst), flags, want_w=True)
+    X = W.normal_f32((N, 602), seed=46)
+    Xp = g.pitched_empty(N, 602, torch.float32)
+    Xp.copy_(dev(X))
+    plan = g.gnnagg_plan_rows(d_rp)
+    B = g.gnnagg_auto_source_blocks(N, 602, g.F32, int(Xp.stride(0)), plan)
+    assert B == 4
+    blocks = g.gnnagg_plan_source_blocks(d_rp, d_ci, B)
+    ref = oracle.aggregate(oracle.WSUM, rp, ci, w, X, threads=16)
+    say("c6 F=602: plain")
+    out = g.gnnagg_aggregate(g.WSUM, d_rp, d_ci, d_w, Xp, g.pitched_empty(N, 602, torch.float32), g.F_CHUNK_AUTO, plan)
+    close_all(host(out), ref, what="c6 wsum F=602 plain")
+    say("c6 F=602: over", B, "source blocks")
+    out.fill_(float("nan"))
+    g.gnnagg_aggregate_blocked(g.WSUM, d_rp, d_ci, d_w, Xp, blocks, out, g.F_CHUNK_AUTO)
+    close_all(host(out), ref, what="c6 wsum F=602 blocked")
 
 
 def test_config4_graph_attention_full_size():

@@ -127,13 +127,17 @@ GAT_SOURCES = ["gat.hip", "gather.hpp", "schedule.hpp", "device_utils.hpp", "com
 
 
 def kernel_source_hash(files):
-    """Fingerprint of the HIP sources a kernel is built from: a traffic figure in profiles/ counts for a run
-    only if it was taken with the same kernel."""
+    """Fingerprint of the HIP sources a kernel is built from, comments and blank lines aside: a traffic figure in
+    profiles/ counts for a run only if it was taken with the same code."""
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2104_03058_amd", "csrc")
     for fn in sorted(files):
         h.update(fn.encode())
-        h.update(open(os.path.join(d, fn), "rb").read())
+        for line in open(os.path.join(d, fn), errors="replace"):
+            code = line.split("//", 1)[0].rstrip()  # the sources hold no "//" inside string literals
+            if code.strip():
+                h.update(code.encode())
+                h.update(b"\n")
     return h.hexdigest()[:16]
 
 

@@ -31,7 +31,7 @@ enum { OPK_SUM = 0, OPK_WSUM = 1, OPK_MAX = 2 };
 
 // Wide slices hand the edge indices round with swizzles.  The alternative through LDS tiles
 // (gather_wide_staged) is kept for comparison, behind a definition at build time: it measured level to
-// 3.5 % slower on the benchmark shapes.
+// 4 % slower on the benchmark shapes.
 #ifndef GNNAGG_STAGE_INDICES
 #define GNNAGG_STAGE_INDICES 0
 #endif
@@ -53,9 +53,10 @@ struct AggArgs {
   uint32_t lds_per_workgroup;  // host only: LDS each workgroup should occupy (0 = no cap)
   double* ws;                  // partial results of split rows: [slot][F] (null: no row is split)
   // One source block of a blocked call (all null: the whole edge list of every row).  The call walks
-  // edges [e_begin[r], e_end[r]) of row r only; `pin` [N,F] holds the state the earlier blocks left (sums
-  // as doubles, max as its integer key in a double), `pout` [N,F] receives this block's instead of a
-  // finished row.  The degree that finishes a row (mean, empty-row rule of max) stays rowptr's.
+  // edges [e_begin[r], e_end[r]) of row r only; `pin` (N rows of p_pitch doubles) holds the state the
+  // earlier blocks left (sums as doubles, max as its integer key in a double), `pout` receives this
+  // block's instead of a finished row.  The degree that finishes a row (mean, empty-row rule of max)
+  // stays rowptr's.
   const int64_t* e_begin;
   const int64_t* e_end;
   const double* pin;

@@ -319,8 +319,8 @@ inline void degree_profile(const int64_t* class_off, int64_t N, int64_t hot_rows
 //      lines), mean degree >= 16 and hubs that matter (the 32,768 longest rows take >= 40 % of the edges):
 //      row pieces of one or a few LINES.  A pass then gathers from a column slice of N x piece bytes in
 //      which the hubs' lines stay in L2.
-//        - fp32: one line per piece (10-35 % faster than one chunk at 45,000-1,500,000 rows; two-line
-//          pieces are within 7 % of it where they win and up to 23 % behind where they lose);
+//        - fp32: one line per piece (10-40 % faster than one chunk at 45,000-1,500,000 rows; two-line
+//          pieces are up to 10 % ahead of it where they win and up to 23 % behind where they lose);
 //        - short rows: every pass pays a chain of dependent loads per row (plan, row pointer, indices) that
 //          few edges do not amortise - at mean degree 50 and 45-64 passes two- to four-line pieces are
 //          3-12 % faster than one-line ones - so at least ~75 / (mean degree) lines (a power of two), but

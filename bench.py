@@ -752,6 +752,28 @@ HELD_OUT_4 = [
     (260_000, 52_000_000, 1.8, 1100.0, 384, "f32", "wsum"),
     (330_000, 8_250_000, 1.7, 1500.0, 640, "bf16", "mean"),
 ]
+# A fifth set, dense shapes around the thresholds of the source-block rule (mean degree 150-600, 100,000-500,000
+# rows and a few just outside), drawn after that rule was frozen: never used to adjust it.
+HELD_OUT_5 = [
+    (110_000, 13_750_000, 1.9, 500.0, 512, "f32", "wsum"),    # degree 250, just above the row threshold
+    (95_000, 14_250_000, 1.8, 450.0, 768, "f32", "mean"),     # degree 300, just below it
+    (400_000, 36_000_000, 2.0, 1500.0, 256, "f32", "wsum"),   # degree 180, below the degree threshold
+    (300_000, 33_000_000, 1.7, 1300.0, 320, "f32", "max"),    # degree 220
+    (150_000, 45_000_000, 2.1, 600.0, 448, "f32", "mean"),    # degree 600
+    (220_000, 38_500_000, 1.8, 900.0, 1024, "f32", "wsum"),   # degree 350, wide rows
+    (480_000, 60_000_000, 1.9, 1800.0, 128, "f32", "wsum"),   # degree 250, the narrowest rows the rule blocks
+    (180_000, 40_500_000, 1.8, 800.0, 640, "bf16", "sum"),    # degree 450, bf16: never blocked
+]
+# A sixth set of dense fp32 shapes, drawn after the number of blocks became a function of how the edges are
+# spread over the rows (set 5 led to that change): never used to adjust the source-block rule.
+HELD_OUT_6 = [
+    (130_000, 22_750_000, 2.3, 500.0, 384, "f32", "wsum"),    # degree 350, steep law: edges spread out
+    (170_000, 21_250_000, 1.6, 900.0, 512, "f32", "mean"),    # degree 250, heavy tail
+    (350_000, 52_500_000, 1.8, 1400.0, 192, "f32", "wsum"),   # degree 300
+    (125_000, 31_250_000, 2.0, 300.0, 640, "f32", "max"),     # degree 500, capped hubs
+    (240_000, 26_400_000, 2.0, 1000.0, 256, "f32", "mean"),   # degree 220
+    (105_000, 26_250_000, 1.7, 450.0, 1024, "f32", "wsum"),   # degree 500, just above the row threshold
+]
 # the benchmark graphs the rules were first derived on, for the same table (not held out)
 TUNING_SHAPES = [
     (232_965, 57_307_946, 1.8, 680.0, 602, "f32", "wsum"),
@@ -765,9 +787,10 @@ def validate_auto(g, W, torch, steps, warmup, which):
     """Times every held-out shape at chunk widths {32, 64, 128, one chunk} and, at the library's width, at
     resident-workgroup caps {none, 2, 3, 4}, and reports how far the library's own choice is from the best."""
     rows = []
-    shapes = {"1": HELD_OUT, "2": HELD_OUT_2, "3": HELD_OUT_3, "4": HELD_OUT_4, "tuning": TUNING_SHAPES}[which]
+    shapes = {"1": HELD_OUT, "2": HELD_OUT_2, "3": HELD_OUT_3, "4": HELD_OUT_4, "5": HELD_OUT_5, "6": HELD_OUT_6,
+              "tuning": TUNING_SHAPES}[which]
     for k, (N, M, alpha, R, F, xdt, opname) in enumerate(shapes):
-        src, dst = W.powerlaw_graph(N, M, alpha, R, {"1": 100, "2": 300, "3": 500, "4": 700, "tuning": 110}[which] + k)
+        src, dst = W.powerlaw_graph(N, M, alpha, R, {"1": 100, "2": 300, "3": 500, "4": 700, "5": 900, "6": 1100, "tuning": 110}[which] + k)
         gcn = opname == "wsum"
         flags = (g.SELF_LOOPS | g.NORM_SYM) if gcn else 0
         rp, ci, w, _ = g.gnnagg_build_csr(N, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda(), flags, want_w=gcn)
@@ -914,7 +937,7 @@ def main():
                     help="'default': the CPU checker in Algorithm 1's chunk-outer order at the sweep widths of the "
                          "two benchmark configurations that name one (about half a minute); 'none'; or a comma list "
                          "of widths for the main workload")
-    ap.add_argument("--validate-auto", default="", choices=["", "1", "2", "3", "4", "tuning"],
+    ap.add_argument("--validate-auto", default="", choices=["", "1", "2", "3", "4", "5", "6", "tuning"],
                     help="instead of the benchmark: time a set of graph shapes (1-3: used to revise the rule; 4: never "
                          "used for it; tuning: the benchmark graphs) at several chunk widths and resident-workgroup caps and print the regret of the "
                          "library's automatic choices")

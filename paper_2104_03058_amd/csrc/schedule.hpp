@@ -372,16 +372,20 @@ inline int32_t auto_f_chunk(int64_t N, int32_t F, int elem_bytes, bool rows_on_l
 // with the states in transit: 16 bytes per output element and block boundary, written and read back.  The
 // gathers outweigh that only when a row has many edges: on power-law graphs of 50,000-1,500,000 rows
 // (bench.py --validate-auto times 2, 4 and 8 blocks at pieces of 1, 2 and 4 lines next to the plain call)
-// fp32 shapes of mean degree 200-600 and at least 100,000 rows run 4-19 % faster with 4 blocks and two-line
-// pieces than the plain call at its best width; at mean degree 150 and below, on smaller graphs and with
-// bf16 rows (whose plain passes are not bound by L2 misses) the plain call wins, by 5-70 %.  2 to 6 blocks
-// are within a few per cent of each other; 8 and more lose to the traffic of the states.  Returns 1 for
-// "do not block".
+// fp32 shapes of mean degree 200-600 and at least 100,000 rows run 3-23 % faster blocked, with two-line
+// pieces, than the plain call at its best width; at mean degree 150 and below, on smaller graphs and with
+// bf16 rows (whose plain passes are not bound by L2 misses) the plain call wins, by 5-70 %.
+// How many: the plain call already keeps the hubs' lines in L2, so what blocks add depends on how much of
+// the graph is NOT hubs.  Where the longest tenth of the rows holds under 60 % of the edges (flat degree
+// distributions: the third benchmark graph shape, exponents above 2) 4 blocks beat 2 by 7-30 %; where it
+// holds over 70 % 2 blocks beat 4 by 6-10 %; in between they are level.  8 and more lose to the traffic of
+// the states everywhere.  Returns 1 for "do not block".
 inline int32_t auto_source_blocks(int64_t N, int64_t F, int elem_bytes, bool rows_on_lines, const int64_t* class_off) {
   if (!class_off || !rows_on_lines || elem_bytes != 4 || F < 128 || N < 100000) return 1;
-  double mean_degree, hot_share;
-  degree_profile(class_off, N, 32768, &mean_degree, &hot_share);
-  return mean_degree >= 200.0 ? 4 : 1;
+  double mean_degree, top_tenth_share;
+  degree_profile(class_off, N, N / 10, &mean_degree, &top_tenth_share);
+  if (mean_degree < 200.0) return 1;
+  return top_tenth_share < 0.6 ? 4 : 2;
 }
 
 // How many workgroups of the aggregation kernel should share a compute unit.  Every resident wave

@@ -255,17 +255,20 @@ def test_source_block_entry_points_validate_on_the_host(lib):
 
 
 def test_source_block_rule(lib):
-    """Blocks pay on dense fp32 graphs of at least 100,000 rows whose rows start on lines; nowhere else."""
+    """Blocks pay on dense fp32 graphs of at least 100,000 rows whose rows start on lines; nowhere else.  Four
+    where the edges are spread over the rows, two where the longest tenth of the rows holds most of them."""
     import paper_2104_03058_amd as g
     N = 232965
-    dense = plan_of(N, {15: 60, 14: 700, 13: 4000, 12: 12000, 11: 25000, 10: 40000, 9: 50000, 8: 45000, 7: 30000,
-                        6: 15000, 5: 8000})                  # mean degree ~ 500
+    hubs = plan_of(N, {16: 30, 15: 300, 14: 2000, 13: 6000, 12: 10000, 10: 30000, 8: 60000,
+                       6: 80000})                            # mean degree ~ 600, the top tenth holds ~ 3/4
+    flat = plan_of(N, {11: 20000, 10: 80000, 9: 100000, 8: 32965})                      # ~ 600, top tenth ~ 1/5
     medium = plan_of(N, {11: 3000, 9: 20000, 8: 60000, 7: 80000, 6: 50000, 5: 19965})   # mean degree ~ 130
-    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 608, dense) == 4
-    assert g.gnnagg_auto_source_blocks(N, 128, g.F32, 128, dense) == 4
-    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 602, dense) == 1     # rows not on lines
-    assert g.gnnagg_auto_source_blocks(N, 64, g.F32, 64, dense) == 1       # narrow rows: one pass per block is short
-    assert g.gnnagg_auto_source_blocks(N, 512, g.BF16, 512, dense) == 1    # bf16
+    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 608, hubs) == 2
+    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 608, flat) == 4
+    assert g.gnnagg_auto_source_blocks(N, 128, g.F32, 128, flat) == 4
+    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 602, flat) == 1      # rows not on lines
+    assert g.gnnagg_auto_source_blocks(N, 64, g.F32, 64, flat) == 1        # narrow rows: one pass per block is short
+    assert g.gnnagg_auto_source_blocks(N, 512, g.BF16, 512, flat) == 1     # bf16
     assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 608, medium) == 1    # too few edges per row
     assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 608, None) == 1      # no plan
     small = plan_of(60000, {12: 2000, 10: 20000, 9: 38000})

@@ -127,13 +127,16 @@ GAT_SOURCES = ["gat.hip", "gather.hpp", "schedule.hpp", "device_utils.hpp", "com
 
 
 def kernel_source_hash(files):
-    """Fingerprint of the HIP sources a kernel is built from, comments and blank lines aside: a traffic figure in
-    profiles/ counts for a run only if it was taken with the same code."""
+    """Fingerprint of the device code and the launch schedule a kernel is built from: the listed sources up to
+    the line `using namespace gnnagg;` (below it a .hip file holds the host-side entry points), comments and blank
+    lines aside.  A traffic figure in profiles/ counts for a run only if it was taken with the same code."""
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2104_03058_amd", "csrc")
     for fn in sorted(files):
         h.update(fn.encode())
         for line in open(os.path.join(d, fn), errors="replace"):
+            if line.startswith("using namespace gnnagg;"):
+                break
             code = line.split("//", 1)[0].rstrip()  # the sources hold no "//" inside string literals
             if code.strip():
                 h.update(code.encode())
@@ -830,7 +833,7 @@ def validate_auto(g, W, torch, steps, warmup, which):
         g.gnnagg_set_workgroup_cap(-1)
         best = min(list(widths.values()) + list(caps.values()) + [t_auto])
         # the same over source blocks (not part of `best`: the regret above is that of the chunk-width rule)
-        blocked = {}
+        blocked, tuned_blocked = {}, {}
         line = 64 if xdt == "bf16" else 32
         for B in (2, 4, 8):
             blocks = g.gnnagg_plan_source_blocks(rp, ci, B)
@@ -848,25 +851,34 @@ def validate_auto(g, W, torch, steps, warmup, which):
                 e1.record()
                 torch.cuda.synchronize()
                 blocked["%d@%d" % (B, fc)] = e0.elapsed_time(e1) / steps
+            if B <= 4:  # the measuring tuner of the blocked call, for the same tables
+                tuned_blocked[B] = g.gnnagg_tune_blocked(op, rp, ci, w, d_X, out, blocks, workspace=ws)
             del blocks, ws
         # what a caller following the library's two rules gets: blocks where gnnagg_auto_source_blocks says so
         # (at the blocked call's own width), else the plain call at GNNAGG_F_CHUNK_AUTO
         B_auto = g.gnnagg_auto_source_blocks(N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)), plan)
         t_rules = blocked["%d@%d" % (B_auto, 2 * line if xdt != "bf16" else 2 * line)] if B_auto > 1 else t_auto
         best_any = min([best] + list(blocked.values()))
+        # all by measurement: the fastest of the two tuners' answers (plain, 2 blocks, 4 blocks), timed like the rest
+        pick = min([(tuned_ms, 0, tuned)] + [(ms, B, fc) for B, (fc, ms) in tuned_blocked.items()])
+        t_measured = t_tuned if pick[1] == 0 else blocked.get("%d@%d" % (pick[1], pick[2]), pick[0])
         deg = float(len(src)) / N
         row = {"set": which, "class_off": plan.class_offsets(), "N": N, "mean_degree": deg, "max_degree": int((rp[1:] - rp[:-1]).max()), "exponent": alpha, "F": F,
                "x_dtype": xdt, "op": opname, "auto_f_chunk": int(f_auto), "auto_ms": t_auto, "by_width_ms": widths,
                "by_cap_ms_at_auto_width": caps, "best_ms": best, "regret": t_auto / best - 1.0,
                "tuned_f_chunk": tuned, "tuned_ms": t_tuned, "tuned_regret": t_tuned / best - 1.0,
                "blocked_ms": blocked, "auto_source_blocks": int(B_auto), "rules_ms": t_rules,
-               "best_ms_with_blocks": best_any, "rules_regret": t_rules / best_any - 1.0}
+               "best_ms_with_blocks": best_any, "rules_regret": t_rules / best_any - 1.0,
+               "measured_choice": {"source_blocks": pick[1], "f_chunk": pick[2]}, "measured_ms": t_measured,
+               "measured_regret": t_measured / best_any - 1.0}
         log("held-out %d: N=%d deg %.0f a=%.1f F=%d %s %s: auto(width %d) %.3f ms, widths %s, caps %s, regret %.1f %%" %
             (k, N, deg, alpha, F, xdt, opname, f_auto, t_auto, {a: round(b, 3) for a, b in widths.items()},
              {a: round(b, 3) for a, b in caps.items()}, 100 * row["regret"]) +
             "; measured tuner picks %d (%.3f ms, regret %.1f %%)" % (tuned, t_tuned, 100 * row["tuned_regret"]) +
             "; source blocks %s; rule: %d blocks, %.3f ms, regret against everything tried %.1f %%" %
-            ({a: round(b, 3) for a, b in blocked.items()}, B_auto, t_rules, 100 * row["rules_regret"]))
+            ({a: round(b, 3) for a, b in blocked.items()}, B_auto, t_rules, 100 * row["rules_regret"]) +
+            "; both tuners pick %d blocks at width %d: %.3f ms, regret %.1f %%" %
+            (pick[1], pick[2], t_measured, 100 * row["measured_regret"]))
         rows.append(row)
         del d_X, out, rp, ci, w, plan
         torch.cuda.empty_cache()

@@ -23,8 +23,8 @@
  *    gnnagg_combine and gnnagg_rank_sources only enqueue kernels on it and return (no allocation
  *    on the host or the device, no synchronisation, no memset: they can be
  *    captured in a HIP graph); gnnagg_build_csr, gnnagg_check_csr,
- *    gnnagg_plan_rows, gnnagg_plan_source_blocks and gnnagg_tune_f_chunk also
- *    wait for it, because they hand results back to the host.
+ *    gnnagg_plan_rows, gnnagg_plan_source_blocks, gnnagg_tune_f_chunk and
+ *    gnnagg_tune_blocked also wait for it, because they hand results back to the host.
  *  - Every call returns a gnnagg_status.  Invalid arguments are detected on the
  *    host before anything is launched and leave all outputs untouched.  Index
  *    values outside [0, N) inside colidx are a contract violation that the
@@ -312,6 +312,20 @@ GNNAGG_API int gnnagg_aggregate_blocked(int op, int64_t N, const int64_t* rowptr
                              int out_dtype, int64_t out_pitch, int32_t F, int32_t f_chunk, int32_t B,
                              const int64_t* block_ptr, const int32_t* row_order, const int64_t* class_off,
                              void* workspace, size_t* workspace_bytes, void* stream);
+
+/*
+ * gnnagg_tune_f_chunk for the blocked call: times gnnagg_aggregate_blocked on the caller's own arrays, with
+ * the tables of B blocks, at its own chunk width and at row pieces of 1, 2 and 4 cache lines (a warm-up and
+ * three timed calls each) and returns the fastest width in *best_f_chunk and its time per call in *best_ms
+ * (may be NULL).  Comparing *best_ms over a few block counts, and with gnnagg_tune_f_chunk's for the plain
+ * call, settles by measurement what gnnagg_auto_source_blocks settles by rule.  Same arguments and workspace
+ * protocol as gnnagg_aggregate_blocked; `out` holds a valid aggregation afterwards; waits for `stream`.
+ */
+GNNAGG_API int gnnagg_tune_blocked(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                        const float* edge_w, const void* X, int x_dtype, int64_t x_pitch, void* out, int out_dtype,
+                        int64_t out_pitch, int32_t F, int32_t B, const int64_t* block_ptr,
+                        const int32_t* row_order, const int64_t* class_off, void* workspace,
+                        size_t* workspace_bytes, void* stream, int32_t* best_f_chunk, float* best_ms);
 
 /* Number of source blocks worth using for a graph with the row plan class_off (HOST pointer, the plan of
  * gnnagg_plan_rows; NULL: 1) and an X of row pitch x_pitch (0 = F) whose first row starts on a 128-byte

@@ -70,6 +70,9 @@ def load_library():
         lib.gnnagg_aggregate_blocked.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, vp, ci, i64, i32, i32, i32, vp, vp,
                                                  vp, vp, szp, vp]
         lib.gnnagg_aggregate_blocked.restype = ci
+        lib.gnnagg_tune_blocked.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, vp, ci, i64, i32, i32, vp, vp, vp, vp, szp,
+                                            vp, vp, vp]
+        lib.gnnagg_tune_blocked.restype = ci
         lib.gnnagg_auto_source_blocks.argtypes = [i64, i32, ci, i64, vp]
         lib.gnnagg_auto_source_blocks.restype = i32
         lib.gnnagg_row_pitch.argtypes = [i32, ci]
@@ -525,6 +528,29 @@ def gnnagg_tune_f_chunk(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edg
                                  order, class_off, _dev(ws), ctypes.byref(have), _stream(stream), ctypes.byref(best),
                                  ctypes.byref(ms))
     _check("gnnagg_tune_f_chunk", rc)
+    return int(best.value), float(ms.value)
+
+
+def gnnagg_tune_blocked(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w: Optional[torch.Tensor],
+                        X: torch.Tensor, out: torch.Tensor, blocks: "SourceBlocks", stream=None,
+                        workspace: Optional[torch.Tensor] = None):
+    """(best chunk width, its milliseconds per call) of the blocked call with these block tables, by measurement."""
+    lib = load_library()
+    N, F = int(X.shape[0]), int(X.shape[1])
+    if workspace is None:
+        need = gnnagg_aggregate_blocked_workspace_bytes(N, F, blocks)
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device) if need > 0 else _token(X.device)
+    have = ctypes.c_size_t(workspace.numel())
+    best, ms = ctypes.c_int32(0), ctypes.c_float(0.0)
+    rc = lib.gnnagg_tune_blocked(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
+                                 _dev(edge_w, torch.float32, "edge_w"), _rows(X, "X"), _x_dtype(X),
+                                 int(X.stride(0)) if N > 1 else F, _rows(out, "out"),
+                                 F32 if out.dtype == torch.float32 else BF16, int(out.stride(0)) if N > 1 else F, F,
+                                 blocks.B, _dev(blocks.block_ptr, torch.int64, "block_ptr"),
+                                 _dev(blocks.row_order, torch.int32, "row_order"),
+                                 ctypes.cast(blocks.class_off, ctypes.c_void_p), _dev(workspace), ctypes.byref(have),
+                                 _stream(stream), ctypes.byref(best), ctypes.byref(ms))
+    _check("gnnagg_tune_blocked", rc)
     return int(best.value), float(ms.value)
 
 

@@ -764,12 +764,54 @@ extern "C" int gnnagg_aggregate_noalloc(int op, int64_t N, const int64_t* rowptr
                         row_order, class_off, static_cast<double*>(ws), Update(), (hipStream_t)stream_);
 }
 
-extern "C" int gnnagg_aggregate_blocked(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
-                                        const float* edge_w, const void* X, int x_dtype, int64_t x_pitch,
-                                        void* out, int out_dtype, int64_t out_pitch, int32_t F, int32_t f_chunk,
-                                        int32_t B, const int64_t* block_ptr, const int32_t* row_order,
-                                        const int64_t* class_off, void* workspace, size_t* workspace_bytes,
-                                        void* stream_) {
+namespace {
+
+// gnnagg_aggregate_blocked after its argument checks: f_chunk resolved, workspace carved.
+struct BlockedCall {
+  int op;
+  int64_t N;
+  const int64_t* rowptr;
+  const int32_t* colidx;
+  const float* edge_w;
+  const void* X;
+  int x_dtype;
+  int64_t x_pitch;
+  void* out;
+  int out_dtype;
+  int64_t out_pitch;
+  int32_t F, B;
+  const int64_t* block_ptr;
+  const int32_t* row_order;
+  const int64_t* class_off;
+  double* state[2];
+  double* ws;
+  int64_t p_pitch;
+};
+
+int run_blocked(const BlockedCall& c, int32_t f_chunk, hipStream_t stream) {
+  constexpr int kOffs = GNNAGG_PLAN_CLASSES + 1;
+  for (int32_t b = 0; b < c.B; ++b) {
+    Block blk;
+    blk.e_begin = c.block_ptr + (int64_t)b * c.N;
+    blk.e_end = c.block_ptr + (int64_t)(b + 1) * c.N;
+    blk.pin = b > 0 ? c.state[(b - 1) & 1] : nullptr;
+    blk.pout = b + 1 < c.B ? c.state[b & 1] : nullptr;
+    blk.p_pitch = c.p_pitch;
+    int rc = aggregate_impl(c.op, c.N, c.rowptr, c.colidx, c.edge_w, c.X, c.x_dtype, c.x_pitch, c.out, c.out_dtype,
+                            c.out_pitch, c.F, f_chunk, c.row_order + (int64_t)b * c.N,
+                            c.class_off + (size_t)b * kOffs, c.ws, Update(), stream, blk);
+    if (rc != GNNAGG_OK) return rc;
+  }
+  return GNNAGG_OK;
+}
+
+// Checks and workspace protocol shared by gnnagg_aggregate_blocked and gnnagg_tune_blocked.  GNNAGG_OK with
+// *done = true: the call is complete (size query answered, or nothing to do).
+int prepare_blocked(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* edge_w,
+                    const void* X, int x_dtype, int64_t x_pitch, void* out, int out_dtype, int64_t out_pitch,
+                    int32_t F, int32_t f_chunk, int32_t B, const int64_t* block_ptr, const int32_t* row_order,
+                    const int64_t* class_off, void* workspace, size_t* workspace_bytes, BlockedCall* c, bool* done) {
+  *done = false;
   if (!workspace_bytes) return GNNAGG_ENULL;
   if (B < 1 || B > GNNAGG_MAX_SOURCE_BLOCKS) return GNNAGG_EINVAL;
   if (!class_off || !row_order || (N > 0 && !block_ptr)) return GNNAGG_ENULL;
@@ -787,35 +829,111 @@ extern "C" int gnnagg_aggregate_blocked(int op, int64_t N, const int64_t* rowptr
   const size_t need = (size_t)n_state * state_bytes + need_split;
   if (!workspace) {
     *workspace_bytes = need;
+    *done = true;
     return GNNAGG_OK;
   }
   if (*workspace_bytes < need || ((uintptr_t)workspace & 255u)) return GNNAGG_EWORKSPACE;
   bool nothing;
   int rc = check_aggregate_args(op, N, rowptr, colidx, edge_w, X, x_dtype, out, out_dtype, F, f_chunk, row_order,
                                 class_off, &nothing);
-  if (rc != GNNAGG_OK || nothing) return rc;
+  if (rc != GNNAGG_OK) return rc;
+  if (nothing) {
+    *done = true;
+    return GNNAGG_OK;
+  }
   if ((uintptr_t)block_ptr % 8) return GNNAGG_EINVAL;
-  if (f_chunk == GNNAGG_F_CHUNK_AUTO) {
-    const int64_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
-    const bool rows_on_lines = ((uintptr_t)X % 128) == 0 && ((uint64_t)x_pitch * (uint64_t)xs) % 128 == 0;
-    const int32_t piece = (x_dtype == GNNAGG_F32) ? 64 : 128;  // two lines per piece
-    f_chunk = (rows_on_lines && F >= 2 * piece) ? piece : 0;
-  }
   char* base = static_cast<char*>(workspace);
-  double* state[2] = {reinterpret_cast<double*>(base), reinterpret_cast<double*>(base + state_bytes)};
-  double* ws = need_split > 0 ? reinterpret_cast<double*>(base + (size_t)n_state * state_bytes) : nullptr;
-  for (int32_t b = 0; b < B; ++b) {
-    Block blk;
-    blk.e_begin = block_ptr + (int64_t)b * N;
-    blk.e_end = block_ptr + (int64_t)(b + 1) * N;
-    blk.pin = b > 0 ? state[(b - 1) & 1] : nullptr;
-    blk.pout = b + 1 < B ? state[b & 1] : nullptr;
-    blk.p_pitch = p_pitch;
-    rc = aggregate_impl(op, N, rowptr, colidx, edge_w, X, x_dtype, x_pitch, out, out_dtype, out_pitch, F, f_chunk,
-                        row_order + (int64_t)b * N, class_off + (size_t)b * kOffs, ws, Update(), (hipStream_t)stream_,
-                        blk);
-    if (rc != GNNAGG_OK) return rc;
+  *c = BlockedCall{op, N, rowptr, colidx, edge_w, X, x_dtype, x_pitch, out, out_dtype, out_pitch, F, B, block_ptr,
+                   row_order, class_off,
+                   {reinterpret_cast<double*>(base), reinterpret_cast<double*>(base + state_bytes)},
+                   need_split > 0 ? reinterpret_cast<double*>(base + (size_t)n_state * state_bytes) : nullptr, p_pitch};
+  return GNNAGG_OK;
+}
+
+// Row pieces of two lines when the rows of X start on lines and are at least two pieces long, else one chunk.
+int32_t blocked_auto_f_chunk(const void* X, int x_dtype, int64_t x_pitch, int32_t F) {
+  const int64_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
+  const bool rows_on_lines = ((uintptr_t)X % 128) == 0 && ((uint64_t)x_pitch * (uint64_t)xs) % 128 == 0;
+  const int32_t piece = (x_dtype == GNNAGG_F32) ? 64 : 128;
+  return (rows_on_lines && F >= 2 * piece) ? piece : 0;
+}
+
+}  // namespace
+
+extern "C" int gnnagg_aggregate_blocked(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                                        const float* edge_w, const void* X, int x_dtype, int64_t x_pitch,
+                                        void* out, int out_dtype, int64_t out_pitch, int32_t F, int32_t f_chunk,
+                                        int32_t B, const int64_t* block_ptr, const int32_t* row_order,
+                                        const int64_t* class_off, void* workspace, size_t* workspace_bytes,
+                                        void* stream_) {
+  BlockedCall c;
+  bool done;
+  int rc = prepare_blocked(op, N, rowptr, colidx, edge_w, X, x_dtype, x_pitch, out, out_dtype, out_pitch, F, f_chunk,
+                           B, block_ptr, row_order, class_off, workspace, workspace_bytes, &c, &done);
+  if (rc != GNNAGG_OK || done) return rc;
+  if (f_chunk == GNNAGG_F_CHUNK_AUTO) f_chunk = blocked_auto_f_chunk(c.X, c.x_dtype, c.x_pitch, F);
+  return run_blocked(c, f_chunk, (hipStream_t)stream_);
+}
+
+extern "C" int gnnagg_tune_blocked(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx,
+                                   const float* edge_w, const void* X, int x_dtype, int64_t x_pitch, void* out,
+                                   int out_dtype, int64_t out_pitch, int32_t F, int32_t B, const int64_t* block_ptr,
+                                   const int32_t* row_order, const int64_t* class_off, void* workspace,
+                                   size_t* workspace_bytes, void* stream_, int32_t* best_f_chunk, float* best_ms) {
+  BlockedCall c;
+  bool done;
+  int rc = prepare_blocked(op, N, rowptr, colidx, edge_w, X, x_dtype, x_pitch, out, out_dtype, out_pitch, F, 0, B,
+                           block_ptr, row_order, class_off, workspace, workspace_bytes, &c, &done);
+  if (rc != GNNAGG_OK) return rc;
+  if (done && !workspace) return GNNAGG_OK;  // size query
+  if (!best_f_chunk) return GNNAGG_ENULL;
+  if (done) {
+    *best_f_chunk = F;
+    if (best_ms) *best_ms = 0.0f;
+    return GNNAGG_OK;
   }
+  hipStream_t stream = (hipStream_t)stream_;
+  // candidates: the blocked call's own choice and row pieces of 1, 2 and 4 lines
+  const int32_t line_cols = (x_dtype == GNNAGG_F32) ? 32 : 64;
+  int32_t cand[4];
+  int n_cand = 0;
+  auto add = [&](int32_t w) {
+    if (w <= 0 || w >= F) w = F;
+    for (int k = 0; k < n_cand; ++k)
+      if (cand[k] == w) return;
+    cand[n_cand++] = w;
+  };
+  add(blocked_auto_f_chunk(c.X, c.x_dtype, c.x_pitch, F));
+  for (int32_t lines = 1; lines <= 4; lines *= 2) add(lines * line_cols);
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return GNNAGG_EDEVICE;
+  if (hipEventCreate(&e1) != hipSuccess) {
+    (void)hipEventDestroy(e0);
+    return GNNAGG_EDEVICE;
+  }
+  constexpr int kTimedCalls = 3;
+  float best = 0.0f;
+  int32_t best_w = cand[0];
+  for (int k = 0; k < n_cand && rc == GNNAGG_OK; ++k) {
+    float ms = 0.0f;
+    for (int rep = 0; rep <= kTimedCalls && rc == GNNAGG_OK; ++rep) {  // call 0 warms caches and code
+      if (rep == 1 && hipEventRecord(e0, stream) != hipSuccess) rc = GNNAGG_EDEVICE;
+      if (rc == GNNAGG_OK) rc = run_blocked(c, cand[k], stream);
+    }
+    if (rc == GNNAGG_OK && (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                            hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+      rc = GNNAGG_EDEVICE;
+    if (rc == GNNAGG_OK && (k == 0 || ms < best)) {
+      best = ms;
+      best_w = cand[k];
+    }
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc != GNNAGG_OK) return rc;
+  if (hipStreamSynchronize(stream) != hipSuccess) return GNNAGG_EDEVICE;
+  *best_f_chunk = best_w;
+  if (best_ms) *best_ms = best / (float)kTimedCalls;
   return GNNAGG_OK;
 }
 

@@ -196,3 +196,26 @@ def test_plan_source_blocks_rejects_rows_that_are_not_ascending_and_bad_block_co
         with pytest.raises(g.GnnaggError) as e:
             g.gnnagg_plan_source_blocks(dev(rp), dev(ci_ok), B)
         assert e.value.status == -1
+
+
+def test_measured_tuner_of_the_blocked_call_returns_a_valid_width_and_leaves_a_valid_result():
+    N, src, dst = W.graph("c4", 0.02)
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, oracle.SELF_LOOPS | oracle.NORM_SYM, want_w=True)
+    F = 300
+    X = W.normal_f32((N, F), seed=21)
+    d_rp, d_ci, d_w = dev(rp), dev(ci), dev(w)
+    Xp = g.pitched_empty(N, F, torch.float32)
+    Xp.copy_(dev(X))
+    out = g.pitched_empty(N, F, torch.float32)
+    ref = oracle.aggregate(oracle.WSUM, rp, ci, w, X, threads=8)
+    times = {}
+    for B in (1, 2, 4):
+        blocks = g.gnnagg_plan_source_blocks(d_rp, d_ci, B)
+        out.fill_(float("nan"))
+        width, ms = g.gnnagg_tune_blocked(g.WSUM, d_rp, d_ci, d_w, Xp, out, blocks)
+        assert width in (32, 64, 128) and ms > 0.0, (B, width, ms)
+        assert_close(host(out), ref, "after tuning with %d blocks" % B)   # the last timed call left a whole result
+        times[B] = ms
+    plain_width, plain_ms = g.gnnagg_tune_f_chunk(g.WSUM, d_rp, d_ci, d_w, Xp, out, g.gnnagg_plan_rows(d_rp))
+    assert plain_ms > 0.0 and plain_width > 0
+    say("  tuned: plain %.3f ms at %d; blocked %s" % (plain_ms, plain_width, times))

@@ -253,6 +253,20 @@ def test_source_block_entry_points_validate_on_the_host(lib):
     assert call(N=0, X=None, out=None, bp=None, co=ctypes.cast(empty, ctypes.c_void_p)) == 0
     assert call(N=0, X=None, out=None, bp=None) == EINVAL  # a plan for 100 rows
 
+    tune = lib.gnnagg_tune_blocked
+    best, ms = ctypes.c_int32(-1), ctypes.c_float(-1.0)
+
+    def tcall(op=0, N=100, X=one, F=8, B=3, bp=one, co=offp, out=other, ws=one, wsb=big, bestp=ctypes.byref(best)):
+        return tune(op, N, one, one, one, X, 0, 0, out, 0, 0, F, B, bp, one, co, ws,
+                    ctypes.byref(wsb) if wsb is not None else None, None, bestp, ctypes.byref(ms))
+
+    assert tcall(wsb=None) == ENULL
+    assert tcall(B=0) == EINVAL and tcall(co=None) == ENULL and tcall(op=7) == EINVAL
+    assert tcall(ws=None, wsb=need, bestp=None) == 0 and need.value == 2 * 100 * 16 * 8   # size query needs no result slot
+    assert tcall(bestp=None) == ENULL
+    assert tcall(wsb=ctypes.c_size_t(16)) == EWS
+    assert tcall(N=0, X=None, out=None, bp=None, co=ctypes.cast(empty, ctypes.c_void_p)) == 0 and best.value == 8
+
 
 def test_source_block_rule(lib):
     """Blocks pay on dense fp32 graphs of at least 100,000 rows whose rows start on lines; nowhere else.  Four

@@ -219,3 +219,37 @@ def test_measured_tuner_of_the_blocked_call_returns_a_valid_width_and_leaves_a_v
     plain_width, plain_ms = g.gnnagg_tune_f_chunk(g.WSUM, d_rp, d_ci, d_w, Xp, out, g.gnnagg_plan_rows(d_rp))
     assert plain_ms > 0.0 and plain_width > 0
     say("  tuned: plain %.3f ms at %d; blocked %s" % (plain_ms, plain_width, times))
+
+
+def test_blocked_call_can_be_captured_in_a_graph_and_replayed():
+    """The blocked call only enqueues kernels, so it can be captured once and replayed: every replay, with fresh
+    inputs copied in place and eager work in between, gives the bits of the eager call."""
+    N, src, dst = W.graph("c4", 0.01)
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, oracle.SELF_LOOPS | oracle.NORM_SYM, want_w=True)
+    d_rp, d_ci, d_w = dev(rp), dev(ci), dev(w)
+    blocks = g.gnnagg_plan_source_blocks(d_rp, d_ci, 3)
+    F = 160
+    X = torch.zeros((N, F), dtype=torch.float32, device="cuda")
+    out = torch.empty((N, F), dtype=torch.float32, device="cuda")
+    ws = torch.empty(g.gnnagg_aggregate_blocked_workspace_bytes(N, F, blocks), dtype=torch.uint8, device="cuda")
+
+    def call():
+        g.gnnagg_aggregate_blocked(g.WSUM, d_rp, d_ci, d_w, X, blocks, out, 32, workspace=ws)
+
+    call()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for k in range(3):
+        Xh = W.normal_f32((N, F), seed=990 + k)
+        X.copy_(dev(Xh))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.clone()
+        out.zero_()
+        ws.fill_(0x7F)
+        call()
+        torch.cuda.synchronize()
+        assert torch.equal(got, out), "replay %d differs from the eager call" % k
+        assert_close(host(out), oracle.aggregate(oracle.WSUM, rp, ci, w, Xh, threads=8), "captured blocked call %d" % k)

@@ -195,6 +195,7 @@ class Bench:
         self.ceil = {}         # probe name -> dict(rate figures)
         self.copy_gbs = None
         self.mfma_tflops = None
+        self.line_rates = {}   # bare line-gather rates by working set (line_probe)
         self.traffic = measured_traffic()
         self.threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
 
@@ -322,21 +323,24 @@ class Bench:
                 "beyond_l2_gbs": (traffic / t / 1e9) if traffic else None,
                 "kernel_ms": kern_ms, "algorithmic_bytes": b_alg, "measured_copy_gbs": self.copy_gbs,
                 "note": "achieved = algorithmic bytes / time; above peak when L2 serves the gathers"}
+        # ceilings: the bare line gather of this run (the access pattern alone, no index stream, no arithmetic);
+        # the aggregation kernel's own rate on a uniform L2-resident graph is reported next to it
         l2 = None
-        peak_lines = self.ceil.get("probe-l2-line", {}).get("lines_per_s")
+        hw_lines = self.line_rates.get("l2", {}).get("lines_per_s")
+        own_lines = self.ceil.get("probe-l2-line", {}).get("lines_per_s")
         if lines:
             l2 = {"bound": "l2-line-requests", "unit": "G lines/s", "achieved": lines / t / 1e9,
-                  "peak": peak_lines / 1e9 if peak_lines else None,
-                  "frac": (lines / t / peak_lines) if peak_lines else None, "lines_per_call": lines,
-                  "peak_source": "probe-l2-line of this run (one 128-byte line per edge, X resident in L2)"}
+                  "peak": hw_lines / 1e9 if hw_lines else None,
+                  "frac": (lines / t / hw_lines) if hw_lines else None, "lines_per_call": lines,
+                  "peak_source": "bare gather of random 128-byte lines out of 3.7 MB (L2-resident), this run",
+                  "aggregation_kernel_on_an_l2_resident_uniform_graph": own_lines / 1e9 if own_lines else None,
+                  "frac_of_that": (lines / t / own_lines) if own_lines else None}
         fab = None
-        # A probe's own rate across the L2 boundary: counted bytes of its profile over this run's time
-        # (its algorithmic rate where no current profile of the probe is at hand).
-        beyond = [v.get("beyond_l2_gbs") or v["algorithmic_gbs"] for k, v in self.ceil.items() if k != "probe-l2-line"]
-        if traffic and beyond:
+        hw_beyond = [v["gbs"] for k, v in self.line_rates.items() if k != "l2"]
+        if traffic and hw_beyond:
             fab = {"bound": "fabric (beyond L2: Infinity Cache + HBM, not separable in the counters)", "unit": "GB/s",
-                   "achieved": traffic / t / 1e9, "peak": max(beyond), "frac": traffic / t / 1e9 / max(beyond),
-                   "peak_source": "fastest probe of this run beyond L2, in counted bytes across the L2 boundary"}
+                   "achieved": traffic / t / 1e9, "peak": max(hw_beyond), "frac": traffic / t / 1e9 / max(hw_beyond),
+                   "peak_source": "bare gather of random 128-byte lines out of 134 MB / 2 GB, the faster, this run"}
         return roof, l2, fab
 
     # ---- one aggregation workload (sum / wsum / mean / max, plain or ranked)
@@ -902,6 +906,35 @@ def copy_probe(g, torch, n_probe):
     return copy_ms, 2.0 * probe_bytes / (copy_ms * 1e-3) / 1e9, probe_bytes
 
 
+LINE_PROBE_SETS = (("l2", 3_727_360), ("infinity_cache", 134_217_728), ("hbm", 2_147_483_648))
+
+
+def line_probe(g, torch, repeats=3):
+    """The bare access pattern of a one-line gather (gnnagg_line_gather_probe: random 128-byte lines, eight lanes
+    per line, eight loads in flight per lane, no index stream, no arithmetic) out of working sets that live in
+    L2, in the Infinity Cache and in HBM: what the memory system gives the pattern itself."""
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    out = {}
+    for name, nbytes in LINE_PROBE_SETS:
+        buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(3)
+        wgs = 256 * 16
+        rounds = 36  # 3.8e7 lines per launch
+        g.gnnagg_line_gather_probe(buf, rounds, wgs, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        lines = 0
+        for _ in range(repeats):
+            lines += g.gnnagg_line_gather_probe(buf, rounds, wgs, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        out[name] = {"working_set_bytes": nbytes, "lines_per_s": lines / (ms * 1e-3),
+                     "gbs": lines * 128 / (ms * 1e-3) / 1e9, "kernel_ms": ms / repeats}
+        del buf
+    return out
+
+
 def mfma_probe(g, torch):
     """fp64 matrix rate the device sustains: a loop of nothing but the matrix instruction on every SIMD."""
     sink = torch.zeros(1, dtype=torch.float64, device="cuda")
@@ -934,8 +967,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c4-gcn#auto",
-                    help="a workload name (optionally name@width), or 'copy' for the library's plain copy kernel "
-                         "on 1 GiB alone (profiler calibration)")
+                    help="a workload name (optionally name#blocks and/or @width), 'copy' for the library's plain copy "
+                         "kernel on 1 GiB alone (profiler calibration), or 'line-probe' for the bare line gather")
     ap.add_argument("--f-chunk", type=int, default=-1,
                     help="chunk width; -1 = let the library pick (GNNAGG_F_CHUNK_AUTO, the default), 0 = one chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip every CPU-rate leg (parity checks stay)")
@@ -978,12 +1011,21 @@ def main():
                           "ms_per_step": copy_ms, "bytes_read": probe_bytes, "bytes_written": probe_bytes,
                           "config": {"workload": "copy"}}), flush=True)
         return
+    if args.workload == "line-probe":  # the bare line gather alone (profiler runs)
+        rates = line_probe(g, torch, max(args.steps, 3))
+        print(json.dumps({"metric": "bare line gather", "value": rates["l2"]["lines_per_s"], "unit": "lines/s",
+                          "n_gpus": 1, "config": {"workload": "line-probe"}, "rates": rates,
+                          "measured_copy_gbs": copy_gbs}), flush=True)
+        return
     if split_name(args.workload)[0] not in WORKLOADS:
         sys.exit("unknown workload %s (known: %s)" % (args.workload, ", ".join(sorted(WORKLOADS))))
 
     b = Bench(g, W, torch, args.steps, args.warmup, not args.contiguous)
     b.copy_gbs = copy_gbs
     b.mfma_tflops = mfma_probe(g, torch)
+    b.line_rates = line_probe(g, torch)
+    log("bare line gathers: " + ", ".join("%s %.0f G lines/s (%.2f TB/s)" % (k, v["lines_per_s"] / 1e9, v["gbs"] / 1e3)
+                                          for k, v in b.line_rates.items()))
     log("fp64 matrix-instruction probe: %.1f TFLOP/s sustained (published peak %.1f)" % (b.mfma_tflops,
                                                                                           MFMA_F64_PEAK_TFLOPS))
     also_names = [w for w in args.also.split(",") if w and w != args.workload]
@@ -1014,7 +1056,7 @@ def main():
             sweeps[w] = b.cpu_chunk_sweep(w, CPU_CHUNK_SWEEPS[w])
     rec["ceilings"] = {"hbm_peak_gbs": HBM_PEAK_GBS, "measured_copy_gbs": copy_gbs,
                        "mfma_f64_peak_tflops": MFMA_F64_PEAK_TFLOPS, "measured_mfma_f64_tflops": b.mfma_tflops,
-                       "probes": b.ceil,
+                       "bare_line_gather": b.line_rates, "probes": b.ceil,
                        "note": "probe-l2-line: one line per edge out of 3.7 MB (L2-resident); probe-mall-line: out of "
                                "134 MB (Infinity Cache); probe-hbm-line: out of 2.1 GB; probe-hbm-row: 2.4 KB rows out "
                                "of 5.1 GB; uniform random graphs, same kernel"}

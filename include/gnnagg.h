@@ -434,6 +434,18 @@ GNNAGG_API int gnnagg_copy_probe(void* dst, const void* src, size_t bytes, void*
  */
 GNNAGG_API int gnnagg_mfma_f64_probe(double* sink, int64_t iters, int32_t workgroups, void* stream);
 
+/*
+ * Measurement aid, not part of the method: the bare access pattern of a one-line gather.  `workgroups`
+ * workgroups of 256 lanes; every group of eight lanes reads 8 * rounds 128-byte lines of buf[0 .. bytes)
+ * chosen by a hash (16 bytes per lane, eight loads in flight per lane), loads no index and keeps no sum:
+ * the rate at which the memory system serves random lines out of a working set of `bytes` bytes - in L2,
+ * in the Infinity Cache or in HBM, by its size - as a ceiling for the aggregation kernels' line requests.
+ * Lines read per call: workgroups * 32 * 8 * rounds.  buf: 128-byte aligned, bytes a multiple of 128
+ * (below 2^39); sink: 4 bytes of device memory, never written.  Asynchronous on `stream`.
+ */
+GNNAGG_API int gnnagg_line_gather_probe(const void* buf, size_t bytes, int32_t rounds, int32_t workgroups,
+                             void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -12,7 +12,7 @@ from .binding import (  # noqa: F401
     gnnagg_aggregate_noalloc, gnnagg_aggregate_update, gnnagg_aggregate_workspace_bytes, gnnagg_auto_f_chunk,
     gnnagg_auto_source_blocks,
     gnnagg_build_csr, gnnagg_check_csr, gnnagg_combine, gnnagg_copy_probe, gnnagg_gat_attention,
-    gnnagg_gat_workspace_bytes, gnnagg_mfma_f64_probe, gnnagg_plan_rows, gnnagg_plan_source_blocks,
+    gnnagg_gat_workspace_bytes, gnnagg_line_gather_probe, gnnagg_mfma_f64_probe, gnnagg_plan_rows, gnnagg_plan_source_blocks,
     gnnagg_rank_sources, gnnagg_row_pitch, gnnagg_set_workgroup_cap, gnnagg_strerror, gnnagg_tune_blocked, gnnagg_tune_f_chunk,
     pitched_empty, gnnagg_version, library_path, load_library,
 )

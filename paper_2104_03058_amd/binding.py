@@ -95,6 +95,8 @@ def load_library():
         lib.gnnagg_mfma_f64_probe.restype = ci
         lib.gnnagg_mfma_f64_probe.argtypes = [vp, i64, i32, vp]
         lib.gnnagg_copy_probe.restype = ci
+        lib.gnnagg_line_gather_probe.argtypes = [vp, ctypes.c_size_t, i32, i32, vp, vp]
+        lib.gnnagg_line_gather_probe.restype = ci
         lib.gnnagg_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         _lib = lib
     return _lib
@@ -552,6 +554,14 @@ def gnnagg_tune_blocked(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edg
                                  _stream(stream), ctypes.byref(best), ctypes.byref(ms))
     _check("gnnagg_tune_blocked", rc)
     return int(best.value), float(ms.value)
+
+
+def gnnagg_line_gather_probe(buf: torch.Tensor, rounds: int, workgroups: int, sink: torch.Tensor, stream=None) -> int:
+    """Enqueues the bare one-line gather over `buf` (uint8, 128-byte aligned); returns the lines it reads."""
+    rc = load_library().gnnagg_line_gather_probe(_dev(buf), buf.numel() * buf.element_size(), rounds, workgroups,
+                                                 _dev(sink), _stream(stream))
+    _check("gnnagg_line_gather_probe", rc)
+    return workgroups * 32 * 8 * rounds
 
 
 def gnnagg_mfma_f64_probe(sink: torch.Tensor, iters: int, workgroups: int, stream=None) -> float:

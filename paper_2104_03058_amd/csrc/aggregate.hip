@@ -218,8 +218,14 @@ struct AggAcc {
   template <bool MASKED>
   __device__ inline void use(int u, float w, bool ok) {
     float v[VEC];
-    unpack(raw[u], v);
-    st.template add<MASKED>(v, w, ok);
+    if constexpr (MASKED && OPK != OPK_MAX) {
+      // sums: a missing entry is zeroed in the bits it was loaded as, then takes the unmasked path
+      unpack(and_bits(raw[u], keep_bits(ok)), v);
+      st.template add<false>(v, w, true);
+    } else {
+      unpack(raw[u], v);
+      st.template add<MASKED>(v, w, ok);
+    }
   }
 };
 

@@ -45,6 +45,33 @@ __device__ inline void unpack(u32x4_h r, float (&v)[8]) {
   v[4] = bf16lo(r.z); v[5] = bf16hi(r.z); v[6] = bf16lo(r.w); v[7] = bf16hi(r.w);
 }
 
+// All-ones for an entry that exists, zero for one that does not, as a value the optimiser cannot see through:
+// ANDed into the raw bits of a loaded row piece it makes a missing entry an exact +0 at one integer
+// instruction per 32 bits loaded.  (Written as a select on the widened value the same masking costs two
+// selects per fp64 value, because the compiler moves a select on the fp32 value behind the conversion.)
+__device__ inline uint32_t keep_bits(bool ok) {
+  uint32_t m = ok ? 0xffffffffu : 0u;
+  asm("" : "+v"(m));
+  return m;
+}
+__device__ inline float and_bits(float r, uint32_t m) { return __uint_as_float(__float_as_uint(r) & m); }
+__device__ inline f32x2_u and_bits(f32x2_u r, uint32_t m) {
+  f32x2_u o; o.x = and_bits((float)r.x, m); o.y = and_bits((float)r.y, m);
+  return o;
+}
+__device__ inline f32x4_u and_bits(f32x4_u r, uint32_t m) {
+  f32x4_u o; o.x = and_bits((float)r.x, m); o.y = and_bits((float)r.y, m); o.z = and_bits((float)r.z, m);
+  o.w = and_bits((float)r.w, m);
+  return o;
+}
+__device__ inline uint16_t and_bits(uint16_t r, uint32_t m) { return (uint16_t)(r & m); }
+__device__ inline u32x1_h and_bits(u32x1_h r, uint32_t m) { return r & m; }
+__device__ inline u32x2_h and_bits(u32x2_h r, uint32_t m) { u32x2_h o; o.x = r.x & m; o.y = r.y & m; return o; }
+__device__ inline u32x4_h and_bits(u32x4_h r, uint32_t m) {
+  u32x4_h o; o.x = r.x & m; o.y = r.y & m; o.z = r.z & m; o.w = r.w & m;
+  return o;
+}
+
 template <int VEC>
 __device__ inline void store_row(float* p, const float (&v)[VEC]) {
   if constexpr (VEC == 1) {

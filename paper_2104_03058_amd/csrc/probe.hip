@@ -3,6 +3,9 @@
 // against a kernel whose traffic is known (bytes read = bytes written = n).
 // gnnagg_mfma_f64_probe: a loop of fp64 matrix instructions on every SIMD, the rate the
 // Combination kernel's arithmetic can at best reach on the device at hand.
+// gnnagg_line_gather_probe: random 128-byte lines out of a buffer, eight lanes per line, eight lines in
+// flight per lane and nothing else: what the memory system gives the access pattern of a one-line gather
+// when no index is loaded and nothing is accumulated.
 #include "common.hpp"
 
 namespace gnnagg {
@@ -34,10 +37,53 @@ __global__ __launch_bounds__(kBlock) void mfma_f64_probe_kernel(double* __restri
   if (s == -1.0) sink[0] = s;  // never true: keeps the chains alive
 }
 
+// Counter-based index: a 32-bit mix of (lane group, position), the same in the eight lanes of a group.
+__device__ inline uint32_t mix32(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x7feb352du;
+  x ^= x >> 15;
+  x *= 0x846ca68bu;
+  x ^= x >> 16;
+  return x;
+}
+
+// Every group of eight lanes reads `rounds` x 8 random lines of the buffer, 16 bytes per lane (one whole
+// 128-byte line per group and load), eight independent loads issued back to back per round.
+__global__ __launch_bounds__(kBlock) void line_gather_probe_kernel(const u32x4* __restrict__ buf, uint32_t n_lines,
+                                                                   int32_t rounds, uint32_t* __restrict__ sink) {
+  const uint32_t group = (blockIdx.x * (uint32_t)kBlock + threadIdx.x) >> 3;
+  const uint32_t part = threadIdx.x & 7u;
+  u32x4 acc = (u32x4){0u, 0u, 0u, 0u};
+  for (int32_t r = 0; r < rounds; ++r) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const uint32_t h = mix32(group * 0x9e3779b9u + (uint32_t)(r * 8 + u));
+      const uint32_t line = (uint32_t)(((uint64_t)h * (uint64_t)n_lines) >> 32);  // in [0, n_lines)
+      v[u] = buf[(uint64_t)line * 8u + part];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  if (acc.x == 0x9e3779b9u && acc.y == 0x7f4a7c15u && acc.z == 0x2545f491u) sink[0] = acc.w;  // keeps the loads alive
+}
+
 }  // namespace
 }  // namespace gnnagg
 
 using namespace gnnagg;
+
+extern "C" int gnnagg_line_gather_probe(const void* buf, size_t bytes, int32_t rounds, int32_t workgroups,
+                                        void* sink, void* stream) {
+  if (!buf || !sink) return GNNAGG_ENULL;
+  if (bytes < 128 || bytes % 128 || bytes / 128 > 0xffffffffull || ((uintptr_t)buf % 128) || ((uintptr_t)sink % 4) ||
+      rounds <= 0 || rounds > (1 << 20) || workgroups <= 0 || workgroups > (1 << 20))
+    return GNNAGG_EINVAL;
+  hipLaunchKernelGGL(line_gather_probe_kernel, dim3((unsigned)workgroups), dim3(kBlock), 0, (hipStream_t)stream,
+                     (const u32x4*)buf, (uint32_t)(bytes / 128), rounds, (uint32_t*)sink);
+  GNNAGG_HIP_TRY(hipGetLastError());
+  return GNNAGG_OK;
+}
 
 extern "C" int gnnagg_mfma_f64_probe(double* sink, int64_t iters, int32_t workgroups, void* stream) {
   if (!sink) return GNNAGG_ENULL;

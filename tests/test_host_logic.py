@@ -268,6 +268,18 @@ def test_source_block_entry_points_validate_on_the_host(lib):
     assert tcall(N=0, X=None, out=None, bp=None, co=ctypes.cast(empty, ctypes.c_void_p)) == 0 and best.value == 8
 
 
+def test_line_gather_probe_validates_on_the_host(lib):
+    EINVAL, ENULL = -1, -2
+    one, other = ctypes.c_void_p(4096), ctypes.c_void_p(8192)
+    f = lib.gnnagg_line_gather_probe
+    assert f(None, 1 << 20, 1, 1, other, None) == ENULL and f(one, 1 << 20, 1, 1, None, None) == ENULL
+    assert f(one, 100, 1, 1, other, None) == EINVAL          # not whole lines
+    assert f(one, 0, 1, 1, other, None) == EINVAL
+    assert f(ctypes.c_void_p(4100), 1 << 20, 1, 1, other, None) == EINVAL   # buffer not on a line
+    assert f(one, 1 << 20, 0, 1, other, None) == EINVAL and f(one, 1 << 20, 1, 0, other, None) == EINVAL
+    assert f(one, 1 << 40, 1, 1, other, None) == EINVAL      # more than 2^32 lines
+
+
 def test_source_block_rule(lib):
     """Blocks pay on dense fp32 graphs of at least 100,000 rows whose rows start on lines; nowhere else.  Four
     where the edges are spread over the rows, two where the longest tenth of the rows holds most of them."""

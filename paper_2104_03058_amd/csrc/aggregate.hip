@@ -201,7 +201,10 @@ struct State<OPK_MAX, VEC> {
 };
 
 // Accumulator policy of the walk in gather.hpp: one 16-byte piece of the source row per edge.
-template <typename T, int OPK, int VEC>
+// BITMASK: a missing entry is zeroed in the bits it was loaded as (sums only; the slices of 1 to 32 lanes,
+// where every batch is masked), instead of by selects on the widened values (wave-wide slices, where only
+// a row's last batch is masked and the selects are scalar-driven).
+template <typename T, int OPK, int VEC, bool BITMASK>
 struct AggAcc {
   static constexpr bool kWeighted = (OPK == OPK_WSUM);
   State<OPK, VEC> st;
@@ -218,7 +221,7 @@ struct AggAcc {
   template <bool MASKED>
   __device__ inline void use(int u, float w, bool ok) {
     float v[VEC];
-    if constexpr (MASKED && OPK != OPK_MAX) {
+    if constexpr (MASKED && BITMASK && OPK != OPK_MAX) {
       // sums: a missing entry is zeroed in the bits it was loaded as, then takes the unmasked path
       unpack(and_bits(raw[u], keep_bits(ok)), v);
       st.template add<false>(v, w, true);
@@ -252,7 +255,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
     if (e0 > e1) e0 = e1;
     if (e1 - e0 > ((int64_t)1 << kSplitLenLog2)) e1 = e0 + ((int64_t)1 << kSplitLenLog2);
   }
-  AggAcc<T, OPK, VEC> acc;
+  AggAcc<T, OPK, VEC, MODE != MODE_WAVE> acc;
   acc.st.init();
   // A later source block: the lane that will write the row starts from the state the earlier blocks left
   // (the other lanes of the row from nothing), so the read is in flight while the row is gathered and the

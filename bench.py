@@ -327,12 +327,15 @@ class Bench:
         # the aggregation kernel's own rate on a uniform L2-resident graph is reported next to it
         l2 = None
         hw_lines = self.line_rates.get("l2", {}).get("lines_per_s")
+        full_lines = self.line_rates.get("l2", {}).get("with_index_stream_and_fp64_sums_lines_per_s")
         own_lines = self.ceil.get("probe-l2-line", {}).get("lines_per_s")
         if lines:
             l2 = {"bound": "l2-line-requests", "unit": "G lines/s", "achieved": lines / t / 1e9,
                   "peak": hw_lines / 1e9 if hw_lines else None,
                   "frac": (lines / t / hw_lines) if hw_lines else None, "lines_per_call": lines,
                   "peak_source": "bare gather of random 128-byte lines out of 3.7 MB (L2-resident), this run",
+                  "same_pattern_with_index_stream_and_fp64_sums": full_lines / 1e9 if full_lines else None,
+                  "frac_of_the_pattern_with_index_stream_and_fp64_sums": (lines / t / full_lines) if full_lines else None,
                   "aggregation_kernel_on_an_l2_resident_uniform_graph": own_lines / 1e9 if own_lines else None,
                   "frac_of_that": (lines / t / own_lines) if own_lines else None}
         fab = None
@@ -910,28 +913,35 @@ LINE_PROBE_SETS = (("l2", 3_727_360), ("infinity_cache", 134_217_728), ("hbm", 2
 
 
 def line_probe(g, torch, repeats=3):
-    """The bare access pattern of a one-line gather (gnnagg_line_gather_probe: random 128-byte lines, eight lanes
-    per line, eight loads in flight per lane, no index stream, no arithmetic) out of working sets that live in
-    L2, in the Infinity Cache and in HBM: what the memory system gives the pattern itself."""
+    """The access pattern of a one-line gather (gnnagg_line_gather_probe: random 128-byte lines, eight lanes per
+    line, eight loads in flight per lane) out of working sets that live in L2, in the Infinity Cache and in HBM:
+    alone (no index stream, no arithmetic: what the memory system gives the pattern), and with the ingredients
+    of an aggregation pass (line numbers read from memory like colidx, bit mask, fp64 sums) but none of its rows."""
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    wgs, rounds = 256 * 16, 36  # 3.8e7 lines per launch
     out = {}
-    for name, nbytes in LINE_PROBE_SETS:
-        buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(3)
-        wgs = 256 * 16
-        rounds = 36  # 3.8e7 lines per launch
-        g.gnnagg_line_gather_probe(buf, rounds, wgs, sink)
+
+    def timed(buf, idx):
+        g.gnnagg_line_gather_probe(buf, rounds, wgs, sink, idx)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         lines = 0
         for _ in range(repeats):
-            lines += g.gnnagg_line_gather_probe(buf, rounds, wgs, sink)
+            lines += g.gnnagg_line_gather_probe(buf, rounds, wgs, sink, idx)
         e1.record()
         torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1)
-        out[name] = {"working_set_bytes": nbytes, "lines_per_s": lines / (ms * 1e-3),
-                     "gbs": lines * 128 / (ms * 1e-3) / 1e9, "kernel_ms": ms / repeats}
-        del buf
+        return lines / (e0.elapsed_time(e1) * 1e-3)
+
+    for name, nbytes in LINE_PROBE_SETS:
+        buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(3)
+        idx = torch.randint(0, nbytes // 128, (wgs * 256 * rounds,), dtype=torch.int32, device="cuda",
+                            generator=torch.Generator(device="cuda").manual_seed(5))
+        rate, full = timed(buf, None), timed(buf, idx)
+        out[name] = {"working_set_bytes": nbytes, "lines_per_s": rate, "gbs": rate * 128 / 1e9,
+                     "with_index_stream_and_fp64_sums_lines_per_s": full,
+                     "with_index_stream_and_fp64_sums_gbs": full * 132 / 1e9}  # 128-byte line + 4-byte line number
+        del buf, idx
     return out
 
 
@@ -1024,8 +1034,9 @@ def main():
     b.copy_gbs = copy_gbs
     b.mfma_tflops = mfma_probe(g, torch)
     b.line_rates = line_probe(g, torch)
-    log("bare line gathers: " + ", ".join("%s %.0f G lines/s (%.2f TB/s)" % (k, v["lines_per_s"] / 1e9, v["gbs"] / 1e3)
-                                          for k, v in b.line_rates.items()))
+    log("line gathers, alone / with index stream and fp64 sums: " + ", ".join(
+        "%s %.0f / %.0f G lines/s" % (k, v["lines_per_s"] / 1e9, v["with_index_stream_and_fp64_sums_lines_per_s"] / 1e9)
+        for k, v in b.line_rates.items()))
     log("fp64 matrix-instruction probe: %.1f TFLOP/s sustained (published peak %.1f)" % (b.mfma_tflops,
                                                                                           MFMA_F64_PEAK_TFLOPS))
     also_names = [w for w in args.also.split(",") if w and w != args.workload]

@@ -435,16 +435,21 @@ GNNAGG_API int gnnagg_copy_probe(void* dst, const void* src, size_t bytes, void*
 GNNAGG_API int gnnagg_mfma_f64_probe(double* sink, int64_t iters, int32_t workgroups, void* stream);
 
 /*
- * Measurement aid, not part of the method: the bare access pattern of a one-line gather.  `workgroups`
+ * Measurement aid, not part of the method: the access pattern of a one-line gather.  `workgroups`
  * workgroups of 256 lanes; every group of eight lanes reads 8 * rounds 128-byte lines of buf[0 .. bytes)
- * chosen by a hash (16 bytes per lane, eight loads in flight per lane), loads no index and keeps no sum:
- * the rate at which the memory system serves random lines out of a working set of `bytes` bytes - in L2,
- * in the Infinity Cache or in HBM, by its size - as a ceiling for the aggregation kernels' line requests.
+ * (16 bytes per lane, eight loads in flight per lane).
+ *   idx == NULL: the pattern alone - lines chosen by a hash, no index loaded, no sum kept: the rate at which
+ *     the memory system serves random lines out of a working set of `bytes` bytes (in L2, in the Infinity
+ *     Cache or in HBM, by its size), the ceiling for the aggregation kernels' line requests.
+ *   idx != NULL: [workgroups * 32 * 8 * rounds] uint32 line numbers (clamped to the buffer), read the way an
+ *     aggregation pass reads colidx (one per lane and round, a round ahead, handed round with swizzles);
+ *     the loaded floats pass a bit mask and are summed in fp64: an aggregation pass without its rows, what
+ *     the ingredients themselves cost.
  * Lines read per call: workgroups * 32 * 8 * rounds.  buf: 128-byte aligned, bytes a multiple of 128
- * (below 2^39); sink: 4 bytes of device memory, never written.  Asynchronous on `stream`.
+ * (below 2^38); sink: 4 bytes of device memory, never written.  Asynchronous on `stream`.
  */
-GNNAGG_API int gnnagg_line_gather_probe(const void* buf, size_t bytes, int32_t rounds, int32_t workgroups,
-                             void* sink, void* stream);
+GNNAGG_API int gnnagg_line_gather_probe(const void* buf, size_t bytes, const uint32_t* idx, int32_t rounds,
+                             int32_t workgroups, void* sink, void* stream);
 
 #ifdef __cplusplus
 }

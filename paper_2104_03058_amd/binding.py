@@ -95,7 +95,7 @@ def load_library():
         lib.gnnagg_mfma_f64_probe.restype = ci
         lib.gnnagg_mfma_f64_probe.argtypes = [vp, i64, i32, vp]
         lib.gnnagg_copy_probe.restype = ci
-        lib.gnnagg_line_gather_probe.argtypes = [vp, ctypes.c_size_t, i32, i32, vp, vp]
+        lib.gnnagg_line_gather_probe.argtypes = [vp, ctypes.c_size_t, vp, i32, i32, vp, vp]
         lib.gnnagg_line_gather_probe.restype = ci
         lib.gnnagg_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         _lib = lib
@@ -556,12 +556,19 @@ def gnnagg_tune_blocked(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edg
     return int(best.value), float(ms.value)
 
 
-def gnnagg_line_gather_probe(buf: torch.Tensor, rounds: int, workgroups: int, sink: torch.Tensor, stream=None) -> int:
-    """Enqueues the bare one-line gather over `buf` (uint8, 128-byte aligned); returns the lines it reads."""
-    rc = load_library().gnnagg_line_gather_probe(_dev(buf), buf.numel() * buf.element_size(), rounds, workgroups,
-                                                 _dev(sink), _stream(stream))
+def gnnagg_line_gather_probe(buf: torch.Tensor, rounds: int, workgroups: int, sink: torch.Tensor,
+                             idx: Optional[torch.Tensor] = None, stream=None) -> int:
+    """Enqueues the one-line gather probe over `buf` (uint8, 128-byte aligned): the pattern alone, or with `idx`
+    (int32, workgroups * 256 * rounds line numbers) the index stream and fp64 sums as well; returns the lines it
+    reads."""
+    lines = workgroups * 32 * 8 * rounds
+    if idx is not None and idx.numel() < lines:
+        raise ValueError("idx must hold one line number per line read")
+    rc = load_library().gnnagg_line_gather_probe(_dev(buf), buf.numel() * buf.element_size(),
+                                                 _dev(idx, torch.int32, "idx"), rounds, workgroups, _dev(sink),
+                                                 _stream(stream))
     _check("gnnagg_line_gather_probe", rc)
-    return workgroups * 32 * 8 * rounds
+    return lines
 
 
 def gnnagg_mfma_f64_probe(sink: torch.Tensor, iters: int, workgroups: int, stream=None) -> float:

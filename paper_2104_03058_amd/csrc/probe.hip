@@ -5,7 +5,8 @@
 // Combination kernel's arithmetic can at best reach on the device at hand.
 // gnnagg_line_gather_probe: random 128-byte lines out of a buffer, eight lanes per line, eight lines in
 // flight per lane and nothing else: what the memory system gives the access pattern of a one-line gather
-// when no index is loaded and nothing is accumulated.
+// when no index is loaded and nothing is accumulated - or, given an index array, with the index stream, the
+// bit mask and the fp64 sums of an aggregation pass and nothing of its row structure.
 #include "common.hpp"
 
 namespace gnnagg {
@@ -49,23 +50,62 @@ __device__ inline uint32_t mix32(uint32_t x) {
 
 // Every group of eight lanes reads `rounds` x 8 random lines of the buffer, 16 bytes per lane (one whole
 // 128-byte line per group and load), eight independent loads issued back to back per round.
+// FULL = false: the pattern alone - line numbers from a hash, the loaded words folded with xor.
+// FULL = true: with the ingredients of an aggregation pass - the line numbers come from memory (one per
+// lane and round, requested one round ahead, handed round the group with swizzles), the loaded floats are
+// zeroed by a bit mask where the line number is negative (it never is) and summed in fp64.
+template <bool FULL>
 __global__ __launch_bounds__(kBlock) void line_gather_probe_kernel(const u32x4* __restrict__ buf, uint32_t n_lines,
-                                                                   int32_t rounds, uint32_t* __restrict__ sink) {
+                                                                   const uint32_t* __restrict__ idx, int32_t rounds,
+                                                                   uint32_t* __restrict__ sink) {
   const uint32_t group = (blockIdx.x * (uint32_t)kBlock + threadIdx.x) >> 3;
   const uint32_t part = threadIdx.x & 7u;
   u32x4 acc = (u32x4){0u, 0u, 0u, 0u};
+  double sum[4] = {0.0, 0.0, 0.0, 0.0};
+  const uint64_t first = (uint64_t)group * (uint64_t)rounds * 8u;  // this group's line numbers in idx
+  uint32_t mine = 0;
+  if (FULL) mine = min(idx[first + part], n_lines - 1u);
   for (int32_t r = 0; r < rounds; ++r) {
+    uint32_t next = 0;
+    if (FULL && r + 1 < rounds) next = min(idx[first + (uint64_t)(r + 1) * 8u + part], n_lines - 1u);
+    uint32_t line[8];
+    if (FULL) {
+      line[0] = (uint32_t)__builtin_amdgcn_ds_swizzle((int)mine, (0 << 5) | 0x18);
+      line[1] = (uint32_t)__builtin_amdgcn_ds_swizzle((int)mine, (1 << 5) | 0x18);
+      line[2] = (uint32_t)__builtin_amdgcn_ds_swizzle((int)mine, (2 << 5) | 0x18);
+      line[3] = (uint32_t)__builtin_amdgcn_ds_swizzle((int)mine, (3 << 5) | 0x18);
+      line[4] = (uint32_t)__builtin_amdgcn_ds_swizzle((int)mine, (4 << 5) | 0x18);
+      line[5] = (uint32_t)__builtin_amdgcn_ds_swizzle((int)mine, (5 << 5) | 0x18);
+      line[6] = (uint32_t)__builtin_amdgcn_ds_swizzle((int)mine, (6 << 5) | 0x18);
+      line[7] = (uint32_t)__builtin_amdgcn_ds_swizzle((int)mine, (7 << 5) | 0x18);
+    } else {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const uint32_t h = mix32(group * 0x9e3779b9u + (uint32_t)(r * 8 + u));
+        line[u] = (uint32_t)(((uint64_t)h * (uint64_t)n_lines) >> 32);  // in [0, n_lines)
+      }
+    }
     u32x4 v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const uint32_t h = mix32(group * 0x9e3779b9u + (uint32_t)(r * 8 + u));
-      const uint32_t line = (uint32_t)(((uint64_t)h * (uint64_t)n_lines) >> 32);  // in [0, n_lines)
-      v[u] = buf[(uint64_t)line * 8u + part];
-    }
+    for (int u = 0; u < 8; ++u) v[u] = buf[(uint64_t)line[u] * 8u + part];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) acc ^= v[u];
+    for (int u = 0; u < 8; ++u) {
+      if (FULL) {
+        uint32_t m = (int32_t)line[u] >= 0 ? 0xffffffffu : 0u;
+        asm("" : "+v"(m));
+        sum[0] += (double)__uint_as_float(v[u].x & m);
+        sum[1] += (double)__uint_as_float(v[u].y & m);
+        sum[2] += (double)__uint_as_float(v[u].z & m);
+        sum[3] += (double)__uint_as_float(v[u].w & m);
+      } else {
+        acc ^= v[u];
+      }
+    }
+    mine = next;
   }
-  if (acc.x == 0x9e3779b9u && acc.y == 0x7f4a7c15u && acc.z == 0x2545f491u) sink[0] = acc.w;  // keeps the loads alive
+  const double s = sum[0] + sum[1] + sum[2] + sum[3];
+  if ((acc.x == 0x9e3779b9u && acc.y == 0x7f4a7c15u && acc.z == 0x2545f491u) || s == 1.2345e300)
+    sink[0] = acc.w ^ (uint32_t)__double2hiint(s);  // never true: keeps the loads and the sums alive
 }
 
 }  // namespace
@@ -73,14 +113,19 @@ __global__ __launch_bounds__(kBlock) void line_gather_probe_kernel(const u32x4* 
 
 using namespace gnnagg;
 
-extern "C" int gnnagg_line_gather_probe(const void* buf, size_t bytes, int32_t rounds, int32_t workgroups,
-                                        void* sink, void* stream) {
+extern "C" int gnnagg_line_gather_probe(const void* buf, size_t bytes, const uint32_t* idx, int32_t rounds,
+                                        int32_t workgroups, void* sink, void* stream) {
   if (!buf || !sink) return GNNAGG_ENULL;
-  if (bytes < 128 || bytes % 128 || bytes / 128 > 0xffffffffull || ((uintptr_t)buf % 128) || ((uintptr_t)sink % 4) ||
-      rounds <= 0 || rounds > (1 << 20) || workgroups <= 0 || workgroups > (1 << 20))
+  if (bytes < 128 || bytes % 128 || bytes / 128 > 0x7fffffffull || ((uintptr_t)buf % 128) || ((uintptr_t)sink % 4) ||
+      rounds <= 0 || rounds > (1 << 20) || workgroups <= 0 || workgroups > (1 << 20) || ((uintptr_t)idx % 4))
     return GNNAGG_EINVAL;
-  hipLaunchKernelGGL(line_gather_probe_kernel, dim3((unsigned)workgroups), dim3(kBlock), 0, (hipStream_t)stream,
-                     (const u32x4*)buf, (uint32_t)(bytes / 128), rounds, (uint32_t*)sink);
+  const dim3 grid((unsigned)workgroups), block(kBlock);
+  if (idx)
+    hipLaunchKernelGGL(line_gather_probe_kernel<true>, grid, block, 0, (hipStream_t)stream, (const u32x4*)buf,
+                       (uint32_t)(bytes / 128), idx, rounds, (uint32_t*)sink);
+  else
+    hipLaunchKernelGGL(line_gather_probe_kernel<false>, grid, block, 0, (hipStream_t)stream, (const u32x4*)buf,
+                       (uint32_t)(bytes / 128), idx, rounds, (uint32_t*)sink);
   GNNAGG_HIP_TRY(hipGetLastError());
   return GNNAGG_OK;
 }

@@ -272,12 +272,13 @@ def test_line_gather_probe_validates_on_the_host(lib):
     EINVAL, ENULL = -1, -2
     one, other = ctypes.c_void_p(4096), ctypes.c_void_p(8192)
     f = lib.gnnagg_line_gather_probe
-    assert f(None, 1 << 20, 1, 1, other, None) == ENULL and f(one, 1 << 20, 1, 1, None, None) == ENULL
-    assert f(one, 100, 1, 1, other, None) == EINVAL          # not whole lines
-    assert f(one, 0, 1, 1, other, None) == EINVAL
-    assert f(ctypes.c_void_p(4100), 1 << 20, 1, 1, other, None) == EINVAL   # buffer not on a line
-    assert f(one, 1 << 20, 0, 1, other, None) == EINVAL and f(one, 1 << 20, 1, 0, other, None) == EINVAL
-    assert f(one, 1 << 40, 1, 1, other, None) == EINVAL      # more than 2^32 lines
+    assert f(None, 1 << 20, None, 1, 1, other, None) == ENULL and f(one, 1 << 20, None, 1, 1, None, None) == ENULL
+    assert f(one, 100, None, 1, 1, other, None) == EINVAL          # not whole lines
+    assert f(one, 0, None, 1, 1, other, None) == EINVAL
+    assert f(ctypes.c_void_p(4100), 1 << 20, None, 1, 1, other, None) == EINVAL   # buffer not on a line
+    assert f(one, 1 << 20, None, 0, 1, other, None) == EINVAL and f(one, 1 << 20, None, 1, 0, other, None) == EINVAL
+    assert f(one, 1 << 40, None, 1, 1, other, None) == EINVAL      # more than 2^31 lines
+    assert f(one, 1 << 20, ctypes.c_void_p(4098), 1, 1, other, None) == EINVAL    # index array not on 4 bytes
 
 
 def test_source_block_rule(lib):

@@ -379,7 +379,8 @@ class Bench:
         op = {"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname]
 
         if n_blocks < 0:
-            n_blocks = g.gnnagg_auto_source_blocks(N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)),
+            n_blocks = g.gnnagg_auto_source_blocks({"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname],
+                                                   N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)),
                                                    c["plan"])
             n_blocks = 0 if n_blocks <= 1 else n_blocks
         if n_blocks:  # per graph, like the CSR and the plan; the states in transit live in a workspace kept here
@@ -784,6 +785,16 @@ HELD_OUT_6 = [
     (240_000, 26_400_000, 2.0, 1000.0, 256, "f32", "mean"),   # degree 220
     (105_000, 26_250_000, 1.7, 450.0, 1024, "f32", "wsum"),   # degree 500, just above the row threshold
 ]
+# A seventh set, mostly sum / mean / max on dense graphs of middling concentration, drawn after the block count
+# became a function of the operator as well: never used to adjust the source-block rule.
+HELD_OUT_7 = [
+    (280_000, 36_400_000, 1.9, 1200.0, 384, "f32", "mean"),   # degree 260
+    (160_000, 28_000_000, 2.0, 700.0, 512, "f32", "max"),     # degree 350
+    (420_000, 44_100_000, 1.95, 1600.0, 160, "f32", "sum"),   # degree 210
+    (200_000, 45_000_000, 1.85, 900.0, 256, "f32", "mean"),   # degree 450
+    (130_000, 19_500_000, 1.75, 600.0, 768, "f32", "sum"),    # degree 300, heavier tail
+    (300_000, 42_000_000, 1.9, 1300.0, 320, "f32", "wsum"),   # degree 280, weighted
+]
 # the benchmark graphs the rules were first derived on, for the same table (not held out)
 TUNING_SHAPES = [
     (232_965, 57_307_946, 1.8, 680.0, 602, "f32", "wsum"),
@@ -798,9 +809,9 @@ def validate_auto(g, W, torch, steps, warmup, which):
     resident-workgroup caps {none, 2, 3, 4}, and reports how far the library's own choice is from the best."""
     rows = []
     shapes = {"1": HELD_OUT, "2": HELD_OUT_2, "3": HELD_OUT_3, "4": HELD_OUT_4, "5": HELD_OUT_5, "6": HELD_OUT_6,
-              "tuning": TUNING_SHAPES}[which]
+              "7": HELD_OUT_7, "tuning": TUNING_SHAPES}[which]
     for k, (N, M, alpha, R, F, xdt, opname) in enumerate(shapes):
-        src, dst = W.powerlaw_graph(N, M, alpha, R, {"1": 100, "2": 300, "3": 500, "4": 700, "5": 900, "6": 1100, "tuning": 110}[which] + k)
+        src, dst = W.powerlaw_graph(N, M, alpha, R, {"1": 100, "2": 300, "3": 500, "4": 700, "5": 900, "6": 1100, "7": 1300, "tuning": 110}[which] + k)
         gcn = opname == "wsum"
         flags = (g.SELF_LOOPS | g.NORM_SYM) if gcn else 0
         rp, ci, w, _ = g.gnnagg_build_csr(N, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda(), flags, want_w=gcn)
@@ -863,7 +874,7 @@ def validate_auto(g, W, torch, steps, warmup, which):
             del blocks, ws
         # what a caller following the library's two rules gets: blocks where gnnagg_auto_source_blocks says so
         # (at the blocked call's own width), else the plain call at GNNAGG_F_CHUNK_AUTO
-        B_auto = g.gnnagg_auto_source_blocks(N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)), plan)
+        B_auto = g.gnnagg_auto_source_blocks(op, N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)), plan)
         t_rules = blocked["%d@%d" % (B_auto, 2 * line if xdt != "bf16" else 2 * line)] if B_auto > 1 else t_auto
         best_any = min([best] + list(blocked.values()))
         # all by measurement: the fastest of the two tuners' answers (plain, 2 blocks, 4 blocks), timed like the rest
@@ -992,7 +1003,7 @@ def main():
                     help="'default': the CPU checker in Algorithm 1's chunk-outer order at the sweep widths of the "
                          "two benchmark configurations that name one (about half a minute); 'none'; or a comma list "
                          "of widths for the main workload")
-    ap.add_argument("--validate-auto", default="", choices=["", "1", "2", "3", "4", "5", "6", "tuning"],
+    ap.add_argument("--validate-auto", default="", choices=["", "1", "2", "3", "4", "5", "6", "7", "tuning"],
                     help="instead of the benchmark: time a set of graph shapes (1-3: used to revise the rule; 4: never "
                          "used for it; tuning: the benchmark graphs) at several chunk widths and resident-workgroup caps and print the regret of the "
                          "library's automatic choices")

@@ -327,11 +327,12 @@ GNNAGG_API int gnnagg_tune_blocked(int op, int64_t N, const int64_t* rowptr, con
                         const int32_t* row_order, const int64_t* class_off, void* workspace,
                         size_t* workspace_bytes, void* stream, int32_t* best_f_chunk, float* best_ms);
 
-/* Number of source blocks worth using for a graph with the row plan class_off (HOST pointer, the plan of
- * gnnagg_plan_rows; NULL: 1) and an X of row pitch x_pitch (0 = F) whose first row starts on a 128-byte
- * line; 1 means the plain calls are the faster ones (host arithmetic only; 0 for invalid arguments).
- * Blocks pay on dense graphs only: the states in transit cost 16 bytes per output element and block. */
-GNNAGG_API int32_t gnnagg_auto_source_blocks(int64_t N, int32_t F, int x_dtype, int64_t x_pitch,
+/* Number of source blocks worth using for operator `op` on a graph with the row plan class_off (HOST
+ * pointer, the plan of gnnagg_plan_rows; NULL: 1) and an X of row pitch x_pitch (0 = F) whose first row
+ * starts on a 128-byte line; 1 means the plain calls are the faster ones (host arithmetic only; 0 for
+ * invalid arguments).  Blocks pay on dense graphs only: the states in transit cost 16 bytes per output
+ * element and block. */
+GNNAGG_API int32_t gnnagg_auto_source_blocks(int op, int64_t N, int32_t F, int x_dtype, int64_t x_pitch,
                                   const int64_t* class_off);
 
 /*

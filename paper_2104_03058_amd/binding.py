@@ -73,7 +73,7 @@ def load_library():
         lib.gnnagg_tune_blocked.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, vp, ci, i64, i32, i32, vp, vp, vp, vp, szp,
                                             vp, vp, vp]
         lib.gnnagg_tune_blocked.restype = ci
-        lib.gnnagg_auto_source_blocks.argtypes = [i64, i32, ci, i64, vp]
+        lib.gnnagg_auto_source_blocks.argtypes = [ci, i64, i32, ci, i64, vp]
         lib.gnnagg_auto_source_blocks.restype = i32
         lib.gnnagg_row_pitch.argtypes = [i32, ci]
         lib.gnnagg_gat_attention.restype = ci
@@ -590,11 +590,11 @@ def gnnagg_auto_f_chunk(N: int, F: int, x_dtype: int = F32, x_pitch: int = 0,
     return int(load_library().gnnagg_auto_f_chunk(N, F, x_dtype, x_pitch, class_off))
 
 
-def gnnagg_auto_source_blocks(N: int, F: int, x_dtype: int = F32, x_pitch: int = 0,
+def gnnagg_auto_source_blocks(op: int, N: int, F: int, x_dtype: int = F32, x_pitch: int = 0,
                               plan: Optional[RowPlan] = None) -> int:
-    """Number of source blocks the library recommends for this graph and width (1: use the plain calls)."""
+    """Number of source blocks the library recommends for this operator, graph and width (1: use the plain calls)."""
     return int(load_library().gnnagg_auto_source_blocks(
-        N, F, x_dtype, x_pitch, ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None))
+        op, N, F, x_dtype, x_pitch, ctypes.cast(plan.class_off, ctypes.c_void_p) if plan is not None else None))
 
 
 def gnnagg_combine(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor] = None, relu: bool = False,

@@ -1041,8 +1041,9 @@ extern "C" int64_t gnnagg_row_pitch(int32_t F, int dtype) {
   return padded / elem;
 }
 
-extern "C" int32_t gnnagg_auto_source_blocks(int64_t N, int32_t F, int x_dtype, int64_t x_pitch,
+extern "C" int32_t gnnagg_auto_source_blocks(int op, int64_t N, int32_t F, int x_dtype, int64_t x_pitch,
                                              const int64_t* class_off) {
+  if (op < GNNAGG_SUM || op > GNNAGG_MAX) return 0;
   if (N < 0 || F <= 0 || (x_dtype != GNNAGG_F32 && x_dtype != GNNAGG_BF16)) return 0;
   const int elem = x_dtype == GNNAGG_F32 ? 4 : 2;
   if (x_pitch == 0) x_pitch = F;
@@ -1052,7 +1053,7 @@ extern "C" int32_t gnnagg_auto_source_blocks(int64_t N, int32_t F, int x_dtype, 
     for (int k = 0; k < GNNAGG_PLAN_CLASSES; ++k)
       if (class_off[k] > class_off[k + 1]) return 0;
   }
-  return auto_source_blocks(N, F, elem, ((uint64_t)x_pitch * (uint64_t)elem) % 128 == 0, class_off);
+  return auto_source_blocks(N, F, elem, ((uint64_t)x_pitch * (uint64_t)elem) % 128 == 0, op == GNNAGG_WSUM, class_off);
 }
 
 extern "C" int32_t gnnagg_auto_f_chunk(int64_t N, int32_t F, int x_dtype, int64_t x_pitch, const int64_t* class_off) {

@@ -377,15 +377,17 @@ inline int32_t auto_f_chunk(int64_t N, int32_t F, int elem_bytes, bool rows_on_l
 // bf16 rows (whose plain passes are not bound by L2 misses) the plain call wins, by 5-70 %.
 // How many: the plain call already keeps the hubs' lines in L2, so what blocks add depends on how much of
 // the graph is NOT hubs.  Where the longest tenth of the rows holds under 60 % of the edges (flat degree
-// distributions: the third benchmark graph shape, exponents above 2) 4 blocks beat 2 by 7-30 %; where it
-// holds over 70 % 2 blocks beat 4 by 6-10 %; in between they are level.  8 and more lose to the traffic of
-// the states everywhere.  Returns 1 for "do not block".
-inline int32_t auto_source_blocks(int64_t N, int64_t F, int elem_bytes, bool rows_on_lines, const int64_t* class_off) {
+// distributions: the third benchmark graph shape, exponents above 2) 4 blocks beat 2 by 5-30 %; where it
+// holds over 70 % 2 blocks beat 4 by 4-11 %.  In between the weighted sum is level (its passes also stream
+// the edge weights, which blocks do not help), while sum, mean and max still gain 3-9 % from 4.  8 and more
+// lose to the traffic of the states everywhere.  Returns 1 for "do not block".
+inline int32_t auto_source_blocks(int64_t N, int64_t F, int elem_bytes, bool rows_on_lines, bool weighted,
+                                  const int64_t* class_off) {
   if (!class_off || !rows_on_lines || elem_bytes != 4 || F < 128 || N < 100000) return 1;
   double mean_degree, top_tenth_share;
   degree_profile(class_off, N, N / 10, &mean_degree, &top_tenth_share);
   if (mean_degree < 200.0) return 1;
-  return top_tenth_share < 0.6 ? 4 : 2;
+  return top_tenth_share < (weighted ? 0.6 : 0.7) ? 4 : 2;
 }
 
 // How many workgroups of the aggregation kernel should share a compute unit.  Every resident wave

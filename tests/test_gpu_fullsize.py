@@ -59,8 +59,9 @@ def test_config4_full_size_gcn_and_mean():
     assert g.gnnagg_auto_f_chunk(N, 602, g.F32, 602, plan) == 602
     outp = g.pitched_empty(N, 602, torch.float32)
     # the blocked call as the benchmark's headline runs it: as many source blocks as the library recommends
-    B = g.gnnagg_auto_source_blocks(N, 602, g.F32, int(Xp.stride(0)), plan)
-    assert B == 2 and g.gnnagg_auto_source_blocks(N, 602, g.F32, 602, plan) == 1
+    B = g.gnnagg_auto_source_blocks(g.WSUM, N, 602, g.F32, int(Xp.stride(0)), plan)
+    assert B == 2 and g.gnnagg_auto_source_blocks(g.WSUM, N, 602, g.F32, 602, plan) == 1
+    assert g.gnnagg_auto_source_blocks(g.MEAN, N, 602, g.F32, int(Xp.stride(0)), plan) == 4
     blocks = g.gnnagg_plan_source_blocks(d_rp, d_ci, B)
     ws = torch.empty(g.gnnagg_aggregate_blocked_workspace_bytes(N, 602, blocks), dtype=torch.uint8, device="cuda")
     ref = oracle.aggregate(oracle.WSUM, rp, ci, w, X, threads=16)
@@ -86,6 +87,11 @@ def test_config4_full_size_gcn_and_mean():
         outp.fill_(float("nan"))
         g.gnnagg_aggregate(g.MEAN, d_rp, d_ci, None, Xp, outp, fc, plan)
         close_all(host(outp), ref, what="c4 mean pitched fc=%d" % fc)
+    # sum, mean and max get 4 blocks on this graph (no stream of edge weights that blocks do nothing for)
+    del blocks, ws
+    B = g.gnnagg_auto_source_blocks(g.MEAN, N, 602, g.F32, int(Xp.stride(0)), plan)
+    blocks = g.gnnagg_plan_source_blocks(d_rp, d_ci, B)
+    ws = torch.empty(g.gnnagg_aggregate_blocked_workspace_bytes(N, 602, blocks), dtype=torch.uint8, device="cuda")
     say("c4 full: mean over", B, "source blocks")
     outp.fill_(float("nan"))
     g.gnnagg_aggregate_blocked(g.MEAN, d_rp, d_ci, None, Xp, blocks, outp, g.F_CHUNK_AUTO, workspace=ws)
@@ -178,7 +184,7 @@ def test_dense_small_graph_at_input_width_over_source_blocks():
     Xp = g.pitched_empty(N, 602, torch.float32)
     Xp.copy_(dev(X))
     plan = g.gnnagg_plan_rows(d_rp)
-    B = g.gnnagg_auto_source_blocks(N, 602, g.F32, int(Xp.stride(0)), plan)
+    B = g.gnnagg_auto_source_blocks(g.WSUM, N, 602, g.F32, int(Xp.stride(0)), plan)
     assert B == 4
     blocks = g.gnnagg_plan_source_blocks(d_rp, d_ci, B)
     ref = oracle.aggregate(oracle.WSUM, rp, ci, w, X, threads=16)

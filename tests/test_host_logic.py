@@ -290,18 +290,25 @@ def test_source_block_rule(lib):
                        6: 80000})                            # mean degree ~ 600, the top tenth holds ~ 3/4
     flat = plan_of(N, {11: 20000, 10: 80000, 9: 100000, 8: 32965})                      # ~ 600, top tenth ~ 1/5
     medium = plan_of(N, {11: 3000, 9: 20000, 8: 60000, 7: 80000, 6: 50000, 5: 19965})   # mean degree ~ 130
-    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 608, hubs) == 2
-    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 608, flat) == 4
-    assert g.gnnagg_auto_source_blocks(N, 128, g.F32, 128, flat) == 4
-    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 602, flat) == 1      # rows not on lines
-    assert g.gnnagg_auto_source_blocks(N, 64, g.F32, 64, flat) == 1        # narrow rows: one pass per block is short
-    assert g.gnnagg_auto_source_blocks(N, 512, g.BF16, 512, flat) == 1     # bf16
-    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 608, medium) == 1    # too few edges per row
-    assert g.gnnagg_auto_source_blocks(N, 602, g.F32, 608, None) == 1      # no plan
+    assert g.gnnagg_auto_source_blocks(g.WSUM, N, 602, g.F32, 608, hubs) == 2
+    assert g.gnnagg_auto_source_blocks(g.WSUM, N, 602, g.F32, 608, flat) == 4
+    between = plan_of(N, {15: 300, 14: 2500, 13: 6500, 12: 10000, 11: 12000, 10: 25000, 9: 40000, 8: 50000,
+                          7: 50000, 6: 36665})               # the top tenth holds about 65 % of the edges
+    assert g.gnnagg_auto_source_blocks(g.WSUM, N, 602, g.F32, 608, between) == 2   # the weights' stream gains nothing
+    for op in (g.SUM, g.MEAN, g.MAX):
+        assert g.gnnagg_auto_source_blocks(op, N, 602, g.F32, 608, between) == 4
+        assert g.gnnagg_auto_source_blocks(op, N, 602, g.F32, 608, hubs) == 2
+    assert g.gnnagg_auto_source_blocks(9, N, 602, g.F32, 608, flat) == 0            # no such operator
+    assert g.gnnagg_auto_source_blocks(g.WSUM, N, 128, g.F32, 128, flat) == 4
+    assert g.gnnagg_auto_source_blocks(g.WSUM, N, 602, g.F32, 602, flat) == 1      # rows not on lines
+    assert g.gnnagg_auto_source_blocks(g.WSUM, N, 64, g.F32, 64, flat) == 1        # narrow rows: one pass per block is short
+    assert g.gnnagg_auto_source_blocks(g.WSUM, N, 512, g.BF16, 512, flat) == 1     # bf16
+    assert g.gnnagg_auto_source_blocks(g.WSUM, N, 602, g.F32, 608, medium) == 1    # too few edges per row
+    assert g.gnnagg_auto_source_blocks(g.WSUM, N, 602, g.F32, 608, None) == 1      # no plan
     small = plan_of(60000, {12: 2000, 10: 20000, 9: 38000})
-    assert g.gnnagg_auto_source_blocks(60000, 602, g.F32, 608, small) == 1  # small graph
-    assert g.gnnagg_auto_source_blocks(10, 0, g.F32) == 0 and g.gnnagg_auto_source_blocks(10, 8, 7) == 0
-    assert g.gnnagg_auto_source_blocks(10, 8, g.F32, 4) == 0
+    assert g.gnnagg_auto_source_blocks(g.WSUM, 60000, 602, g.F32, 608, small) == 1  # small graph
+    assert g.gnnagg_auto_source_blocks(g.WSUM, 10, 0, g.F32) == 0 and g.gnnagg_auto_source_blocks(g.WSUM, 10, 8, 7) == 0
+    assert g.gnnagg_auto_source_blocks(g.WSUM, 10, 8, g.F32, 4) == 0
 
 
 # ------------------------------------------------------------------ launch geometry

@@ -517,3 +517,17 @@ def test_bench_module_is_importable_and_its_workloads_name_known_graphs():
         assert {"workload", "kernel_sources", "kernel_source_hash", "fetch_bytes", "write_bytes", "source"} <= set(rec)
     assert len(bench.kernel_source_hash(bench.AGGREGATE_SOURCES)) == 16
     assert bench.kernel_source_hash(bench.AGGREGATE_SOURCES) != bench.kernel_source_hash(bench.GAT_SOURCES)
+
+
+def test_traffic_records_under_profiles_were_taken_with_the_kernels_in_the_tree():
+    """bench.py reports the counted traffic of a workload only from a profile whose recorded fingerprint of the
+    kernel sources equals the tree's; a record that has gone stale would silently turn `roofline.traffic` into
+    null, so the records kept under profiles/ are checked against the sources here."""
+    import importlib
+    bench = importlib.import_module("bench")
+    recs = bench.measured_traffic()
+    assert "c4-gcn#auto" in recs and "c4-gcn" in recs and "c5-sum" in recs and "c4-gat" in recs
+    for name, rec in recs.items():
+        assert rec["kernel_source_hash"] == bench.kernel_source_hash(rec["kernel_sources"]), \
+            "%s: %s was taken with other kernel sources" % (name, rec["source"])
+        assert rec["fetch_bytes"] > 0 and rec["write_bytes"] >= 0

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gnnagg_ref.c")
 _LIB = os.path.join(_HERE, "libgnnagg_ref.so")
 
-SUM, WSUM, MEAN, MAX = 0, 1, 2, 3
+SUM, WSUM, MEAN, MAX, SUM_SCALED = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 SELF_LOOPS, NORM_SYM = 1, 2
 
@@ -52,6 +52,10 @@ def _load():
         lib.gnnagg_ref_combine.argtypes = [i64, vp, ci, i32, vp, vp, i32, ci, vp, ci]
         lib.gnnagg_ref_update.restype = ci
         lib.gnnagg_ref_update.argtypes = [i64, i32, vp, vp, ci, vp]
+        lib.gnnagg_ref_gcn_factors.restype = ci
+        lib.gnnagg_ref_gcn_factors.argtypes = [i64, vp, vp]
+        lib.gnnagg_ref_scale_rows.restype = ci
+        lib.gnnagg_ref_scale_rows.argtypes = [i64, i32, vp, ci, vp, vp]
         _lib = lib
     return _lib
 
@@ -171,4 +175,26 @@ def update(A, bias=None, relu=False):
     rc = _load().gnnagg_ref_update(N, F, _p(A), _p(bias), int(bool(relu)), _p(out))
     if rc != 0:
         raise ValueError("gnnagg_ref_update failed: %d" % rc)
+    return out
+
+
+def gcn_factors(rowptr):
+    """s[i] = 1/sqrt(deg(i)) as float32, 0 for an empty row."""
+    rowptr = _c(rowptr, np.int64)
+    N = rowptr.shape[0] - 1
+    s = np.empty(N, dtype=np.float32)
+    if _load().gnnagg_ref_gcn_factors(N, _p(rowptr), _p(s)) != 0:
+        raise ValueError("gnnagg_ref_gcn_factors failed")
+    return s
+
+
+def scale_rows(X, scale):
+    """out[j, :] = scale[j] * X[j, :] as float32; X float32 or uint16 (bf16 bits)."""
+    X = np.ascontiguousarray(X)
+    N, F = X.shape
+    scale = _c(scale, np.float32)
+    assert scale.shape[0] == N
+    out = np.empty((N, F), dtype=np.float32)
+    if _load().gnnagg_ref_scale_rows(N, F, _p(X), _xinfo(X), _p(scale), _p(out)) != 0:
+        raise ValueError("gnnagg_ref_scale_rows failed")
     return out

@@ -24,7 +24,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { REF_SUM = 0, REF_WSUM = 1, REF_MEAN = 2, REF_MAX = 3 };
+enum { REF_SUM = 0, REF_WSUM = 1, REF_MEAN = 2, REF_MAX = 3, REF_SUM_SCALED = 4 };
 enum { REF_F32 = 0, REF_BF16 = 1 };
 enum { REF_SELF_LOOPS = 1, REF_NORM_SYM = 2 };
 
@@ -117,6 +117,9 @@ int gnnagg_ref_build_csr(int64_t N, int64_t E, const int32_t* src, const int32_t
  * order, one fp64 accumulator per column.
  *   sum / wsum : (float) sum_e w_e * X[colidx[e], f]   (w = 1 for sum)
  *   mean       : 0 if the row is empty, else (float)(sum / deg)
+ *   scaled sum : (float)(s_i * sum_e X[colidx[e], f]), the N factors s passed as edge_w: a weighted sum
+ *                whose weights are s_i times a factor of the source that X already carries (GCN,
+ *                Section III, with s = d^-1/2 on both sides)
  *   max        : +0.0f if the row is empty, else the largest value, with
  *                -0 ordered below +0 so that the result is unique.
  * acc is scratch for c1-c0 doubles.
@@ -146,7 +149,11 @@ static void reduce_row(int op, const int64_t* rowptr, const int32_t* colidx, con
     for (int64_t f = 0; f < W; ++f) acc[f] += w * x_at(X, x_dtype, (int64_t)colidx[e] * F + c0 + f);
   }
   const double deg = (double)(e1 - e0);
-  for (int64_t f = 0; f < W; ++f) out_row[f] = (float)(op == REF_MEAN ? acc[f] / deg : acc[f]);
+  for (int64_t f = 0; f < W; ++f) {
+    if (op == REF_MEAN) out_row[f] = (float)(acc[f] / deg);
+    else if (op == REF_SUM_SCALED) out_row[f] = (float)((double)edge_w[i] * acc[f]);
+    else out_row[f] = (float)acc[f];
+  }
 }
 
 /* Whole-matrix aggregation.  form 0: destination-row outer loop over full
@@ -158,8 +165,8 @@ static void reduce_row(int op, const int64_t* rowptr, const int32_t* colidx, con
 int gnnagg_ref_aggregate(int op, int64_t N, const int64_t* rowptr, const int32_t* colidx, const float* edge_w,
                          const void* X, int x_dtype, float* out, int32_t F, int32_t f_chunk, int form,
                          int threads) {
-  if (op < 0 || op > 3 || N < 0 || F <= 0 || !rowptr || !out || !X) return -1;
-  if (op == REF_WSUM && !edge_w) return -1;
+  if (op < 0 || op > 4 || N < 0 || F <= 0 || !rowptr || !out || !X) return -1;
+  if ((op == REF_WSUM || op == REF_SUM_SCALED) && !edge_w) return -1;
   if (x_dtype != REF_F32 && x_dtype != REF_BF16) return -1;
   const int64_t width = (form == 0 || f_chunk <= 0 || f_chunk >= F) ? F : f_chunk;
   const int64_t P = (F + width - 1) / width;
@@ -187,8 +194,8 @@ int gnnagg_ref_aggregate(int op, int64_t N, const int64_t* rowptr, const int32_t
 int gnnagg_ref_aggregate_rows(int op, int64_t nrows, const int64_t* rows, const int64_t* rowptr,
                               const int32_t* colidx, const float* edge_w, const void* X, int x_dtype,
                               float* out, int32_t F, int threads) {
-  if (op < 0 || op > 3 || nrows < 0 || F <= 0 || !rows || !rowptr || !out || !X) return -1;
-  if (op == REF_WSUM && !edge_w) return -1;
+  if (op < 0 || op > 4 || nrows < 0 || F <= 0 || !rows || !rowptr || !out || !X) return -1;
+  if ((op == REF_WSUM || op == REF_SUM_SCALED) && !edge_w) return -1;
   if (x_dtype != REF_F32 && x_dtype != REF_BF16) return -1;
   int fail = 0;
 #pragma omp parallel num_threads(threads > 1 ? threads : 1)
@@ -352,5 +359,26 @@ int gnnagg_ref_update(int64_t N, int32_t F, const float* A, const float* bias, i
       if (relu && !(y > 0.0f)) y = 0.0f;
       out[n * F + f] = y;
     }
+  return 0;
+}
+
+/* GCN's weights in factored form (the GCN operator of Section III): 1/sqrt(d_i d_j) = s_i s_j with
+ *   s[i] = (float)(1/sqrt(d_i)), d_i the length of row i; 0 for an empty row. */
+int gnnagg_ref_gcn_factors(int64_t N, const int64_t* rowptr, float* s) {
+  if (N < 0 || !rowptr || !s) return -1;
+  for (int64_t i = 0; i < N; ++i) {
+    const int64_t d = rowptr[i + 1] - rowptr[i];
+    s[i] = d > 0 ? (float)(1.0 / sqrt((double)d)) : 0.0f;
+  }
+  return 0;
+}
+
+/* out[j,f] = (float)(scale[j] * X[j,f]): the product of two fp32 values is exact in fp64, so this is the
+ * correctly rounded fp32 product. */
+int gnnagg_ref_scale_rows(int64_t N, int32_t F, const void* X, int x_dtype, const float* scale, float* out) {
+  if (N < 0 || F <= 0 || !X || !scale || !out) return -1;
+  if (x_dtype != REF_F32 && x_dtype != REF_BF16) return -1;
+  for (int64_t j = 0; j < N; ++j)
+    for (int32_t f = 0; f < F; ++f) out[j * F + f] = (float)((double)scale[j] * x_at(X, x_dtype, j * F + f));
   return 0;
 }

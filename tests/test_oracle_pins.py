@@ -164,6 +164,74 @@ def test_gcn_matches_dense_normalised_adjacency():
         assert np.allclose(got, Ahat @ X.astype(np.float64), rtol=2e-6, atol=1e-6)
 
 
+# ---------------------------------------------------------------- GCN in factored form
+def test_gcn_factors_closed_form():
+    # rows of 0, 1, 4, 16 and 3 in-edges: 0, 1, 1/2, 1/4 exactly, and 1/sqrt(3) rounded once
+    deg = [0, 1, 4, 16, 3]
+    rp = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    s = oracle.gcn_factors(rp)
+    assert s.dtype == np.float32
+    assert s[:4].tolist() == [0.0, 1.0, 0.5, 0.25]
+    assert s[4] == np.float32(1.0 / np.sqrt(3.0))
+    N, src, dst = W.graph("c1")
+    rp, _, _, _ = oracle.build_csr(N, src, dst, flags=oracle.SELF_LOOPS)
+    d = np.bincount(dst, minlength=N).astype(np.float64) + 1.0
+    assert np.array_equal(oracle.gcn_factors(rp), (1.0 / np.sqrt(d)).astype(np.float32))
+
+
+def test_scale_rows_is_the_rounded_fp32_product():
+    X = W.normal_f32((23, 9), seed=3)
+    s = W.normal_f32((23,), seed=4)
+    assert np.array_equal(oracle.scale_rows(X, s), X * s[:, None])          # numpy's fp32 product rounds correctly
+    assert np.array_equal(oracle.scale_rows(X, np.full(23, 0.25, np.float32)), X / 4)   # a power of two: exact
+    B = W.normal_bf16((23, 9), seed=5)
+    assert np.array_equal(oracle.scale_rows(B, s), W.bf16_to_f32(B) * s[:, None])
+    # the factor belongs to the ROW (a transposed operand scales columns): row 1 only
+    one = np.zeros(23, np.float32)
+    one[1] = 2.0
+    got = oracle.scale_rows(X, one)
+    assert np.array_equal(got[1], 2 * X[1]) and not got[[0] + list(range(2, 23))].any()
+
+
+def test_scaled_sum_matches_dense_brute_force_and_its_special_cases():
+    for k, (N, src, dst) in enumerate(tiny_graphs()):
+        X = W.normal_f32((N, 6), seed=20 + k)
+        C = dense_count(N, src, dst)
+        rp, ci, _, _ = oracle.build_csr(N, src, dst)
+        s = W.normal_f32((N,), seed=30 + k)
+        got = oracle.aggregate(oracle.SUM_SCALED, rp, ci, s, X)
+        assert np.allclose(got, s.astype(np.float64)[:, None] * (C @ X.astype(np.float64)), rtol=1e-6, atol=1e-6)
+        plain = oracle.aggregate(oracle.SUM, rp, ci, None, X)
+        # factor 1: the plain sum, bit for bit; a power of two: the plain sum scaled exactly
+        assert np.array_equal(oracle.aggregate(oracle.SUM_SCALED, rp, ci, np.ones(N, np.float32), X), plain)
+        assert np.array_equal(oracle.aggregate(oracle.SUM_SCALED, rp, ci, np.full(N, -0.5, np.float32), X), -plain / 2)
+        # the factor is the DESTINATION's: only row 0's factor moves row 0
+        s2 = s.copy()
+        s2[0] += 1.0
+        got2 = oracle.aggregate(oracle.SUM_SCALED, rp, ci, s2, X)
+        assert np.array_equal(got2[1:], got[1:])
+        if rp[1] > rp[0] and np.abs(plain[0]).max() > 1e-3:
+            assert not np.array_equal(got2[0], got[0])
+        assert np.array_equal(oracle.aggregate_rows(oracle.SUM_SCALED, np.arange(N), rp, ci, s, X), got)
+
+
+@pytest.mark.parametrize("key", ["c1", "c2"])
+def test_factored_gcn_is_the_gcn_weighted_sum_up_to_the_rounding_of_the_weights(key):
+    # s_i * sum_j (s_j x_j) against sum_j fl(1/sqrt(d_i d_j)) x_j, the latter pinned above against scipy and the
+    # dense normalised adjacency.  Each term differs by at most three roundings to fp32 (s_i, s_j, s_j x_j) on one
+    # side and one (the edge weight) on the other: 4 * 2^-24 of the sum of the terms' magnitudes, plus half an ulp
+    # of each result.
+    N, src, dst = W.graph(key)
+    X = W.normal_f32((N, 19), seed=8)
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, flags=oracle.SELF_LOOPS | oracle.NORM_SYM, want_w=True)
+    s = oracle.gcn_factors(rp)
+    got = oracle.aggregate(oracle.SUM_SCALED, rp, ci, s, oracle.scale_rows(X, s))
+    ref = oracle.aggregate(oracle.WSUM, rp, ci, w, X)
+    mag = oracle.aggregate(oracle.WSUM, rp, ci, w, np.abs(X))
+    assert np.all(np.abs(got.astype(np.float64) - ref) <= 4 * 2.0 ** -24 * mag + 2.0 ** -23 * np.abs(ref))
+    assert np.abs(got - ref).max() > 0          # and they are two roundings of it, not one computation
+
+
 @pytest.mark.parametrize("key", ["c1", "c2"])
 def test_sum_matches_scipy_spmm(key):
     N, src, dst = W.graph(key)

@@ -59,6 +59,11 @@ WORKLOADS = {
     "c4-hid32-gcn": ("c4", "wsum", 32, "f32", True),
     "c4-hid8-gcn": ("c4", "wsum", 8, "f32", True),
     "c6-gcn": ("c6", "wsum", 602, "f32", True),      # the third graph shape at the dense graph's input width
+    # GCN with its weights in factored form: s_j into the rows of X (gnnagg_scale_rows, inside the timed step),
+    # a plain sum, s_i at the store (GNNAGG_SUM_SCALED); checked against the checker's per-edge weighted sum
+    "c4-gcn-factored": ("c4", "gcn-factored", 602, "f32", True),
+    "c6-gcn-factored": ("c6", "gcn-factored", 602, "f32", True),
+    "c4-hid32-gcn-factored": ("c4", "gcn-factored", 32, "f32", True),
     "c6-mean-256": ("c6", "mean", 256, "f32", False),
     "c4-mean-256": ("c4", "mean", 256, "f32", False),
     "c4-sum-bf16-512": ("c4", "sum", 512, "bf16", False),
@@ -106,12 +111,12 @@ def split_name(workload):
 DEFAULT_ALSO = (
     PROBES
     + ["c4-gcn@8", "c4-gcn@16", "c4-gcn@32", "c4-gcn@64", "c4-gcn@all",
-       "c4-gcn", "c4-mean#auto", "c4-mean", "c4-mean@8", "c4-mean@16", "c4-mean@32", "c4-mean@64", "c4-mean@all",
-       "c4-hid32-gcn", "c4-hid8-gcn", "c4-gat", "c4-combine-32", "c4-layer-32", "c4-layer-32-fused",
+       "c4-gcn", "c4-gcn-factored#auto", "c4-mean#auto", "c4-mean", "c4-mean@8", "c4-mean@16", "c4-mean@32", "c4-mean@64", "c4-mean@all",
+       "c4-hid32-gcn", "c4-hid32-gcn-factored", "c4-hid8-gcn", "c4-gat", "c4-combine-32", "c4-layer-32", "c4-layer-32-fused",
        "c4-layer2-32-41-fused",
        "c5-sum", "c5-max", "c5-sum-f32", "c5-sum-f16", "c5-sum-f32-ranked", "c5-sum-f16-ranked",
        "c5-layer-16", "c5-layer-16-ranked",
-       "c6-gcn#auto", "c6-gcn", "c6-hid32-gcn", "c6-hid16-gcn", "c6-hid8-gcn", "c6-hid32-mean", "c6-gat",
+       "c6-gcn#auto", "c6-gcn", "c6-gcn-factored#auto", "c6-hid32-gcn", "c6-hid16-gcn", "c6-hid8-gcn", "c6-hid32-mean", "c6-gat",
        "c2-mean", "c3-gat", "c1-gcn", "c1-gcn@16", "c1-gcn@64", "c1-gcn@all"])
 CPU_BASELINE_ALSO = {"c5-sum": 5.0, "c5-max": 5.0}     # multi-threaded checker on a bounded sample (seconds)
 SINGLE_THREAD_ALSO = {"c1-gcn", "c2-mean", "c3-gat"}    # whole graph on one thread
@@ -376,11 +381,15 @@ class Bench:
         else:
             d_X, out = d_X0, torch.empty((N, F), dtype=torch.float32, device="cuda")
         del d_X0
-        op = {"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname]
+        op = {"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX, "gcn-factored": g.SUM_SCALED}[opname]
+        factored = opname == "gcn-factored"
+        weights, gathered = c["w"], d_X
+        if factored:  # the factors once per graph; the scaled copy of X is made inside every timed step
+            weights = g.gnnagg_gcn_factors(c["rp"])
+            gathered = torch.empty_like(d_X) if not self.pitched else g.pitched_empty(N, F, torch.float32)
 
         if n_blocks < 0:
-            n_blocks = g.gnnagg_auto_source_blocks({"sum": g.SUM, "wsum": g.WSUM, "mean": g.MEAN, "max": g.MAX}[opname],
-                                                   N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)),
+            n_blocks = g.gnnagg_auto_source_blocks(op, N, F, g.BF16 if xdt == "bf16" else g.F32, int(d_X.stride(0)),
                                                    c["plan"])
             n_blocks = 0 if n_blocks <= 1 else n_blocks
         if n_blocks:  # per graph, like the CSR and the plan; the states in transit live in a workspace kept here
@@ -393,12 +402,18 @@ class Bench:
             ws = torch.empty(max(g.gnnagg_aggregate_blocked_workspace_bytes(N, F, blocks), 256), dtype=torch.uint8,
                              device="cuda")
 
-            def step():
-                g.gnnagg_aggregate_blocked(op, c["rp"], d_ci, c["w"], d_X, blocks, out, f_chunk, workspace=ws)
+            def aggregate():
+                g.gnnagg_aggregate_blocked(op, c["rp"], d_ci, weights, gathered, blocks, out, f_chunk, workspace=ws)
         else:
-            def step():
-                g.gnnagg_aggregate(op, c["rp"], d_ci, c["w"], d_X, out, f_chunk, c["plan"])
+            def aggregate():
+                g.gnnagg_aggregate(op, c["rp"], d_ci, weights, gathered, out, f_chunk, c["plan"])
 
+        def step():
+            if factored:
+                g.gnnagg_scale_rows(d_X, weights, gathered)
+            aggregate()
+
+        scale_ms = float(self.time_steps(lambda: g.gnnagg_scale_rows(d_X, weights, gathered))[0].mean()) if factored else None
         ms, ms_per_step = self.time_steps(step)
         nnz = c["nnz"]
         x_bytes = 2 if xdt == "bf16" else 4
@@ -413,6 +428,8 @@ class Bench:
         # priced at ONE pass over the edge list, whatever chunk width runs: the index and weight re-reads of
         # a chunked run are the method's overhead, not work to take credit for
         b_alg = algorithmic_bytes(nnz, N, F, x_bytes, opname == "wsum", 0)
+        if factored:  # the scaling pass reads and writes X once, and the aggregation reads the factors
+            b_alg += 2 * N * F * 4 + 2 * N * 4
         kern_ms = float(ms.mean())
         cfg = {"workload": workload, "graph": self.W.GRAPHS[gkey].name, "N": N, "nnz": nnz, "F": F, "op": opname,
                "f_chunk": f_chunk, "f_chunk_used": f_used, "x_dtype": xdt, "x_row_pitch": int(d_X.stride(0)),
@@ -427,6 +444,8 @@ class Bench:
                                                                                    opname == "wsum", f_eff),
                      "compulsory_bytes": N * F * x_bytes + N * F * 4 + nnz * (8 if opname == "wsum" else 4) + (N + 1) * 8})
         roof["compulsory_frac"] = roof["compulsory_bytes"] / (HBM_PEAK_GBS * 1e9) / (kern_ms * 1e-3)
+        if factored:
+            roof.update({"kernel": "scale_rows_kernel + aggregate_kernel", "scale_rows_ms": scale_ms})
         ef = float(nnz) * F
         log("%s: step %.3f ms wall, kernel mean %.3f ms (min %.3f), %.3e edge-features/s, %.0f GB/s algorithmic" %
             (workload, ms_per_step, kern_ms, ms.min(), ef / (ms_per_step * 1e-3), roof["achieved"]))
@@ -435,7 +454,8 @@ class Bench:
         # ---- CPU checker: parity on sampled rows; optionally its rate on a bounded sample / on one thread
         import oracle
         rp, ci, w = self.checker_csr(gkey, flags)
-        rop = {"sum": oracle.SUM, "wsum": oracle.WSUM, "mean": oracle.MEAN, "max": oracle.MAX}[opname]
+        rop = {"sum": oracle.SUM, "wsum": oracle.WSUM, "mean": oracle.MEAN, "max": oracle.MAX,
+               "gcn-factored": oracle.WSUM}[opname]  # factored: against the per-edge weights it stands in for
         rows = self.sample_rows(rp)
         cpu = None
         if cpu_seconds > 0:

@@ -20,7 +20,8 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    gnnagg_aggregate, gnnagg_aggregate_ws, gnnagg_aggregate_update,
  *    gnnagg_aggregate_noalloc, gnnagg_aggregate_blocked, gnnagg_gat_attention,
- *    gnnagg_combine and gnnagg_rank_sources only enqueue kernels on it and return (no allocation
+ *    gnnagg_combine, gnnagg_rank_sources, gnnagg_gcn_factors and gnnagg_scale_rows only enqueue kernels on
+ *    it and return (no allocation
  *    on the host or the device, no synchronisation, no memset: they can be
  *    captured in a HIP graph); gnnagg_build_csr, gnnagg_check_csr,
  *    gnnagg_plan_rows, gnnagg_plan_source_blocks, gnnagg_tune_f_chunk and
@@ -59,7 +60,12 @@ typedef enum {
   GNNAGG_SUM = 0,  /* out[i,f] = sum_j X[j,f] */
   GNNAGG_WSUM = 1, /* out[i,f] = sum_j edge_w[e] * X[j,f]   (GCN with the weights of NORM_SYM) */
   GNNAGG_MEAN = 2, /* out[i,f] = (sum_j X[j,f]) / deg(i), 0 for an empty row (GraphSAGE mean) */
-  GNNAGG_MAX = 3   /* out[i,f] = max_j X[j,f], +0.0 for an empty row; -0 orders below +0 */
+  GNNAGG_MAX = 3,  /* out[i,f] = max_j X[j,f], +0.0 for an empty row; -0 orders below +0 */
+  /* out[i,f] = row_scale[i] * sum_j X[j,f]: a weighted sum whose weights factor into a per-destination
+   * and a per-source part, w_ij = a_i b_j, with the sources' part already in X (gnnagg_scale_rows).  GCN's
+   * weights do (a = b = d^-1/2, gnnagg_gcn_factors), and the stream of per-edge weights then goes unread.
+   * row_scale ([N] fp32) is passed in the edge_w argument. */
+  GNNAGG_SUM_SCALED = 4
 } gnnagg_op;
 
 typedef enum { GNNAGG_F32 = 0, GNNAGG_BF16 = 1 } gnnagg_dtype;
@@ -133,7 +139,8 @@ GNNAGG_API int gnnagg_plan_rows(int64_t N, const int64_t* rowptr, int32_t* row_o
  *            exactly; sums accumulate in fp64)
  *   out      [N,F] row-major, out_dtype GNNAGG_F32, or GNNAGG_BF16 (the fp32 result rounded to
  *            nearest even: halves the write stream)
- *   edge_w   [nnz] fp32, required for GNNAGG_WSUM, ignored otherwise
+ *   edge_w   [nnz] fp32, required for GNNAGG_WSUM; for GNNAGG_SUM_SCALED the [N] fp32 factors of the
+ *            destinations, required; ignored otherwise
  *   f_chunk  chunk WIDTH (the width of one decomposition layer,
  *            Section III): chunk c covers columns [c*f_chunk, min(F,(c+1)*f_chunk)).
  *            Chunks run one after another over all rows (the chunk-outer,
@@ -408,6 +415,36 @@ GNNAGG_API int gnnagg_combine(int64_t N, const void* X, int x_dtype, int32_t F, 
  */
 GNNAGG_API int gnnagg_rank_sources(int64_t N, int64_t nnz, const int32_t* colidx, int32_t* rank,
                         int32_t* colidx_ranked, void* workspace, size_t* workspace_bytes, void* stream);
+
+/*
+ * GCN's aggregation weights in factored form (the GCN operator of Section III: the adjacency matrix with
+ * self-loops, normalised by the degrees on both sides): 1/sqrt(d_i d_j) = s_i s_j with
+ *
+ *     s[i] = (float)(1 / sqrt(d_i)),  d_i = rowptr[i+1] - rowptr[i];  0 for an empty row
+ *
+ *   s   [N] fp32 out.  Asynchronous on `stream`.
+ *
+ * out = GNNAGG_SUM_SCALED(rowptr, colidx, s, gnnagg_scale_rows(X, s)) is then the GCN aggregation of X
+ * without the [nnz] stream of edge weights; it differs from GNNAGG_WSUM with the weights of
+ * GNNAGG_NORM_SYM by how the weights are rounded (here s_j X[j,f] is rounded to fp32 once per source row,
+ * there 1/sqrt(d_i d_j) once per edge): a few units of 2^-24 relative to the sum of the terms' magnitudes.
+ */
+GNNAGG_API int gnnagg_gcn_factors(int64_t N, const int64_t* rowptr, float* s, void* stream);
+
+/*
+ * out[j,f] = scale[j] * X[j,f]: the per-source part of factored aggregation weights, applied to the
+ * feature rows once instead of to every edge (see GNNAGG_SUM_SCALED).  One fp32 product per element,
+ * correctly rounded (a bf16 input is widened first).
+ *
+ *   X      [N,F] GNNAGG_F32 or GNNAGG_BF16, row pitch x_pitch elements (>= F; 0 = F)
+ *   scale  [N] fp32
+ *   out    [N,F] fp32, row pitch out_pitch; may be X itself when X is fp32 and the pitches agree, must not
+ *          overlap it otherwise.  Columns [F, pitch) are neither read nor written.
+ *
+ * Asynchronous on `stream`.
+ */
+GNNAGG_API int gnnagg_scale_rows(int64_t N, int32_t F, const void* X, int x_dtype, int64_t x_pitch,
+                                 const float* scale, float* out, int64_t out_pitch, void* stream);
 
 /*
  * Measurement aid, not part of the method: overrides, for every later aggregation call of the process, how

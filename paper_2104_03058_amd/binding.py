@@ -14,7 +14,7 @@ from typing import Optional
 
 import torch
 
-SUM, WSUM, MEAN, MAX = 0, 1, 2, 3
+SUM, WSUM, MEAN, MAX, SUM_SCALED = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 SELF_LOOPS, NORM_SYM = 1, 2
 PLAN_CLASSES = 33
@@ -91,6 +91,10 @@ def load_library():
         lib.gnnagg_tune_f_chunk.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, vp, ci, i64, i32, vp, vp, vp, szp, vp,
                                             ctypes.POINTER(i32), ctypes.POINTER(f32)]
         lib.gnnagg_set_workgroup_cap.restype = ci
+        lib.gnnagg_gcn_factors.argtypes = [i64, vp, vp, vp]
+        lib.gnnagg_gcn_factors.restype = ci
+        lib.gnnagg_scale_rows.argtypes = [i64, i32, vp, ci, i64, vp, vp, i64, vp]
+        lib.gnnagg_scale_rows.restype = ci
         lib.gnnagg_set_workgroup_cap.argtypes = [ci]
         lib.gnnagg_mfma_f64_probe.restype = ci
         lib.gnnagg_mfma_f64_probe.argtypes = [vp, i64, i32, vp]
@@ -141,6 +145,16 @@ def _rows(t: torch.Tensor, name: str):
     if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1) or (t.shape[0] > 1 and t.stride(0) < t.shape[1]):
         raise ValueError("%s must be [N, F] with contiguous rows" % name)
     return ctypes.c_void_p(t.data_ptr())
+
+
+def _weights(op: int, edge_w: Optional[torch.Tensor], rowptr: torch.Tensor, colidx: torch.Tensor):
+    """The edge_w argument of an aggregation call: one weight per edge for WSUM, one factor per destination
+    for SUM_SCALED (the library cannot see the length of the array it is handed)."""
+    if edge_w is not None and op in (WSUM, SUM_SCALED):
+        need = int(colidx.numel()) if op == WSUM else int(rowptr.numel()) - 1
+        if edge_w.dim() != 1 or int(edge_w.numel()) < need:
+            raise ValueError("edge_w must hold %d values for this operator" % need)
+    return _dev(edge_w, torch.float32, "edge_w")
 
 
 def gnnagg_row_pitch(F: int, dtype: torch.dtype = torch.float32) -> int:
@@ -291,7 +305,7 @@ def gnnagg_aggregate(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w
             workspace = torch.empty(need, dtype=torch.uint8, device=X.device) if need > 0 else _token(X.device)
         have = ctypes.c_size_t(workspace.numel() * workspace.element_size())
         rc = lib.gnnagg_aggregate_ws(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
-                                     _dev(edge_w, torch.float32, "edge_w"), _rows(X, "X"), _x_dtype(X), x_pitch,
+                                     _weights(op, edge_w, rowptr, colidx), _rows(X, "X"), _x_dtype(X), x_pitch,
                                      _rows(out, "out"), F32 if out.dtype == torch.float32 else BF16, out_pitch, F,
                                      f_chunk, order, class_off, _dev(workspace), ctypes.byref(have), _stream(stream))
         _check("gnnagg_aggregate_ws", rc)
@@ -299,7 +313,7 @@ def gnnagg_aggregate(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edge_w
             workspace.record_stream(torch.cuda.current_stream() if stream is None else stream)
     else:
         rc = lib.gnnagg_aggregate(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
-                                  _dev(edge_w, torch.float32, "edge_w"), _dev(X, None, "X"), _x_dtype(X),
+                                  _weights(op, edge_w, rowptr, colidx), _dev(X, None, "X"), _x_dtype(X),
                                   _dev(out, None, "out"), F32 if out.dtype == torch.float32 else BF16, F, f_chunk,
                                   order, class_off, _stream(stream))
         _check("gnnagg_aggregate", rc)
@@ -339,7 +353,7 @@ def gnnagg_aggregate_update(op: int, rowptr: torch.Tensor, colidx: torch.Tensor,
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device) if need > 0 else _token(X.device)
     have = ctypes.c_size_t(workspace.numel() * workspace.element_size())
     rc = lib.gnnagg_aggregate_update(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
-                                     _dev(edge_w, torch.float32, "edge_w"), _rows(X, "X"), _x_dtype(X), x_pitch, F,
+                                     _weights(op, edge_w, rowptr, colidx), _rows(X, "X"), _x_dtype(X), x_pitch, F,
                                      f_chunk, _dev(W2, torch.float32, "W2"), H2, _dev(bias, torch.float32, "bias"),
                                      int(bool(relu)), _rows(out, "out"),
                                      F32 if out.dtype == torch.float32 else BF16, out_pitch, order, class_off,
@@ -366,7 +380,7 @@ def gnnagg_aggregate_noalloc(op: int, rowptr: torch.Tensor, colidx: torch.Tensor
     order, class_off = _plan_args(plan, N)
     x_pitch, out_pitch = int(X.stride(0)) if N > 1 else F, int(out.stride(0)) if N > 1 else F
     rc = lib.gnnagg_aggregate_noalloc(op, N, _dev(rowptr, torch.int64, "rowptr"),
-                                      _dev(colidx, torch.int32, "colidx"), _dev(edge_w, torch.float32, "edge_w"),
+                                      _dev(colidx, torch.int32, "colidx"), _weights(op, edge_w, rowptr, colidx),
                                       _rows(X, "X"), _x_dtype(X), x_pitch, _rows(out, "out"),
                                       F32 if out.dtype == torch.float32 else BF16, out_pitch, F, f_chunk, order,
                                       class_off, _stream(stream))
@@ -423,7 +437,7 @@ def gnnagg_aggregate_blocked(op: int, rowptr: torch.Tensor, colidx: torch.Tensor
     x_pitch, out_pitch = int(X.stride(0)) if N > 1 else F, int(out.stride(0)) if N > 1 else F
     args = lambda ws, have: lib.gnnagg_aggregate_blocked(  # noqa: E731
         op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
-        _dev(edge_w, torch.float32, "edge_w"), _rows(X, "X"), _x_dtype(X), x_pitch, _rows(out, "out"),
+        _weights(op, edge_w, rowptr, colidx), _rows(X, "X"), _x_dtype(X), x_pitch, _rows(out, "out"),
         F32 if out.dtype == torch.float32 else BF16, out_pitch, F, f_chunk, blocks.B,
         _dev(blocks.block_ptr, torch.int64, "block_ptr"), _dev(blocks.row_order, torch.int32, "row_order"),
         ctypes.cast(blocks.class_off, ctypes.c_void_p), ws, ctypes.byref(have), _stream(stream))
@@ -524,7 +538,7 @@ def gnnagg_tune_f_chunk(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edg
     have = ctypes.c_size_t(ws.numel())
     best, ms = ctypes.c_int32(0), ctypes.c_float(0.0)
     rc = lib.gnnagg_tune_f_chunk(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
-                                 _dev(edge_w, torch.float32, "edge_w"), _rows(X, "X"), _x_dtype(X),
+                                 _weights(op, edge_w, rowptr, colidx), _rows(X, "X"), _x_dtype(X),
                                  int(X.stride(0)) if N > 1 else F, _rows(out, "out"),
                                  F32 if out.dtype == torch.float32 else BF16, int(out.stride(0)) if N > 1 else F, F,
                                  order, class_off, _dev(ws), ctypes.byref(have), _stream(stream), ctypes.byref(best),
@@ -545,7 +559,7 @@ def gnnagg_tune_blocked(op: int, rowptr: torch.Tensor, colidx: torch.Tensor, edg
     have = ctypes.c_size_t(workspace.numel())
     best, ms = ctypes.c_int32(0), ctypes.c_float(0.0)
     rc = lib.gnnagg_tune_blocked(op, N, _dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
-                                 _dev(edge_w, torch.float32, "edge_w"), _rows(X, "X"), _x_dtype(X),
+                                 _weights(op, edge_w, rowptr, colidx), _rows(X, "X"), _x_dtype(X),
                                  int(X.stride(0)) if N > 1 else F, _rows(out, "out"),
                                  F32 if out.dtype == torch.float32 else BF16, int(out.stride(0)) if N > 1 else F, F,
                                  blocks.B, _dev(blocks.block_ptr, torch.int64, "block_ptr"),
@@ -618,6 +632,36 @@ def gnnagg_combine(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor
                                        _dev(out, torch.float32, "out"), _dev(out_rows, torch.int32, "out_rows"),
                                        _stream(stream))
     _check("gnnagg_combine", rc)
+    return out
+
+
+def gnnagg_gcn_factors(rowptr: torch.Tensor, stream=None) -> torch.Tensor:
+    """s[i] = 1/sqrt(deg(i)) as fp32 (0 for an empty row): GCN's edge weight 1/sqrt(d_i d_j) is s[i] * s[j]."""
+    N = int(rowptr.numel()) - 1
+    s = torch.empty(max(N, 1), dtype=torch.float32, device=rowptr.device)
+    _check("gnnagg_gcn_factors",
+           load_library().gnnagg_gcn_factors(N, _dev(rowptr, torch.int64, "rowptr"), _dev(s), _stream(stream)))
+    return s[:N]
+
+
+def gnnagg_scale_rows(X: torch.Tensor, scale: torch.Tensor, out: Optional[torch.Tensor] = None,
+                      stream=None) -> torch.Tensor:
+    """out[j, :] = scale[j] * X[j, :] in fp32 (X fp32 or bf16, rows may be a pitch apart).  out=None: a new matrix
+    with its rows on 128-byte lines; out=X (fp32) scales in place."""
+    if X.dim() != 2:
+        raise ValueError("X must be [N, F]")
+    N, F = int(X.shape[0]), int(X.shape[1])
+    if scale.dim() != 1 or int(scale.numel()) < N:
+        raise ValueError("scale must be [N]")
+    if out is None:
+        out = pitched_empty(N, F, torch.float32, X.device)
+    elif tuple(out.shape) != (N, F) or out.dtype != torch.float32:
+        raise ValueError("out must be fp32 [N, F]")
+    x_pitch = int(X.stride(0)) if N > 1 else F
+    out_pitch = int(out.stride(0)) if N > 1 else F
+    rc = load_library().gnnagg_scale_rows(N, F, _rows(X, "X"), _x_dtype(X), x_pitch, _dev(scale, torch.float32, "scale"),
+                                          _rows(out, "out"), out_pitch, _stream(stream))
+    _check("gnnagg_scale_rows", rc)
     return out
 
 

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgnnagg.so")
-SOURCES = ["api_misc.cpp", "radix_sort.hip", "csr_build.hip", "aggregate.hip", "gat.hip", "combine.hip", "probe.hip"]
+SOURCES = ["api_misc.cpp", "radix_sort.hip", "csr_build.hip", "aggregate.hip", "gat.hip", "combine.hip", "scale.hip", "probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -41,6 +41,7 @@ struct AggArgs {
   const int64_t* rowptr;
   const int32_t* colidx;
   const float* edge_w;
+  const float* row_scale;  // [N]: the finished sum of row r is multiplied by row_scale[r] (null: by 1)
   const void* X;
   void* out;
   int32_t out_bf16;  // 1: out holds bf16 (the fp32 result rounded to nearest even), 0: fp32
@@ -125,8 +126,9 @@ struct State {
 #pragma unroll
     for (int k = 0; k < VEC; ++k) acc[k] = slot[k];
   }
-  __device__ inline float result(int k, int64_t deg, bool mean) const {
-    return (float)((mean && deg > 0) ? acc[k] / (double)deg : acc[k]);
+  // the row's value: the mean divides by the degree, every other sum takes the row's factor (exact for 1)
+  __device__ inline float result(int k, int64_t deg, bool mean, double scale) const {
+    return (float)((mean && deg > 0) ? acc[k] / (double)deg : acc[k] * scale);
   }
   // partial result of one piece of a split row, one double per column
   __device__ inline void dump(double* p) const {
@@ -182,7 +184,9 @@ struct State<OPK_MAX, VEC> {
 #pragma unroll
     for (int k = 0; k < VEC; ++k) key[k] = p[k];
   }
-  __device__ inline float result(int k, int64_t deg, bool) const { return deg > 0 ? key_value(key[k]) : 0.0f; }
+  __device__ inline float result(int k, int64_t deg, bool, double) const {
+    return deg > 0 ? key_value(key[k]) : 0.0f;
+  }
   __device__ inline void dump(double* p) const {  // an int32 key is exact in a double
 #pragma unroll
     for (int k = 0; k < VEC; ++k) p[k] = (double)key[k];
@@ -297,9 +301,10 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(const AggArgs a) {
     st.hand_on(a.pout + r * a.p_pitch + col);
   } else if (role.writer) {
     if (a.e_begin) deg = a.rowptr[r + 1] - a.rowptr[r];  // source blocks: the row's whole degree finishes it
+    const double scale = a.row_scale ? (double)a.row_scale[r] : 1.0;
     float res[VEC];
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) res[k] = st.result(k, deg, a.mean != 0);
+    for (int k = 0; k < VEC; ++k) res[k] = st.result(k, deg, a.mean != 0, scale);
     if constexpr (FUSE) {
       // one slice, one chunk, columns [0, F): park the row for the dense layer below
       const int lrow = hub ? 0 : (wv << (6 - role.L)) + (lane >> role.L);
@@ -348,7 +353,8 @@ struct MergeArgs {
   int64_t F, out_pitch;
   int64_t rows;  // split rows in all runs together
   int32_t out_bf16, mean, nrun;
-  const float* bias;  // the Update step, as in AggArgs
+  const float* row_scale;  // as in AggArgs
+  const float* bias;       // the Update step, as in AggArgs
   const float* W2;
   int32_t H2, relu;
   const double* pin;  // source blocks, as in AggArgs (rowptr is the whole graph's: it gives the degree)
@@ -386,7 +392,8 @@ __global__ __launch_bounds__(kBlock) void split_merge_kernel(const MergeArgs a) 
     st.hand_on(a.pout + r * a.p_pitch + col);
     return;
   }
-  const float res = update_bias_act(st.result(0, deg, a.mean != 0), a.bias, col, a.relu);
+  const double scale = a.row_scale ? (double)a.row_scale[r] : 1.0;
+  const float res = update_bias_act(st.result(0, deg, a.mean != 0, scale), a.bias, col, a.relu);
   if (a.out_bf16) static_cast<uint16_t*>(a.out)[r * a.out_pitch + col] = (uint16_t)bf16_bits(res);
   else static_cast<float*>(a.out)[r * a.out_pitch + col] = res;
 }
@@ -409,6 +416,7 @@ __global__ __launch_bounds__(kBlock) void split_merge_fused_kernel(const MergeAr
   const int64_t deg = a.rowptr[r + 1] - a.rowptr[r];
   const int64_t pieces = (int64_t)1 << run.split_log2;
   const double* p = a.ws + ((int64_t)run.ws_begin + i * pieces) * a.F;
+  const double scale = a.row_scale ? (double)a.row_scale[r] : 1.0;
   double y = 0.0;
   for (int64_t f = 0; f < a.F; ++f) {
     State<OPK, 1> st;
@@ -419,7 +427,7 @@ __global__ __launch_bounds__(kBlock) void split_merge_fused_kernel(const MergeAr
       else o.acc[0] = p[q * a.F + f];
       st.merge(o);
     }
-    y = __builtin_fma((double)st.result(0, deg, a.mean != 0), (double)a.W2[f * a.H2 + h], y);
+    y = __builtin_fma((double)st.result(0, deg, a.mean != 0, scale), (double)a.W2[f * a.H2 + h], y);
   }
   if (a.bias) y += (double)a.bias[h];
   const float res = update_bias_act((float)y, nullptr, h, a.relu);
@@ -536,7 +544,7 @@ int check_aggregate_args(int op, int64_t N, const int64_t* rowptr, const int32_t
                          const void* X, int x_dtype, void* out, int out_dtype, int32_t F, int32_t f_chunk,
                          const int32_t* row_order, const int64_t* class_off, bool* nothing) {
   *nothing = false;
-  if (op < GNNAGG_SUM || op > GNNAGG_MAX) return GNNAGG_EINVAL;
+  if (op < GNNAGG_SUM || op > GNNAGG_SUM_SCALED) return GNNAGG_EINVAL;
   if (N < 0 || F <= 0 || f_chunk < GNNAGG_F_CHUNK_AUTO) return GNNAGG_EINVAL;
   if (x_dtype != GNNAGG_F32 && x_dtype != GNNAGG_BF16) return GNNAGG_EINVAL;
   if (out_dtype != GNNAGG_F32 && out_dtype != GNNAGG_BF16) return GNNAGG_EINVAL;
@@ -547,7 +555,7 @@ int check_aggregate_args(int op, int64_t N, const int64_t* rowptr, const int32_t
     return GNNAGG_OK;
   }
   if (!rowptr || !X || !out) return GNNAGG_ENULL;
-  if (op == GNNAGG_WSUM && !edge_w) return GNNAGG_ENULL;
+  if ((op == GNNAGG_WSUM || op == GNNAGG_SUM_SCALED) && !edge_w) return GNNAGG_ENULL;
   // colidx may only be NULL for a graph without edges, which the host cannot see; require it
   if (!colidx) return GNNAGG_ENULL;
   const size_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
@@ -595,6 +603,12 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
                 launches[0].g_log2 > 4))
     return GNNAGG_EUNSUPPORTED;  // cannot happen for F <= 64
   const int opk = (op == GNNAGG_WSUM) ? OPK_WSUM : (op == GNNAGG_MAX ? OPK_MAX : OPK_SUM);
+  // a sum with factors per destination: the edge_w argument holds N factors, and no edge has a weight
+  const float* row_scale = nullptr;
+  if (op == GNNAGG_SUM_SCALED) {
+    row_scale = edge_w;
+    edge_w = nullptr;
+  }
 
   // build and validate every launch before the first one is enqueued
   AggArgs args[kMaxLaunches];
@@ -604,6 +618,7 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
     a.rowptr = rowptr;
     a.colidx = colidx;
     a.edge_w = edge_w;
+    a.row_scale = row_scale;
     a.X = X;
     a.out = out;
     a.out_bf16 = (out_dtype == GNNAGG_BF16);
@@ -649,6 +664,7 @@ int aggregate_impl(int op, int64_t N, const int64_t* rowptr, const int32_t* coli
     m.out_pitch = out_pitch;
     m.out_bf16 = (out_dtype == GNNAGG_BF16);
     m.mean = (op == GNNAGG_MEAN);
+    m.row_scale = row_scale;
     m.bias = up.bias;
     m.W2 = up.W2;
     m.H2 = up.H2;
@@ -1043,7 +1059,7 @@ extern "C" int64_t gnnagg_row_pitch(int32_t F, int dtype) {
 
 extern "C" int32_t gnnagg_auto_source_blocks(int op, int64_t N, int32_t F, int x_dtype, int64_t x_pitch,
                                              const int64_t* class_off) {
-  if (op < GNNAGG_SUM || op > GNNAGG_MAX) return 0;
+  if (op < GNNAGG_SUM || op > GNNAGG_SUM_SCALED) return 0;
   if (N < 0 || F <= 0 || (x_dtype != GNNAGG_F32 && x_dtype != GNNAGG_BF16)) return 0;
   const int elem = x_dtype == GNNAGG_F32 ? 4 : 2;
   if (x_pitch == 0) x_pitch = F;

@@ -1,7 +1,7 @@
 // Status strings and version of libgnnagg.
 #include "gnnagg.h"
 
-extern "C" int gnnagg_version(void) { return 300; }  // major*10000 + minor*100 + patch
+extern "C" int gnnagg_version(void) { return 310; }  // major*10000 + minor*100 + patch
 
 extern "C" const char* gnnagg_strerror(int status) {
   switch (status) {

@@ -81,6 +81,24 @@ def test_config4_full_size_gcn_and_mean():
         out = g.gnnagg_aggregate(g.WSUM, d_rp, d_ci, d_w, d_X, None, fc, plan)
         close_all(host(out), ref, what="c4 wsum fc=%d" % fc)
         del out
+    # the same aggregation with the weights in factored form (s_j into the rows, a plain sum, s_i at the store),
+    # over as many source blocks as the library recommends for it: every row against the per-edge weighted sum
+    s = g.gnnagg_gcn_factors(d_rp)
+    assert_bits(host(s), oracle.gcn_factors(rp), "gcn factors")
+    Xs = g.gnnagg_scale_rows(Xp, s)
+    sample = sample_rows(rp)
+    assert_bits(host(Xs[torch.from_numpy(sample).cuda()]), oracle.scale_rows(X[sample], host(s)[sample]), "scaled rows")
+    Bf = g.gnnagg_auto_source_blocks(g.SUM_SCALED, N, 602, g.F32, int(Xs.stride(0)), plan)
+    assert Bf == 4
+    blocks_f = g.gnnagg_plan_source_blocks(d_rp, d_ci, Bf)
+    say("c4 full: factored weights over", Bf, "source blocks")
+    outp.fill_(float("nan"))
+    g.gnnagg_aggregate_blocked(g.SUM_SCALED, d_rp, d_ci, s, Xs, blocks_f, outp, g.F_CHUNK_AUTO)
+    close_all(host(outp), ref, what="c4 factored gcn blocked")
+    outp.fill_(float("nan"))
+    g.gnnagg_aggregate(g.SUM_SCALED, d_rp, d_ci, s, Xs, outp, g.F_CHUNK_AUTO, plan)
+    close_all(host(outp), ref, what="c4 factored gcn")
+    del Xs, blocks_f, s
     ref = oracle.aggregate(oracle.MEAN, rp, ci, None, X, threads=16)
     for fc in (8, 16, 32, 64, 0, g.F_CHUNK_AUTO):
         say("c4 full: mean, rows on lines, f_chunk", fc)

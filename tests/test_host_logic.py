@@ -268,6 +268,34 @@ def test_source_block_entry_points_validate_on_the_host(lib):
     assert tcall(N=0, X=None, out=None, bp=None, co=ctypes.cast(empty, ctypes.c_void_p)) == 0 and best.value == 8
 
 
+def test_factored_gcn_entry_points_validate_on_the_host(lib):
+    EINVAL, ENULL = -1, -2
+    one, other = ctypes.c_void_p(4096), other_ptr()
+    agg = lib.gnnagg_aggregate
+    assert agg(5, 4, one, one, one, one, 0, other, 0, 8, 0, None, None, None) == EINVAL    # one past the last operator
+    assert agg(4, 4, one, one, None, one, 0, other, 0, 8, 0, None, None, None) == ENULL    # the factors are required
+    assert lib.gnnagg_auto_source_blocks(5, 200000, 602, 0, 608, None) == 0
+    fac = lib.gnnagg_gcn_factors
+    assert fac(-1, one, other, None) == EINVAL
+    assert fac(4, None, other, None) == ENULL
+    assert fac(4, one, None, None) == ENULL
+    assert fac(4, ctypes.c_void_p(4100), other, None) == EINVAL     # rowptr on a 4-byte boundary
+    assert fac(0, None, None, None) == 0
+    sc = lib.gnnagg_scale_rows
+    assert sc(-1, 8, one, 0, 0, one, other, 0, None) == EINVAL      # N
+    assert sc(4, 0, one, 0, 0, one, other, 0, None) == EINVAL       # F
+    assert sc(4, 8, one, 2, 0, one, other, 0, None) == EINVAL       # x_dtype
+    assert sc(4, 8, one, 0, 7, one, other, 0, None) == EINVAL       # pitch below F
+    assert sc(4, 8, one, 0, 0, one, other, 4, None) == EINVAL
+    assert sc(4, 8, None, 0, 0, one, other, 0, None) == ENULL
+    assert sc(4, 8, one, 0, 0, None, other, 0, None) == ENULL
+    assert sc(4, 8, one, 0, 0, one, None, 0, None) == ENULL
+    assert sc(4, 8, ctypes.c_void_p(4098), 0, 0, one, other, 0, None) == EINVAL   # fp32 X on a 2-byte boundary
+    assert sc(4, 8, one, 1, 0, one, one, 0, None) == EINVAL         # in place needs fp32 rows ...
+    assert sc(4, 8, one, 0, 16, one, one, 8, None) == EINVAL        # ... at one pitch
+    assert sc(0, 8, None, 0, 0, None, None, 0, None) == 0
+
+
 def test_line_gather_probe_validates_on_the_host(lib):
     EINVAL, ENULL = -1, -2
     one, other = ctypes.c_void_p(4096), ctypes.c_void_p(8192)
@@ -495,7 +523,7 @@ def test_bench_module_is_importable_and_its_workloads_name_known_graphs():
     for name, (gkey, opname, F, xdt, gcn) in bench.WORKLOADS.items():
         assert gkey in W.GRAPHS, name
         assert opname in ("sum", "wsum", "mean", "max", "sum-ranked", "gat", "combine", "layer", "layer-ranked",
-                          "layer-fused", "agg-dense", "mean-srcblock"), name
+                          "layer-fused", "agg-dense", "mean-srcblock", "gcn-factored"), name
         assert xdt in ("f32", "bf16"), name
     for name in bench.DEFAULT_ALSO + list(bench.CPU_BASELINE_ALSO) + list(bench.SINGLE_THREAD_ALSO):
         assert bench.split_name(name)[0] in bench.WORKLOADS, name

@@ -77,6 +77,9 @@ WORKLOADS = {
     "c4-combine-32": ("c4", "combine", (602, 32), "f32", False),
     "c4-layer-32": ("c4", "layer", (602, 32), "f32", True),
     "c4-layer-32-fused": ("c4", "layer-fused", (602, 32), "f32", True),
+    # the same layer with GCN's weights in factored form: Combination writes s_j (X W)_j (gnnagg_combine_scaled),
+    # the aggregation is GNNAGG_SUM_SCALED with the Update step at its store; checked against per-edge weights
+    "c4-layer-32-factored": ("c4", "layer-factored", (602, 32), "f32", True),
     # second layer at the hidden width: aggregate 32 columns, then x W2 [32, 41] + bias in the same kernel
     "c4-layer2-32-41-fused": ("c4", "agg-dense", (32, 41), "f32", True),
     # the sparse graph at hidden width 16 after Combination: rows of 64 bytes, two per line; "-ranked" stores
@@ -113,7 +116,7 @@ DEFAULT_ALSO = (
     + ["c4-gcn@8", "c4-gcn@16", "c4-gcn@32", "c4-gcn@64", "c4-gcn@all",
        "c4-gcn", "c4-gcn-factored#auto", "c4-mean#auto", "c4-mean", "c4-mean@8", "c4-mean@16", "c4-mean@32", "c4-mean@64", "c4-mean@all",
        "c4-hid32-gcn", "c4-hid32-gcn-factored", "c4-hid8-gcn", "c4-gat", "c4-combine-32", "c4-layer-32", "c4-layer-32-fused",
-       "c4-layer2-32-41-fused",
+       "c4-layer-32-factored", "c4-layer2-32-41-fused",
        "c5-sum", "c5-max", "c5-sum-f32", "c5-sum-f16", "c5-sum-f32-ranked", "c5-sum-f16-ranked",
        "c5-layer-16", "c5-layer-16-ranked",
        "c6-gcn#auto", "c6-gcn", "c6-gcn-factored#auto", "c6-hid32-gcn", "c6-hid16-gcn", "c6-hid8-gcn", "c6-hid32-mean", "c6-gat",
@@ -576,6 +579,14 @@ class Bench:
                 g.gnnagg_combine(d_X, d_W, None, False, hid, out_rows=rank)
                 g.gnnagg_aggregate(aop, c["rp"], d_ci, c["w"], hid, out, 0, c["plan"])
             kernels, metric = "combine_kernel + aggregate_kernel", "one layer A (X W), Combination first"
+        elif opname == "layer-factored":
+            fac = g.gnnagg_gcn_factors(c["rp"])
+
+            def step():
+                g.gnnagg_combine(d_X, d_W, None, False, hid, row_scale=fac)
+                g.gnnagg_aggregate_update(g.SUM_SCALED, c["rp"], d_ci, fac, hid, None, d_b, True, out, 0, c["plan"])
+            kernels, metric = ("combine_kernel (rows scaled at its store) + aggregate_kernel (sum scaled, Update at its store)",
+                               "one layer relu(A (X W) + b), Combination first, GCN weights in factored form")
         elif opname == "layer-fused":
             def step():
                 g.gnnagg_combine(d_X, d_W, None, False, hid)
@@ -596,7 +607,7 @@ class Bench:
         else:
             b_alg = N * F * 4 + F * H * 4 + N * H * 4
             if aggregates:
-                b_alg += algorithmic_bytes(nnz, N, H, 4, gcn, 0)
+                b_alg += algorithmic_bytes(nnz, N, H, 4, gcn and opname != "layer-factored", 0)
             ef = float(nnz) * H
         achieved = b_alg / (kern_ms * 1e-3) / 1e9
         log("%s: %.3f ms per step, %.0f GB/s algorithmic" % (workload, kern_ms, achieved))
@@ -616,7 +627,7 @@ class Bench:
                 ref_hid = oracle.combine(X, Wt, threads=self.threads)
                 ref = oracle.aggregate_rows(oracle.WSUM if gcn else oracle.SUM, rows, rp, ci, w, ref_hid,
                                             threads=self.threads)
-                if opname == "layer-fused":
+                if opname in ("layer-fused", "layer-factored"):
                     ref = oracle.update(ref, bias, True)
             got = out[torch.from_numpy(rows).cuda()].cpu().numpy()
         rec = {"metric": metric,
@@ -703,7 +714,7 @@ class Bench:
         op = WORKLOADS[base][1]
         if op == "gat":
             return self.measure_gat(base, f_chunk if not width else f_chunk, single_thread)
-        if op in ("combine", "layer", "layer-ranked", "layer-fused", "agg-dense"):
+        if op in ("combine", "layer", "layer-ranked", "layer-fused", "layer-factored", "agg-dense"):
             return self.measure_layer(base)
         if op == "mean-srcblock":
             return self.measure_source_blocked(base, f_chunk)

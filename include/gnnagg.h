@@ -20,7 +20,7 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    gnnagg_aggregate, gnnagg_aggregate_ws, gnnagg_aggregate_update,
  *    gnnagg_aggregate_noalloc, gnnagg_aggregate_blocked, gnnagg_gat_attention,
- *    gnnagg_combine, gnnagg_rank_sources, gnnagg_gcn_factors and gnnagg_scale_rows only enqueue kernels on
+ *    gnnagg_combine, gnnagg_combine_scaled, gnnagg_rank_sources, gnnagg_gcn_factors and gnnagg_scale_rows only enqueue kernels on
  *    it and return (no allocation
  *    on the host or the device, no synchronisation, no memset: they can be
  *    captured in a HIP graph); gnnagg_build_csr, gnnagg_check_csr,
@@ -397,6 +397,20 @@ GNNAGG_API int gnnagg_gat_attention(int64_t N, const int64_t* rowptr, const int3
  */
 GNNAGG_API int gnnagg_combine(int64_t N, const void* X, int x_dtype, int32_t F, const float* W, const float* bias,
                               int32_t H, int relu, float* out, const int32_t* out_rows, void* stream);
+
+/*
+ * gnnagg_combine with the rows of the result scaled on their way out:
+ *
+ *     out[i, :] = row_scale[i] * act( X[i, :] W + bias )
+ *
+ * the product formed in fp32 on the rounded result, so that the call equals gnnagg_combine followed by
+ * gnnagg_scale_rows bit for bit.  With row_scale = the factors of gnnagg_gcn_factors this is the input of a
+ * GCN aggregation in factored form (GNNAGG_SUM_SCALED; Section III: Combination ahead of Aggregation)
+ * without a scaling pass of its own.  row_scale [N] fp32, required; everything else as in gnnagg_combine.
+ */
+GNNAGG_API int gnnagg_combine_scaled(int64_t N, const void* X, int x_dtype, int32_t F, const float* W,
+                                     const float* bias, int32_t H, int relu, const float* row_scale, float* out,
+                                     const int32_t* out_rows, void* stream);
 
 /*
  * Popularity order of the source vertices, for feature rows narrower than a 128-byte line

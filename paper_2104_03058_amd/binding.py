@@ -91,6 +91,8 @@ def load_library():
         lib.gnnagg_tune_f_chunk.argtypes = [ci, i64, vp, vp, vp, vp, ci, i64, vp, ci, i64, i32, vp, vp, vp, szp, vp,
                                             ctypes.POINTER(i32), ctypes.POINTER(f32)]
         lib.gnnagg_set_workgroup_cap.restype = ci
+        lib.gnnagg_combine_scaled.argtypes = [i64, vp, ci, i32, vp, vp, i32, ci, vp, vp, vp, vp]
+        lib.gnnagg_combine_scaled.restype = ci
         lib.gnnagg_gcn_factors.argtypes = [i64, vp, vp, vp]
         lib.gnnagg_gcn_factors.restype = ci
         lib.gnnagg_scale_rows.argtypes = [i64, i32, vp, ci, i64, vp, vp, i64, vp]
@@ -613,9 +615,10 @@ def gnnagg_auto_source_blocks(op: int, N: int, F: int, x_dtype: int = F32, x_pit
 
 def gnnagg_combine(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor] = None, relu: bool = False,
                    out: Optional[torch.Tensor] = None, stream=None,
-                   out_rows: Optional[torch.Tensor] = None) -> torch.Tensor:
+                   out_rows: Optional[torch.Tensor] = None, row_scale: Optional[torch.Tensor] = None) -> torch.Tensor:
     """out[N,H] fp32 = act(X[N,F] @ W[F,H] + bias); X fp32 or bf16, W and bias fp32.  With out_rows (int32 [N], a
-    permutation) row i of the result is stored as row out_rows[i]."""
+    permutation) row i of the result is stored as row out_rows[i]; with row_scale (fp32 [N]) it is multiplied by
+    row_scale[i] on its way out (gnnagg_combine_scaled)."""
     if X.dim() != 2 or W.dim() != 2 or W.shape[0] != X.shape[1]:
         raise ValueError("X must be [N,F] and W [F,H]")
     N, F, H = int(X.shape[0]), int(X.shape[1]), int(W.shape[1])
@@ -627,6 +630,16 @@ def gnnagg_combine(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor
         out = torch.empty((N, H), dtype=torch.float32, device=X.device)
     elif tuple(out.shape) != (N, H):
         raise ValueError("out must be [N, H]")
+    if row_scale is not None:
+        if row_scale.dim() != 1 or int(row_scale.numel()) < N:
+            raise ValueError("row_scale must be [N]")
+        rc = load_library().gnnagg_combine_scaled(N, _dev(X, None, "X"), _x_dtype(X), F, _dev(W, torch.float32, "W"),
+                                                  _dev(bias, torch.float32, "bias"), H, int(bool(relu)),
+                                                  _dev(row_scale, torch.float32, "row_scale"),
+                                                  _dev(out, torch.float32, "out"),
+                                                  _dev(out_rows, torch.int32, "out_rows"), _stream(stream))
+        _check("gnnagg_combine_scaled", rc)
+        return out
     rc = load_library().gnnagg_combine(N, _dev(X, None, "X"), _x_dtype(X), F, _dev(W, torch.float32, "W"),
                                        _dev(bias, torch.float32, "bias"), H, int(bool(relu)),
                                        _dev(out, torch.float32, "out"), _dev(out_rows, torch.int32, "out_rows"),

@@ -39,6 +39,7 @@ struct CombineArgs {
   const float* bias;
   float* out;
   const int32_t* out_rows;  // row i of the result goes to row out_rows[i] of out (null: i)
+  const float* row_scale;   // row i of the result is multiplied by row_scale[i] after the activation (null: no)
   int64_t N;
   int32_t F, H;
   int32_t col0;       // first output column of this pass
@@ -171,6 +172,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) 
         if (row >= a.N) continue;
         float y = (float)(acc[r][c][v] + b);
         if (a.relu) y = y > 0.0f ? y : 0.0f;
+        if (a.row_scale) y *= a.row_scale[row];  // one fp32 product on the rounded result, as gnnagg_scale_rows
         const int64_t orow = a.out_rows ? (int64_t)a.out_rows[row] : row;
         a.out[orow * a.H + col] = y;
       }
@@ -195,15 +197,17 @@ int launch_combine(const CombineArgs& a, hipStream_t stream) {
 
 using namespace gnnagg;
 
-extern "C" int gnnagg_combine(int64_t N, const void* X, int x_dtype, int32_t F, const float* W, const float* bias,
-                              int32_t H, int relu, float* out, const int32_t* out_rows, void* stream_) {
+namespace {
+
+int combine_impl(int64_t N, const void* X, int x_dtype, int32_t F, const float* W, const float* bias, int32_t H,
+                 int relu, const float* row_scale, float* out, const int32_t* out_rows, void* stream_) {
   if (N < 0 || F <= 0 || H <= 0 || (relu != 0 && relu != 1)) return GNNAGG_EINVAL;
   if (x_dtype != GNNAGG_F32 && x_dtype != GNNAGG_BF16) return GNNAGG_EINVAL;
   if (N == 0) return GNNAGG_OK;
   if (!X || !W || !out) return GNNAGG_ENULL;
   const size_t xs = (x_dtype == GNNAGG_F32) ? 4 : 2;
   if (((uintptr_t)X % xs) || ((uintptr_t)W % 4) || ((uintptr_t)out % 4) || (bias && ((uintptr_t)bias % 4)) ||
-      (out_rows && ((uintptr_t)out_rows % 4)))
+      (out_rows && ((uintptr_t)out_rows % 4)) || (row_scale && ((uintptr_t)row_scale % 4)))
     return GNNAGG_EINVAL;
   if (X == (const void*)out) return GNNAGG_EINVAL;
   if (ceil_div(N, kRowsPerBlock) > 0x7fffffffll) return GNNAGG_EUNSUPPORTED;
@@ -216,6 +220,7 @@ extern "C" int gnnagg_combine(int64_t N, const void* X, int x_dtype, int32_t F, 
     a.bias = bias;
     a.out = out;
     a.out_rows = out_rows;
+    a.row_scale = row_scale;
     a.N = N;
     a.F = F;
     a.H = H;
@@ -227,4 +232,18 @@ extern "C" int gnnagg_combine(int64_t N, const void* X, int x_dtype, int32_t F, 
     if (rc != GNNAGG_OK) return rc;
   }
   return GNNAGG_OK;
+}
+
+}  // namespace
+
+extern "C" int gnnagg_combine(int64_t N, const void* X, int x_dtype, int32_t F, const float* W, const float* bias,
+                              int32_t H, int relu, float* out, const int32_t* out_rows, void* stream) {
+  return combine_impl(N, X, x_dtype, F, W, bias, H, relu, nullptr, out, out_rows, stream);
+}
+
+extern "C" int gnnagg_combine_scaled(int64_t N, const void* X, int x_dtype, int32_t F, const float* W,
+                                     const float* bias, int32_t H, int relu, const float* row_scale, float* out,
+                                     const int32_t* out_rows, void* stream) {
+  if (N > 0 && !row_scale) return GNNAGG_ENULL;
+  return combine_impl(N, X, x_dtype, F, W, bias, H, relu, row_scale, out, out_rows, stream);
 }

@@ -207,3 +207,44 @@ def test_factored_gcn_meets_the_bar_of_the_weighted_sum_it_replaces(key, scale, 
     blocks = g.gnnagg_plan_source_blocks(d_rp, d_ci, 4)
     outb = g.gnnagg_aggregate_blocked(g.SUM_SCALED, d_rp, d_ci, s, Xs, blocks, None, g.F_CHUNK_AUTO)
     assert_close(host(outb), ref, "factored, 4 source blocks")
+
+
+@pytest.mark.parametrize("F,H,bf16", [(96, 16, False), (602, 32, False), (100, 41, True), (7, 130, False)])
+def test_combination_with_scaled_rows_equals_combination_then_scaling(F, H, bf16):
+    N = 1500
+    X = W.normal_bf16((N, F), seed=F) if bf16 else W.normal_f32((N, F), seed=F)
+    Wt = W.normal_f32((F, H), seed=F + 1, std=0.1)
+    b = W.normal_f32((H,), seed=F + 2)
+    s = W.normal_f32((N,), seed=F + 3)
+    d_X, d_W, d_b, d_s = dev(X), dev(Wt), dev(b), dev(s)
+    say("  combine_scaled F", F, "H", H)
+    for bias, relu in ((None, False), (d_b, True)):
+        fused = g.gnnagg_combine(d_X, d_W, bias, relu, row_scale=d_s)
+        plain = g.gnnagg_combine(d_X, d_W, bias, relu)
+        assert_bits(host(fused), host(g.gnnagg_scale_rows(plain, d_s, torch.empty_like(plain))), "fused vs two calls")
+        ref = oracle.scale_rows(oracle.combine(X, Wt, b if bias is not None else None, relu, threads=8), s)
+        assert_close(host(fused), ref, "vs checker")
+    # with the rows also stored in another order
+    perm = torch.randperm(N, device="cuda", generator=torch.Generator(device="cuda").manual_seed(1)).to(torch.int32)
+    moved = g.gnnagg_combine(d_X, d_W, d_b, True, out_rows=perm, row_scale=d_s)
+    straight = g.gnnagg_combine(d_X, d_W, d_b, True, row_scale=d_s)
+    assert_bits(host(moved[perm.long()]), host(straight), "out_rows + row_scale")
+
+
+def test_gcn_layer_in_factored_form_against_the_checkers_layer_with_per_edge_weights():
+    """relu(A_hat (X W) + b): Combination writes s_j (X W)_j, the aggregation sums, scales by s_i and applies
+    the Update step at its store - against the checker's combine, per-edge weighted sum and update."""
+    N, src, dst = W.graph("c2")
+    F, H = 500, 16
+    flags = oracle.SELF_LOOPS | oracle.NORM_SYM
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, flags, want_w=True, threads=8)
+    X = W.normal_f32((N, F), seed=3)
+    Wt = W.normal_f32((F, H), seed=4, std=0.05)
+    b = W.normal_f32((H,), seed=5, std=0.1)
+    ref = oracle.update(oracle.aggregate(oracle.WSUM, rp, ci, w, oracle.combine(X, Wt, threads=8), threads=8), b, True)
+    d_rp, d_ci, _, _ = g.gnnagg_build_csr(N, dev(src), dev(dst), flags)
+    plan = g.gnnagg_plan_rows(d_rp)
+    s = g.gnnagg_gcn_factors(d_rp)
+    hid = g.gnnagg_combine(dev(X), dev(Wt), None, False, row_scale=s)
+    out = g.gnnagg_aggregate_update(g.SUM_SCALED, d_rp, d_ci, s, hid, None, dev(b), True, None, 0, plan)
+    assert_close(host(out), ref, "factored layer")

@@ -294,6 +294,12 @@ def test_factored_gcn_entry_points_validate_on_the_host(lib):
     assert sc(4, 8, one, 1, 0, one, one, 0, None) == EINVAL         # in place needs fp32 rows ...
     assert sc(4, 8, one, 0, 16, one, one, 8, None) == EINVAL        # ... at one pitch
     assert sc(0, 8, None, 0, 0, None, None, 0, None) == 0
+    cs = lib.gnnagg_combine_scaled
+    assert cs(4, one, 0, 8, one, None, 4, 0, None, other, None, None) == ENULL              # the factors are required
+    assert cs(4, one, 0, 8, one, None, 4, 0, ctypes.c_void_p(4098), other, None, None) == EINVAL
+    assert cs(4, one, 0, 0, one, None, 4, 0, one, other, None, None) == EINVAL              # F, as in gnnagg_combine
+    assert cs(4, one, 0, 8, one, None, 4, 0, one, one, None, None) == EINVAL                # out aliases X
+    assert cs(0, None, 0, 8, None, None, 4, 0, None, None, None, None) == 0
 
 
 def test_line_gather_probe_validates_on_the_host(lib):
@@ -523,7 +529,7 @@ def test_bench_module_is_importable_and_its_workloads_name_known_graphs():
     for name, (gkey, opname, F, xdt, gcn) in bench.WORKLOADS.items():
         assert gkey in W.GRAPHS, name
         assert opname in ("sum", "wsum", "mean", "max", "sum-ranked", "gat", "combine", "layer", "layer-ranked",
-                          "layer-fused", "agg-dense", "mean-srcblock", "gcn-factored"), name
+                          "layer-fused", "agg-dense", "mean-srcblock", "gcn-factored", "layer-factored"), name
         assert xdt in ("f32", "bf16"), name
     for name in bench.DEFAULT_ALSO + list(bench.CPU_BASELINE_ALSO) + list(bench.SINGLE_THREAD_ALSO):
         assert bench.split_name(name)[0] in bench.WORKLOADS, name

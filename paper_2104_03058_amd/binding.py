@@ -648,13 +648,17 @@ def gnnagg_combine(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor
     return out
 
 
-def gnnagg_gcn_factors(rowptr: torch.Tensor, stream=None) -> torch.Tensor:
+def gnnagg_gcn_factors(rowptr: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """s[i] = 1/sqrt(deg(i)) as fp32 (0 for an empty row): GCN's edge weight 1/sqrt(d_i d_j) is s[i] * s[j]."""
     N = int(rowptr.numel()) - 1
-    s = torch.empty(max(N, 1), dtype=torch.float32, device=rowptr.device)
+    if out is None:
+        out = torch.empty(max(N, 1), dtype=torch.float32, device=rowptr.device)[:N]
+    elif out.dim() != 1 or int(out.numel()) != N:
+        raise ValueError("out must be [N]")
     _check("gnnagg_gcn_factors",
-           load_library().gnnagg_gcn_factors(N, _dev(rowptr, torch.int64, "rowptr"), _dev(s), _stream(stream)))
-    return s[:N]
+           load_library().gnnagg_gcn_factors(N, _dev(rowptr, torch.int64, "rowptr"), _dev(out, torch.float32, "out"),
+                                             _stream(stream)))
+    return out
 
 
 def gnnagg_scale_rows(X: torch.Tensor, scale: torch.Tensor, out: Optional[torch.Tensor] = None,

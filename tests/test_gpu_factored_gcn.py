@@ -248,3 +248,45 @@ def test_gcn_layer_in_factored_form_against_the_checkers_layer_with_per_edge_wei
     hid = g.gnnagg_combine(dev(X), dev(Wt), None, False, row_scale=s)
     out = g.gnnagg_aggregate_update(g.SUM_SCALED, d_rp, d_ci, s, hid, None, dev(b), True, None, 0, plan)
     assert_close(host(out), ref, "factored layer")
+
+
+def test_factored_path_can_be_captured_in_a_graph_and_replayed():
+    """Factors, row scaling and the scaled sum over source blocks only enqueue kernels: captured once, every
+    replay - fresh inputs copied in place, eager work in between - gives the bits of the eager calls."""
+    N, src, dst = W.graph("c4", 0.01)
+    flags = oracle.SELF_LOOPS | oracle.NORM_SYM
+    rp, ci, w, _ = oracle.build_csr(N, src, dst, flags, want_w=True)
+    d_rp, d_ci = dev(rp), dev(ci)
+    blocks = g.gnnagg_plan_source_blocks(d_rp, d_ci, 3)
+    F = 160
+    X = torch.zeros((N, F), dtype=torch.float32, device="cuda")
+    Xs = torch.empty((N, F), dtype=torch.float32, device="cuda")
+    s = torch.empty(N, dtype=torch.float32, device="cuda")
+    out = torch.empty((N, F), dtype=torch.float32, device="cuda")
+    ws = torch.empty(g.gnnagg_aggregate_blocked_workspace_bytes(N, F, blocks), dtype=torch.uint8, device="cuda")
+
+    def call():
+        g.gnnagg_gcn_factors(d_rp, s)
+        g.gnnagg_scale_rows(X, s, Xs)
+        g.gnnagg_aggregate_blocked(g.SUM_SCALED, d_rp, d_ci, s, Xs, blocks, out, 32, workspace=ws)
+
+    call()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for k in range(3):
+        Xh = W.normal_f32((N, F), seed=880 + k)
+        X.copy_(dev(Xh))
+        s.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.clone()
+        out.zero_()
+        Xs.zero_()
+        s.zero_()
+        ws.fill_(0x7F)
+        call()
+        torch.cuda.synchronize()
+        assert torch.equal(got, out), "replay %d differs from the eager calls" % k
+        assert_close(host(out), oracle.aggregate(oracle.WSUM, rp, ci, w, Xh, threads=8), "captured factored path %d" % k)

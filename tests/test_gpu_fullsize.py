@@ -213,6 +213,12 @@ def test_dense_small_graph_at_input_width_over_source_blocks():
     out.fill_(float("nan"))
     g.gnnagg_aggregate_blocked(g.WSUM, d_rp, d_ci, d_w, Xp, blocks, out, g.F_CHUNK_AUTO)
     close_all(host(out), ref, what="c6 wsum F=602 blocked")
+    say("c6 F=602: weights in factored form, in place, over the same blocks")
+    fac = g.gnnagg_gcn_factors(d_rp)
+    g.gnnagg_scale_rows(Xp, fac, Xp)
+    out.fill_(float("nan"))
+    g.gnnagg_aggregate_blocked(g.SUM_SCALED, d_rp, d_ci, fac, Xp, blocks, out, g.F_CHUNK_AUTO)
+    close_all(host(out), ref, what="c6 factored gcn F=602 blocked")
 
 
 def test_config4_graph_attention_full_size():

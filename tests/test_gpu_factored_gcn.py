@@ -290,3 +290,31 @@ def test_factored_path_can_be_captured_in_a_graph_and_replayed():
         torch.cuda.synchronize()
         assert torch.equal(got, out), "replay %d differs from the eager calls" % k
         assert_close(host(out), oracle.aggregate(oracle.WSUM, rp, ci, w, Xh, threads=8), "captured factored path %d" % k)
+
+
+def test_seeded_sweep_of_small_random_cases_for_the_scaled_sum():
+    """Thirty small cases with shapes drawn from a seeded generator: graph size (one vertex and edgeless graphs
+    among them), a planted hub, feature width, chunk width, input type, with and without a row plan."""
+    rng = np.random.default_rng(31337)
+    for case in range(30):
+        N = int(rng.integers(1, 400))
+        E = int(rng.integers(0, 12 * N + 1))
+        src, dst = (W.random_digraph(N, E, 6000 + case) if E else (np.zeros(0, np.int32), np.zeros(0, np.int32)))
+        if N > 8 and case % 3 == 0:
+            hub_src = rng.integers(0, N, size=int(rng.integers(300, 3000))).astype(np.int32)
+            src = np.concatenate([src, hub_src])
+            dst = np.concatenate([dst, np.full(len(hub_src), int(rng.integers(0, N)), np.int32)])
+        F = int(rng.choice([1, 2, 3, 5, 8, 12, 17, 31, 32, 33, 64, 100, 129, 260, 513]))
+        fc = int(rng.choice([0, 0, 1, 3, 4, 8, 16, 50, g.F_CHUNK_AUTO]))
+        bf16 = bool(rng.integers(0, 2))
+        rp, ci, _, _ = oracle.build_csr(N, src, dst, int(rng.choice([0, oracle.SELF_LOOPS])))
+        X = W.normal_bf16((N, F), seed=6100 + case) if bf16 else W.normal_f32((N, F), seed=6100 + case)
+        s = W.normal_f32((N,), seed=6200 + case)
+        say("  scaled-sum sweep case", case, "N", N, "nnz", len(ci), "F", F, "fc", fc, "bf16", bf16)
+        ref = oracle.aggregate(oracle.SUM_SCALED, rp, ci, s, X)
+        d_rp = dev(rp)
+        plan = g.gnnagg_plan_rows(d_rp) if case & 1 else None
+        d_ci = dev(ci) if len(ci) else torch.zeros(1, dtype=torch.int32, device="cuda")
+        out = torch.full((N, F), float("nan"), dtype=torch.float32, device="cuda")
+        g.gnnagg_aggregate(g.SUM_SCALED, d_rp, d_ci, dev(s), dev(X), out, fc, plan)
+        assert_close(host(out), ref, "sweep %d" % case, 1e-2 if bf16 else 1e-5)
